@@ -1,0 +1,98 @@
+"""Pins for the oracle's attention step (Eq. 3-1, 3-2, 3-7): closed forms, a library
+special case and a scalar-loop evaluation."""
+import numpy as np
+import torch
+
+from oracle import tokencarve_oracle as orc
+from tests.helpers_cpu import softmax_attention_loops
+
+
+def _rand(rng, H, L, dh):
+    return (rng.standard_normal((H, L, dh)) for _ in range(3))
+
+
+def test_uniform_attention_closed_form_causal(rng):
+    # Q = 0 makes every allowed key equally likely: Z_q is the running mean of V and
+    # S(x) = (1/N) sum_{q >= x} 1/(L_s+q+1).
+    H, L, dh, Ls, N = 3, 21, 8, 4, 12
+    _, K, V = _rand(rng, H, L, dh)
+    Z, S = orc.attn_output(np.zeros((H, L, dh)), K, V, Ls, N, causal=True)
+    for q in range(N):
+        expect = np.concatenate([V[h, :Ls + q + 1].mean(axis=0) for h in range(H)])
+        np.testing.assert_allclose(Z[q], expect, rtol=1e-13, atol=1e-13)
+    S_expect = np.array([sum(1.0 / (Ls + q + 1) for q in range(x, N)) / N for x in range(N)])
+    np.testing.assert_allclose(S, S_expect, rtol=1e-13)
+
+
+def test_uniform_attention_closed_form_full(rng):
+    H, L, dh, Ls, N = 2, 17, 4, 3, 9
+    _, K, V = _rand(rng, H, L, dh)
+    Z, S = orc.attn_output(np.zeros((H, L, dh)), K, V, Ls, N, causal=False)
+    expect = np.concatenate([V[h].mean(axis=0) for h in range(H)])
+    np.testing.assert_allclose(Z, np.tile(expect, (N, 1)), rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(S, np.full(N, 1.0 / L), rtol=1e-13)
+
+
+def test_one_hot_attention_picks_one_value_row(rng):
+    # a huge logit on key `tgt` makes the softmax one-hot: Z_q = V[tgt]; S counts the hits.
+    H, L, dh, Ls, N = 2, 16, 8, 2, 10
+    Q, K, V = _rand(rng, H, L, dh)
+    tgt = Ls + 1                                  # visible to every visual query q >= 1
+    K = np.zeros_like(K)
+    K[:, tgt, 0] = 1.0
+    Q = np.zeros_like(Q)
+    Q[:, :, 0] = 1e4
+    Z, S = orc.attn_output(Q, K, V, Ls, N, causal=True)
+    for q in range(1, N):
+        np.testing.assert_allclose(Z[q], np.concatenate([V[h, tgt] for h in range(H)]), rtol=1e-12)
+    assert abs(S[1] - (N - 1) / N) < 1e-12       # queries 1..N-1 put all mass on visual token 1
+    assert np.all(S[2:] < 1e-12)
+
+
+def test_rows_of_softmax_sum_to_one_via_constant_values(rng):
+    H, L, dh, Ls, N = 2, 20, 4, 5, 11
+    Q, K, _ = _rand(rng, H, L, dh)
+    Z, _ = orc.attn_output(Q, K, np.ones((H, L, dh)), Ls, N, causal=True)
+    np.testing.assert_allclose(Z, 1.0, rtol=1e-13)
+
+
+def test_matches_torch_sdpa_float64(rng):
+    # the library's scaled-dot-product attention is the textbook special case of Eq. 3-1/3-2
+    H, L, dh, Ls, N = 4, 40, 16, 6, 25
+    Q, K, V = _rand(rng, H, L, dh)
+    for causal in (True, False):
+        Z, _ = orc.attn_output(Q, K, V, Ls, N, causal=causal)
+        tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(a)) for a in (Q, K, V))
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal)
+        ref = ref[:, Ls:Ls + N].permute(1, 0, 2).reshape(N, H * dh).numpy()
+        np.testing.assert_allclose(Z, ref, rtol=1e-11, atol=1e-12)
+
+
+def test_matches_scalar_loops_including_attention_score(rng):
+    H, L, dh, Ls, N = 2, 13, 4, 3, 7
+    Q, K, V = _rand(rng, H, L, dh)
+    for causal in (True, False):
+        Z, S = orc.attn_output(Q, K, V, Ls, N, causal=causal, scale=0.37)
+        Zl, Sl = softmax_attention_loops(Q, K, V, Ls, N, causal, 0.37)
+        np.testing.assert_allclose(Z, Zl, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(S, Sl, rtol=1e-12)
+
+
+def test_attention_score_mass_balance(rng):
+    # full (non-causal) softmax: the visual columns of each row hold 1 - (mass on text keys);
+    # with no text tokens at all the scores sum to exactly 1.
+    H, L, dh = 3, 12, 4
+    Q, K, V = _rand(rng, H, L, dh)
+    _, S = orc.attn_output(Q, K, V, 0, L, causal=False)
+    assert abs(S.sum() - 1.0) < 1e-13
+    _, S = orc.attn_output(Q, K, V, 0, L, causal=True)
+    assert abs(S.sum() - 1.0) < 1e-13
+
+
+def test_storage_rounding_matches_torch():
+    x = np.random.default_rng(1).standard_normal(20000) * np.logspace(-20, 20, 20000)
+    x = np.concatenate([x, [0.0, 1.0, 1.00390625, 1.001953125, 1.005859375, -3.0e38]])
+    mine = orc.to_storage(x, "bf16")
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(mine, ref)
+    np.testing.assert_array_equal(orc.to_storage(x, "f32"), x.astype(np.float32).astype(np.float64))
