@@ -1,0 +1,153 @@
+/*
+ * tokencarve.h -- C ABI of the MI355X (gfx950) TokenCarve compression library.
+ *
+ * TokenCarve (arXiv 2503.10501) compresses the visual tokens of a multimodal LLM
+ * between LLM layers 2 and 3 during prefill (Section 3.3): it scores every visual
+ * token by its contribution to the singular spectrum of the layer-2 attention
+ * output (Eq. 3-6) mixed with its attention score (Eq. 3-7, 3-8), prunes to the
+ * best L_vc(1+rho) tokens (Stage I), then merges the L_vc*rho lower-scored
+ * survivors that are most similar to a higher-scored one into it (Stage II,
+ * Eq. 3-9, 3-10), leaving L_vc tokens.
+ *
+ * Conventions for every entry point
+ *   - `p` is a HOST pointer.  Every other pointer is a DEVICE pointer owned by the
+ *     caller, contiguous row-major, 16-byte aligned.  The library allocates
+ *     nothing, frees nothing and keeps no pointer after the call returns.
+ *   - All scratch memory comes from `ws` (`ws_bytes` >= tc_workspace_bytes(p)).
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without waiting for it.  Two calls may
+ *     overlap only if they use different workspaces.
+ *   - The return value is a tc_status.  Argument errors are detected on the host
+ *     before anything is launched: a failing call launches nothing and writes
+ *     nothing.  Data-dependent conditions (eigensolver not converged) are reported
+ *     in the device array `info`, never by the return code.
+ *   - Outputs are fully overwritten; inputs are never modified.
+ *   - Token indices are int32, local to the image's visual tokens (0 .. n_vis-1);
+ *     the sequence position of visual token x is vis_start + x.
+ *   - Notation: B batch, L sequence length, L_s = vis_start, N = n_vis, H heads,
+ *     d_h head_dim, D = H*d_h, k_p = k_prune = L_vc(1+rho), k_f = k_final = L_vc,
+ *     |A| = k_p/2 (integer division), |B| = k_p - |A|, m = k_p - k_f <= |B|.
+ */
+#ifndef TOKENCARVE_H
+#define TOKENCARVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define TC_API __attribute__((visibility("default")))
+#else
+#define TC_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  TC_OK = 0,
+  TC_ERR_NULL = -1,      /* a required pointer is NULL                               */
+  TC_ERR_SHAPE = -2,     /* unsupported or inconsistent sizes                        */
+  TC_ERR_DTYPE = -3,     /* dtype / eig_dtype not one of the enumerators             */
+  TC_ERR_PARAM = -4,     /* lambda, k_prune, k_final, tolerances out of range        */
+  TC_ERR_WORKSPACE = -5, /* ws_bytes < tc_workspace_bytes(p)                         */
+  TC_ERR_ALIGN = -6,     /* a pointer is not 16-byte aligned                         */
+  TC_ERR_HIP = -7        /* a HIP launch failed (hipGetLastError was not hipSuccess) */
+} tc_status;
+
+typedef enum { TC_F32 = 0, TC_BF16 = 1 } tc_dtype;          /* storage of Q,K,V,O,X,X_out */
+typedef enum { TC_NORM_NONE = 0, TC_NORM_MINMAX = 1 } tc_norm;
+typedef enum { TC_EIG_F64 = 0, TC_EIG_F32 = 1 } tc_eig_dtype; /* arithmetic of Gram + eigensolver */
+
+typedef struct {
+  int32_t batch;        /* B >= 0 (B == 0: nothing is launched, TC_OK)                         */
+  int32_t seq_len;      /* L                                                                    */
+  int32_t vis_start;    /* L_s ; vis_start + n_vis <= seq_len                                   */
+  int32_t n_vis;        /* N, 1 .. 4096                                                         */
+  int32_t n_heads;      /* H                                                                    */
+  int32_t head_dim;     /* d_h in {64, 128}; D = H * d_h                                        */
+  int32_t hidden_dim;   /* row width of X and X_out, a multiple of 8                            */
+  int32_t dtype;        /* tc_dtype                                                             */
+  int32_t causal;       /* 1: query at position p attends keys 0..p ; 0: all L keys             */
+  float softmax_scale;  /* 0 => 1/sqrt(head_dim)                                                */
+  float lambda;         /* Eq. 3-8 weight of the attention score, in [0,1]                      */
+  int32_t norm_mode;    /* tc_norm: min-max scale C and S over the image before Eq. 3-8, or not */
+  float sv_rtol;        /* Eq. 3-6 drops terms with sigma_i <= sv_rtol * sigma_max; 0 keeps all */
+  int32_t k_prune;      /* k_p: 1 <= k_final <= k_prune <= n_vis, k_prune - k_final <= |B|      */
+  int32_t k_final;      /* k_f                                                                  */
+  int32_t jacobi_max_sweeps; /* 0 => 30                                                         */
+  float jacobi_tol;     /* stop when off(G)/||G||_F measured during a sweep < tol; 0 => default */
+  int32_t eig_dtype;    /* tc_eig_dtype                                                         */
+} tc_params;
+
+/* Bytes of scratch that any entry point may need for `p` (0 if p is invalid). */
+TC_API size_t tc_workspace_bytes(const tc_params* p);
+
+/* Static text for a tc_status value. */
+TC_API const char* tc_status_string(int status);
+
+/*
+ * Eq. 3-1, 3-2 restricted to the visual query rows (Section 3.2.2 slice), and Eq. 3-7.
+ *   Q, K, V     [B, H, L, d_h]  dtype; rotary embedding already applied to Q and K
+ *   O           [B, N, D]       dtype; O[b, x, h*d_h + e] = sum_k A[b,h,L_s+x,k] V[b,h,k,e],
+ *                               A = softmax over the allowed keys of Q K^T * scale, rounded once
+ *   attn_score  [B, N]          float; S[b,x] = mean over h and over visual queries q of
+ *                               A[b,h,L_s+q,L_s+x] (masked entries count as 0); may be NULL
+ */
+TC_API int tc_attn_output(const tc_params* p, const void* Q, const void* K, const void* V, void* O,
+                   float* attn_score, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Section 3.3.1.  SVD of O[b] = U Sigma V^T is realised as the eigen-decomposition of the Gram
+ * matrix O O^T = U Sigma^2 U^T (batched block-Jacobi); Eq. 3-6 then Eq. 3-8.
+ *   O           [B, N, D] dtype
+ *   attn_score  [B, N] float, may be NULL only when lambda == 0
+ *   score       [B, N] float  E of Eq. 3-8
+ *   ics         [B, N] float  C of Eq. 3-6 (before any normalisation); optional (NULL)
+ *   sigma       [B, N] float  singular values, descending; optional
+ *   info        [B] int32     number of Jacobi sweeps used, negated if the tolerance was not
+ *                             reached within jacobi_max_sweeps; optional
+ */
+TC_API int tc_ipgs_score(const tc_params* p, const void* O, const float* attn_score, float* score,
+                  float* ics, float* sigma, int32_t* info, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage I (end of Section 3.3.1) and the ordering used by Eq. 3-9.
+ *   score  [B, N] float
+ *   order  [B, k_prune] int32  visual indices of the k_prune best scores, score descending,
+ *                              equal scores in ascending index order
+ */
+TC_API int tc_select_topk(const tc_params* p, const float* score, int32_t* order, void* ws,
+                   size_t ws_bytes, void* stream);
+
+/*
+ * Stage II (Section 3.3.2).  SetA = order[0 : k_p/2], SetB = the rest (Eq. 3-9); cosine
+ * similarity of `metric` rows (Eq. 3-10); the m SetB tokens with the highest best-similarity are
+ * averaged into their most similar SetA token (unweighted mean of the destination and all of its
+ * sources); every tie goes to the lower visual index.
+ *   X          [B, N, hidden_dim] dtype  rows that are averaged (hidden states of the visual tokens)
+ *   metric     [B, N, D] dtype           rows that are compared (the attention output O); may alias X
+ *   order      [B, k_prune] int32        from tc_select_topk; entries must be distinct, in [0, N)
+ *   X_out      [B, k_final, hidden_dim]  dtype, rows in ascending visual index
+ *   kept_idx   [B, k_final] int32        ascending visual indices of the rows of X_out
+ *   merge_dst  [B, N] int32              -1 pruned; x if x is an output row; a if x was merged into a
+ */
+TC_API int tc_merge(const tc_params* p, const void* X, const void* metric, const int32_t* order,
+             void* X_out, int32_t* kept_idx, int32_t* merge_dst, void* ws, size_t ws_bytes,
+             void* stream);
+
+/*
+ * The whole path of Section 3.3 on one stream: tc_attn_output -> tc_ipgs_score ->
+ * tc_select_topk -> tc_merge (metric = O).
+ *   X                      [B, N, hidden_dim] dtype (visual rows of the hidden states)
+ *   O_opt, score_opt, order_opt, info_opt: optional outputs ([B,N,D] dtype, [B,N] float,
+ *                          [B,k_prune] int32, [B] int32); NULL keeps the intermediate in `ws` only
+ */
+TC_API int tc_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X,
+                void* X_out, int32_t* kept_idx, int32_t* merge_dst, void* O_opt, float* score_opt,
+                int32_t* order_opt, int32_t* info_opt, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENCARVE_H */

@@ -1,0 +1,196 @@
+// C ABI entry points of libtokencarve: argument checks, workspace carving, stage sequencing.
+// The operations are defined in include/tokencarve.h (Section 3.3 of the TokenCarve paper).
+#include <cmath>
+
+#include "tc_internal.h"
+
+namespace tc {
+
+int make_plan(const tc_params* p, Plan* pl) {
+  if (!p) return TC_ERR_NULL;
+  if (p->dtype != TC_F32 && p->dtype != TC_BF16) return TC_ERR_DTYPE;
+  if (p->eig_dtype != TC_EIG_F64 && p->eig_dtype != TC_EIG_F32) return TC_ERR_DTYPE;
+  if (p->batch < 0 || p->seq_len < 1 || p->vis_start < 0 || p->n_vis < 1 || p->n_vis > MAX_NVIS ||
+      (int64_t)p->vis_start + p->n_vis > p->seq_len || p->n_heads < 1 || p->n_heads > 1024 ||
+      (p->head_dim != 64 && p->head_dim != 128) || p->hidden_dim < 8 || (p->hidden_dim % 8) != 0 ||
+      p->hidden_dim > (1 << 20) || p->seq_len > (1 << 20) || p->batch > (1 << 16))
+    return TC_ERR_SHAPE;
+  if (!(p->lambda >= 0.f && p->lambda <= 1.f) || (p->norm_mode != TC_NORM_NONE && p->norm_mode != TC_NORM_MINMAX) ||
+      !(p->sv_rtol >= 0.f && p->sv_rtol < 1.f) || (p->causal != 0 && p->causal != 1) || !(p->softmax_scale >= 0.f) ||
+      !std::isfinite(p->softmax_scale) || p->jacobi_max_sweeps < 0 || p->jacobi_max_sweeps > 1000 ||
+      !(p->jacobi_tol >= 0.f) || !(p->jacobi_tol < 1.f))
+    return TC_ERR_PARAM;
+  if (p->k_final < 1 || p->k_final > p->k_prune || p->k_prune > p->n_vis) return TC_ERR_PARAM;
+  const int nA = p->k_prune / 2, nB = p->k_prune - nA;
+  if (p->k_prune - p->k_final > nB) return TC_ERR_PARAM;
+
+  Plan& q = *pl;
+  q.B = p->batch; q.L = p->seq_len; q.Ls = p->vis_start; q.N = p->n_vis; q.H = p->n_heads; q.dh = p->head_dim;
+  q.D = q.H * q.dh; q.hidden = p->hidden_dim; q.kp = p->k_prune; q.kf = p->k_final; q.m = q.kp - q.kf;
+  q.nA = nA; q.nB = nB;
+  q.Np = round_up(q.N, JT); q.nblk = q.Np / JB; q.P = q.nblk / 2; q.steps = q.nblk - 1;
+  q.q_tile = 128; q.n_qtiles = (q.N + q.q_tile - 1) / q.q_tile;
+  q.esize = p->dtype == TC_BF16 ? 2 : 4;
+  q.tsize = p->eig_dtype == TC_EIG_F64 ? 8 : 4;
+  q.max_sweeps = p->jacobi_max_sweeps > 0 ? p->jacobi_max_sweeps : 30;
+  q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 1e-10 : 2e-6);
+  q.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)q.dh);
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return o; };
+  const size_t B = (size_t)q.B, N = (size_t)q.N, Np = (size_t)q.Np;
+  q.off_O = take(B * N * q.D * q.esize);
+  q.off_S = take(B * N * 4);
+  q.off_Spart = take(B * q.H * (size_t)(q.n_qtiles > 2 ? q.n_qtiles : 2) * N * 4);  // also holds the float path's (max, sum) pairs
+  q.off_G = take(B * Np * Np * q.tsize);
+  q.off_U = take(B * Np * Np * q.tsize);
+  q.off_R = take(B * q.P * JT * JT * q.tsize);
+  q.off_offpart = take(B * (size_t)q.P * q.steps * 8);
+  q.off_state = take(B * sizeof(EigState));
+  q.off_sig = take(B * Np * 8);
+  q.off_sigsort = take(B * Np * 4);
+  q.off_C = take(B * N * 4);
+  q.off_E = take(B * N * 4);
+  q.off_order = take(B * q.kp * 4);
+  q.off_rnorm = take(B * q.kp * 4);
+  q.off_sim = take(B * (size_t)q.nB * (q.nA > 0 ? q.nA : 1) * 4);
+  q.off_mlist = take(B * (size_t)(q.m > 0 ? q.m : 1) * 8);
+  q.off_info = take(B * 4);
+  q.off_minmax = take(B * 16);
+  q.total = off > 0 ? off : 256;
+  return TC_OK;
+}
+
+template <typename T>
+static T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+static int check_ws(const Plan& pl, const void* ws, size_t ws_bytes) {
+  if (!ws) return TC_ERR_NULL;
+  if (misaligned(ws)) return TC_ERR_ALIGN;
+  if (ws_bytes < pl.total) return TC_ERR_WORKSPACE;
+  return TC_OK;
+}
+
+static int ipgs_chain(const Plan& pl, const tc_params* p, const void* O, const float* S, float* score, float* ics,
+                      float* sigma, int32_t* info, void* ws, hipStream_t st) {
+  void* G = at<char>(ws, pl.off_G);
+  void* U = at<char>(ws, pl.off_U);
+  EigState* state = at<EigState>(ws, pl.off_state);
+  int rc = launch_gram(pl, p->dtype, p->eig_dtype, O, G, st);
+  if (rc != TC_OK) return rc;
+  rc = launch_jacobi(pl, p->eig_dtype, G, U, at<char>(ws, pl.off_R), at<double>(ws, pl.off_offpart), state, st);
+  if (rc != TC_OK) return rc;
+  return launch_scores(pl, p->eig_dtype, G, U, state, S, p->lambda, p->norm_mode, p->sv_rtol, at<char>(ws, pl.off_sig),
+                       at<float>(ws, pl.off_C), at<float>(ws, pl.off_minmax), score, ics, sigma, info, st);
+}
+
+}  // namespace tc
+
+using namespace tc;
+
+extern "C" {
+
+size_t tc_workspace_bytes(const tc_params* p) {
+  Plan pl;
+  if (make_plan(p, &pl) != TC_OK) return 0;
+  return pl.total;
+}
+
+const char* tc_status_string(int status) {
+  switch (status) {
+    case TC_OK: return "ok";
+    case TC_ERR_NULL: return "a required pointer is NULL";
+    case TC_ERR_SHAPE: return "unsupported or inconsistent sizes";
+    case TC_ERR_DTYPE: return "unknown dtype";
+    case TC_ERR_PARAM: return "parameter out of range";
+    case TC_ERR_WORKSPACE: return "workspace too small";
+    case TC_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case TC_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int tc_attn_output(const tc_params* p, const void* Q, const void* K, const void* V, void* O, float* attn_score,
+                   void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != TC_OK) return rc;
+  if (!Q || !K || !V || !O) return TC_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(attn_score)) return TC_ERR_ALIGN;
+  if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;
+  return launch_attention(pl, p->dtype, p->causal, Q, K, V, O, attn_score, at<float>(ws, pl.off_Spart),
+                          (hipStream_t)stream);
+}
+
+int tc_ipgs_score(const tc_params* p, const void* O, const float* attn_score, float* score, float* ics, float* sigma,
+                  int32_t* info, void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != TC_OK) return rc;
+  if (!O || !score) return TC_ERR_NULL;
+  if (!attn_score && p->lambda != 0.f) return TC_ERR_NULL;
+  if (misaligned(O) || misaligned(attn_score) || misaligned(score) || misaligned(ics) || misaligned(sigma) ||
+      misaligned(info))
+    return TC_ERR_ALIGN;
+  if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;
+  return ipgs_chain(pl, p, O, attn_score, score, ics, sigma, info, ws, (hipStream_t)stream);
+}
+
+int tc_select_topk(const tc_params* p, const float* score, int32_t* order, void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != TC_OK) return rc;
+  if (!score || !order) return TC_ERR_NULL;
+  if (misaligned(score) || misaligned(order)) return TC_ERR_ALIGN;
+  if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;
+  return launch_topk(pl, score, order, (hipStream_t)stream);
+}
+
+int tc_merge(const tc_params* p, const void* X, const void* metric, const int32_t* order, void* X_out,
+             int32_t* kept_idx, int32_t* merge_dst, void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != TC_OK) return rc;
+  if (!X || !metric || !order || !X_out || !kept_idx || !merge_dst) return TC_ERR_NULL;
+  if (misaligned(X) || misaligned(metric) || misaligned(order) || misaligned(X_out) || misaligned(kept_idx) ||
+      misaligned(merge_dst))
+    return TC_ERR_ALIGN;
+  if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;
+  return launch_merge(pl, p->dtype, X, metric, order, X_out, kept_idx, merge_dst, at<float>(ws, pl.off_rnorm),
+                      at<float>(ws, pl.off_sim), at<int32_t>(ws, pl.off_mlist), (hipStream_t)stream);
+}
+
+int tc_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X, void* X_out,
+                int32_t* kept_idx, int32_t* merge_dst, void* O_opt, float* score_opt, int32_t* order_opt,
+                int32_t* info_opt, void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != TC_OK) return rc;
+  if (!Q || !K || !V || !X || !X_out || !kept_idx || !merge_dst) return TC_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(X) || misaligned(X_out) || misaligned(kept_idx) ||
+      misaligned(merge_dst) || misaligned(O_opt) || misaligned(score_opt) || misaligned(order_opt) ||
+      misaligned(info_opt))
+    return TC_ERR_ALIGN;
+  if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;
+  hipStream_t st = (hipStream_t)stream;
+  void* O = O_opt ? O_opt : at<char>(ws, pl.off_O);
+  float* S = at<float>(ws, pl.off_S);
+  float* E = score_opt ? score_opt : at<float>(ws, pl.off_E);
+  int32_t* order = order_opt ? order_opt : at<int32_t>(ws, pl.off_order);
+  int32_t* info = info_opt ? info_opt : at<int32_t>(ws, pl.off_info);
+  rc = launch_attention(pl, p->dtype, p->causal, Q, K, V, O, S, at<float>(ws, pl.off_Spart), st);
+  if (rc != TC_OK) return rc;
+  rc = ipgs_chain(pl, p, O, S, E, nullptr, nullptr, info, ws, st);
+  if (rc != TC_OK) return rc;
+  rc = launch_topk(pl, E, order, st);
+  if (rc != TC_OK) return rc;
+  return launch_merge(pl, p->dtype, X, O, order, X_out, kept_idx, merge_dst, at<float>(ws, pl.off_rnorm),
+                      at<float>(ws, pl.off_sim), at<int32_t>(ws, pl.off_mlist), st);
+}
+
+}  // extern "C"

@@ -1,0 +1,377 @@
+// Attention output of the visual query rows (Eq. 3-1, 3-2 and the slice of Section 3.2.2) and the
+// attention score of every visual token (Eq. 3-7).
+//
+// bf16 path: one workgroup = one (image, head, 128-query tile); each wavefront owns 32 queries.
+// Scores are formed transposed, S^T = K Q^T, so that a lane owns one query (softmax statistics stay
+// in the lane) and the probabilities feed O^T = V^T P^T straight from the accumulator registers.
+// Two passes over the keys: pass 1 finds the row maximum and normaliser, pass 2 recomputes the
+// scores, forms the exact probabilities, accumulates O^T and the column sums of the probabilities
+// (the attention matrix itself is never stored).  Column sums leave the workgroup as one partial
+// row per (head, query tile) and are added in a fixed order by a second small kernel.
+#include "tc_internal.h"
+
+namespace tc {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf8;
+typedef __attribute__((ext_vector_type(16))) float f16v;
+
+constexpr int AQ = 128;  // queries per workgroup
+constexpr int AK = 64;   // keys per LDS tile
+
+template <int DH>
+struct AttnSmem {
+  static constexpr int KLD = DH + 8;  // bf16 elements per K row in LDS
+  static constexpr int VLD = AK + 8;  // bf16 elements per V^T row in LDS
+  static constexpr int K_BYTES = AK * KLD * 2;
+  static constexpr int V_BYTES = DH * VLD * 2;
+  static constexpr int O_BYTES = 4 * 32 * KLD * 2;
+  static constexpr int MAIN = (K_BYTES + V_BYTES) > O_BYTES ? (K_BYTES + V_BYTES) : O_BYTES;
+};
+
+template <int DH>
+__device__ inline void load_k_tile(const uint16_t* __restrict__ Kh, int k0, int L, uint4* regs) {
+  constexpr int CH = DH / 8, ITER = AK * CH / 256;
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int idx = threadIdx.x + 256 * it, key = idx / CH, ch = idx % CH;
+    regs[it] = (k0 + key < L) ? *reinterpret_cast<const uint4*>(Kh + (size_t)(k0 + key) * DH + ch * 8) : uint4{0, 0, 0, 0};
+  }
+}
+template <int DH>
+__device__ inline void store_k_tile(uint16_t* Ks, const uint4* regs) {
+  constexpr int CH = DH / 8, ITER = AK * CH / 256, KLD = AttnSmem<DH>::KLD;
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int idx = threadIdx.x + 256 * it, key = idx / CH, ch = idx % CH;
+    *reinterpret_cast<uint4*>(Ks + key * KLD + ch * 8) = regs[it];
+  }
+}
+template <int DH>
+__device__ inline void load_v_tile(const uint16_t* __restrict__ Vh, int k0, int L, uint4* regs) {
+  constexpr int ITER = DH / 32;
+  const int key = threadIdx.x & 63;
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int ch = (threadIdx.x >> 6) + 4 * it;
+    regs[it] = (k0 + key < L) ? *reinterpret_cast<const uint4*>(Vh + (size_t)(k0 + key) * DH + ch * 8) : uint4{0, 0, 0, 0};
+  }
+}
+template <int DH>
+__device__ inline void store_v_tile_transposed(uint16_t* Vt, const uint4* regs) {
+  constexpr int ITER = DH / 32, VLD = AttnSmem<DH>::VLD;
+  const int key = threadIdx.x & 63;
+#pragma unroll
+  for (int it = 0; it < ITER; it++) {
+    const int ch = (threadIdx.x >> 6) + 4 * it;
+    const uint32_t w[4] = {regs[it].x, regs[it].y, regs[it].z, regs[it].w};
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      Vt[(ch * 8 + 2 * i) * VLD + key] = (uint16_t)(w[i] & 0xffffu);
+      Vt[(ch * 8 + 2 * i + 1) * VLD + key] = (uint16_t)(w[i] >> 16);
+    }
+  }
+}
+
+// S^T sub-tile: 32 keys (rows) x 32 queries (columns); accumulator element r of a lane is
+// key 8*(r/4) + 4*(lane/32) + r%4, query lane%32.
+template <int DH>
+__device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const bf8* qf, int lane) {
+  constexpr int KLD = AttnSmem<DH>::KLD;
+  f16v acc;
+#pragma unroll
+  for (int i = 0; i < 16; i++) acc[i] = 0.f;
+  const uint16_t* row = Ks + (sub * 32 + (lane & 31)) * KLD + 8 * (lane >> 5);
+#pragma unroll
+  for (int ks = 0; ks < DH / 16; ks++) {
+    const bf8 a = *reinterpret_cast<const bf8*>(row + 16 * ks);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+                                                        const uint16_t* __restrict__ V, uint16_t* __restrict__ O,
+                                                        float* __restrict__ Spart, int L, int Ls, int N, int H,
+                                                        int causal, float scale_log2e, int n_qtiles) {
+  typedef AttnSmem<DH> SM;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SM::MAIN];
+  __shared__ float cs[4][AK];
+  uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
+  uint16_t* Vt = reinterpret_cast<uint16_t*>(smem + SM::K_BYTES);
+  const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const size_t head_off = ((size_t)b * H + h) * (size_t)L * DH;
+  const uint16_t* Qh = Q + head_off;
+  const uint16_t* Kh = K + head_off;
+  const uint16_t* Vh = V + head_off;
+  const int q = qt * AQ + wave * 32 + (lane & 31);
+  const bool qvalid = q < N;
+  const int p = Ls + (qvalid ? q : N - 1);            // sequence position of this lane's query
+  const int kend_q = causal ? p + 1 : L;              // keys [0, kend_q) are visible to it
+  const int q_last = min(N, (qt + 1) * AQ) - 1;
+  const int kend = causal ? min(L, Ls + q_last + 1) : L;
+  const int n_tiles = (kend + AK - 1) / AK;
+
+  bf8 qf[DH / 16];
+#pragma unroll
+  for (int ks = 0; ks < DH / 16; ks++)
+    qf[ks] = *reinterpret_cast<const bf8*>(Qh + (size_t)p * DH + 16 * ks + 8 * half);
+
+  // ---------------- pass 1: row maximum and normaliser (log2 domain) ----------------
+  float m_run = -INFINITY, l_run = 0.f;
+  for (int t = 0; t < n_tiles; t++) {
+    const int k0 = t * AK;
+    uint4 kr[AK * (DH / 8) / 256];
+    load_k_tile<DH>(Kh, k0, L, kr);
+    __syncthreads();
+    store_k_tile<DH>(Ks, kr);
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < 2; sub++) {
+      const f16v acc = score_subtile<DH>(Ks, sub, qf, lane);
+      float s2[16], mx = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        s2[r] = key < kend_q ? acc[r] * scale_log2e : -INFINITY;
+        mx = fmaxf(mx, s2[r]);
+      }
+      if (mx > -INFINITY) {
+        const float m_new = fmaxf(m_run, mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) sum += exp2f(s2[r] - m_new);
+        l_run = l_run * exp2f(m_run - m_new) + sum;
+        m_run = m_new;
+      }
+    }
+  }
+  {
+    const float m_o = __shfl_xor(m_run, 32, 64), l_o = __shfl_xor(l_run, 32, 64);
+    const float M = fmaxf(m_run, m_o);  // finite: key 0 is visible to every query
+    l_run = l_run * exp2f(m_run - M) + l_o * exp2f(m_o - M);
+    m_run = M;
+  }
+  const float inv_l = qvalid ? 1.0f / l_run : 0.f;  // rows past N contribute nothing
+
+  // ---------------- pass 2: probabilities, O^T accumulation, column sums ----------------
+  f16v oacc[DH / 32];
+#pragma unroll
+  for (int mt = 0; mt < DH / 32; mt++)
+#pragma unroll
+    for (int i = 0; i < 16; i++) oacc[mt][i] = 0.f;
+  float* sp_row = Spart + (((size_t)b * H + h) * n_qtiles + qt) * N;
+  for (int t = 0; t < n_tiles; t++) {
+    const int k0 = t * AK;
+    uint4 kr[AK * (DH / 8) / 256], vr[DH / 32];
+    load_k_tile<DH>(Kh, k0, L, kr);
+    load_v_tile<DH>(Vh, k0, L, vr);
+    __syncthreads();
+    store_k_tile<DH>(Ks, kr);
+    store_v_tile_transposed<DH>(Vt, vr);
+    __syncthreads();
+    float pr[32];
+#pragma unroll
+    for (int sub = 0; sub < 2; sub++) {
+      const f16v acc = score_subtile<DH>(Ks, sub, qf, lane);
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        pr[sub * 16 + r] = key < kend_q ? exp2f(acc[r] * scale_log2e - m_run) * inv_l : 0.f;
+      }
+    }
+    // O^T += V^T P^T.  Matrix-core k-slot (half, i) of product (sub, u) is key
+    // sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
+#pragma unroll
+    for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+      for (int u = 0; u < 2; u++) {
+        // probabilities enter the matrix cores as a bf16 head plus a bf16 remainder (16 significant
+        // bits), so O is accurate to its own final rounding
+        bf8 pb, pl;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          const float pv = pr[sub * 16 + 8 * u + i];
+          pb[i] = (__bf16)pv;
+          pl[i] = (__bf16)(pv - (float)pb[i]);
+        }
+#pragma unroll
+        for (int mt = 0; mt < DH / 32; mt++) {
+          const uint16_t* vrow = Vt + (32 * mt + (lane & 31)) * SM::VLD + sub * 32 + 16 * u + 4 * half;
+          const uint2 lo = *reinterpret_cast<const uint2*>(vrow);
+          const uint2 hi = *reinterpret_cast<const uint2*>(vrow + 8);
+          union { uint4 u4; bf8 v; } va;
+          va.u4 = uint4{lo.x, lo.y, hi.x, hi.y};
+          oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb, oacc[mt], 0, 0, 0);
+          oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pl, oacc[mt], 0, 0, 0);
+        }
+      }
+    // column sums over this wavefront's 32 queries: recursive halving across lanes 0..31 of each half
+#pragma unroll
+    for (int o = 16, n = 32; o >= 1; o >>= 1, n >>= 1) {
+      const bool up = (lane & o) != 0;
+#pragma unroll
+      for (int i = 0; i < n / 2; i++) {
+        const float send = up ? pr[i] : pr[i + n / 2];
+        const float keep = up ? pr[i + n / 2] : pr[i];
+        pr[i] = keep + __shfl_xor(send, o, 64);
+      }
+    }
+    {
+      const int vi = lane & 31, sub = vi >> 4, r = vi & 15;
+      cs[wave][sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = pr[0];
+    }
+    __syncthreads();
+    if (tid < AK) {
+      const int x = k0 + tid - Ls;
+      if (x >= 0 && x < N) sp_row[x] = (cs[0][tid] + cs[1][tid]) + (cs[2][tid] + cs[3][tid]);
+    }
+  }
+  // visual tokens behind the last key tile received no attention from this query tile
+  for (int x = max(0, n_tiles * AK - Ls) + tid; x < N; x += 256) sp_row[x] = 0.f;
+
+  // ---------------- write O: transpose through LDS, 16-byte rows stores ----------------
+  __syncthreads();
+  uint16_t* Os = reinterpret_cast<uint16_t*>(smem) + wave * 32 * SM::KLD;
+#pragma unroll
+  for (int mt = 0; mt < DH / 32; mt++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int d = 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3);
+      Os[(lane & 31) * SM::KLD + d] = float_to_bf16_bits(oacc[mt][r]);
+    }
+  __syncthreads();
+  constexpr int CH = DH / 8;
+  for (int idx = lane; idx < 32 * CH; idx += 64) {
+    const int ql = idx / CH, ch = idx % CH;
+    const int qq = qt * AQ + wave * 32 + ql;
+    if (qq < N)
+      *reinterpret_cast<uint4*>(O + ((size_t)b * N + qq) * ((size_t)H * DH) + (size_t)h * DH + ch * 8) =
+          *reinterpret_cast<const uint4*>(Os + ql * SM::KLD + ch * 8);
+  }
+}
+
+// S[b][x] = (1 / (H N)) sum_h sum_tiles partial column sums, in a fixed order.
+__global__ __launch_bounds__(256) void attn_score_reduce(const float* __restrict__ Spart, float* __restrict__ S, int N,
+                                                         int H, int n_qtiles) {
+  const int b = blockIdx.y, x = blockIdx.x * 256 + threadIdx.x;
+  if (x >= N) return;
+  const float* sp = Spart + (size_t)b * H * n_qtiles * N + x;
+  double acc = 0.0;
+  for (int i = 0; i < H * n_qtiles; i++) acc += (double)sp[(size_t)i * N];
+  S[(size_t)b * N + x] = (float)(acc / ((double)H * (double)N));
+}
+
+// ---------------- float32 storage: plain-ALU correctness path ----------------
+// One wavefront per (image, head, query): two passes over the keys, float accumulation.
+template <int DH>
+__global__ __launch_bounds__(64) void attn_f32_rows(const float* __restrict__ Q, const float* __restrict__ K,
+                                                    const float* __restrict__ V, float* __restrict__ O,
+                                                    float* __restrict__ stats, int L, int Ls, int N, int H, int causal,
+                                                    float scale) {
+  __shared__ float qs[DH];
+  const int q = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
+  const size_t head_off = ((size_t)b * H + h) * (size_t)L * DH;
+  const int p = Ls + q, kend = causal ? p + 1 : L;
+  for (int d = lane; d < DH; d += 64) qs[d] = Q[head_off + (size_t)p * DH + d];
+  __syncthreads();
+  float m = -INFINITY, l = 0.f;
+  for (int k = lane; k < kend; k += 64) {
+    const float* kr = K + head_off + (size_t)k * DH;
+    float s = 0.f;
+    for (int d = 0; d < DH; d++) s += qs[d] * kr[d];
+    s *= scale;
+    const float mn = fmaxf(m, s);
+    l = l * expf(m - mn) + expf(s - mn);
+    m = mn;
+  }
+  float M = m;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+  l = (m > -INFINITY) ? l * expf(m - M) : 0.f;
+  l = wave_sum(l);
+  float acc[DH];
+#pragma unroll
+  for (int d = 0; d < DH; d++) acc[d] = 0.f;
+  for (int k = lane; k < kend; k += 64) {
+    const float* kr = K + head_off + (size_t)k * DH;
+    const float* vr = V + head_off + (size_t)k * DH;
+    float s = 0.f;
+    for (int d = 0; d < DH; d++) s += qs[d] * kr[d];
+    const float pk = expf(s * scale - M) / l;
+#pragma unroll
+    for (int d = 0; d < DH; d++) acc[d] += pk * vr[d];
+  }
+  float* out = O + ((size_t)b * N + q) * ((size_t)H * DH) + (size_t)h * DH;
+#pragma unroll
+  for (int d = 0; d < DH; d++) {
+    const float v = wave_sum(acc[d]);
+    if (lane == (d & 63)) out[d] = v;
+  }
+  if (lane == 0) {
+    stats[(((size_t)b * H + h) * N + q) * 2] = M;
+    stats[(((size_t)b * H + h) * N + q) * 2 + 1] = l;
+  }
+}
+
+// One workgroup per (image, visual key x): S[b][x] = mean over heads and visual queries of A[.., q, x].
+template <int DH>
+__global__ __launch_bounds__(256) void attn_f32_cols(const float* __restrict__ Q, const float* __restrict__ K,
+                                                     const float* __restrict__ stats, float* __restrict__ S, int L,
+                                                     int Ls, int N, int H, int causal, float scale) {
+  __shared__ double red[256];
+  const int x = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  double acc = 0.0;
+  for (int idx = tid; idx < H * N; idx += 256) {
+    const int h = idx / N, q = idx % N;
+    if (causal && x > q) continue;
+    const size_t head_off = ((size_t)b * H + h) * (size_t)L * DH;
+    const float* qr = Q + head_off + (size_t)(Ls + q) * DH;
+    const float* kr = K + head_off + (size_t)(Ls + x) * DH;
+    float s = 0.f;
+    for (int d = 0; d < DH; d++) s += qr[d] * kr[d];
+    const float M = stats[(((size_t)b * H + h) * N + q) * 2], l = stats[(((size_t)b * H + h) * N + q) * 2 + 1];
+    acc += (double)(expf(s * scale - M) / l);
+  }
+  red[tid] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  if (tid == 0) S[(size_t)b * N + x] = (float)(red[0] / ((double)H * (double)N));
+}
+
+int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const void* K, const void* V, void* O,
+                     float* S, float* Spart, hipStream_t st) {
+  if (dtype == TC_BF16) {
+    const dim3 grid(pl.n_qtiles, pl.H, pl.B);
+    const float sl2 = pl.scale * 1.4426950408889634f;
+    if (pl.dh == 128)
+      attn_bf16_kernel<128><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
+                                                  (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
+                                                  pl.n_qtiles);
+    else
+      attn_bf16_kernel<64><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
+                                                 (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
+                                                 pl.n_qtiles);
+    if (S) attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.H, pl.n_qtiles);
+  } else {
+    const dim3 grid(pl.N, pl.H, pl.B);
+    if (pl.dh == 128) {
+      attn_f32_rows<128><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart,
+                                              pl.L, pl.Ls, pl.N, pl.H, causal, pl.scale);
+      if (S) attn_f32_cols<128><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
+                                                                   pl.Ls, pl.N, pl.H, causal, pl.scale);
+    } else {
+      attn_f32_rows<64><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart, pl.L,
+                                             pl.Ls, pl.N, pl.H, causal, pl.scale);
+      if (S) attn_f32_cols<64><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
+                                                                  pl.Ls, pl.N, pl.H, causal, pl.scale);
+    }
+  }
+  return check_launch();
+}
+
+}  // namespace tc

@@ -1,0 +1,97 @@
+// Internal declarations shared by the HIP translation units of libtokencarve.
+// Nothing here is part of the C ABI (see include/tokencarve.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tokencarve.h"
+
+namespace tc {
+
+// ---- block-Jacobi geometry -------------------------------------------------------------
+constexpr int JB = 32;      // block size b of the block-Jacobi eigensolver
+constexpr int JT = 2 * JB;  // a block pair spans a 64 x 64 tile
+constexpr int MAX_NVIS = 4096;
+
+__host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// Per-image eigensolver state kept in the workspace.
+struct EigState {
+  double norm2;    // ||G||_F^2, fixed for the whole solve
+  int32_t done;    // 1 once the off-diagonal measure fell below the tolerance
+  int32_t sweeps;  // sweeps executed so far
+};
+
+// Everything an entry point needs to know about sizes and where its scratch lives.
+struct Plan {
+  int B, L, Ls, N, H, dh, D, hidden, kp, kf, m, nA, nB;
+  int Np;        // N rounded up to a multiple of JT (zero padded rows/columns of G)
+  int nblk;      // Np / JB, always even
+  int P;         // nblk / 2 block pairs per step
+  int steps;     // nblk - 1 steps per sweep
+  int q_tile;    // query rows per attention workgroup
+  int n_qtiles;
+  int esize;     // bytes of one stored element (2 or 4)
+  int tsize;     // bytes of one eigensolver element (4 or 8)
+  int max_sweeps;
+  double tol;
+  float scale;
+  size_t off_O, off_S, off_Spart, off_G, off_U, off_R, off_offpart, off_state, off_sig, off_sigsort, off_C,
+      off_E, off_order, off_rnorm, off_sim, off_mlist, off_info, off_minmax;
+  size_t total;
+};
+
+int make_plan(const tc_params* p, Plan* plan);  // validates p; returns tc_status
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// ---- stage launchers (each returns a tc_status; all work is enqueued on `st`) ----------
+int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const void* K, const void* V, void* O,
+                     float* S, float* Spart, hipStream_t st);
+int launch_gram(const Plan& pl, int dtype, int eig_dtype, const void* O, void* G, hipStream_t st);
+int launch_jacobi(const Plan& pl, int eig_dtype, void* G, void* U, void* R, double* offpart, EigState* state,
+                  hipStream_t st);
+int launch_scores(const Plan& pl, int eig_dtype, const void* G, const void* U, const EigState* state,
+                  const float* S, float lambda, int norm_mode, float sv_rtol, void* sig_ws, float* C_ws,
+                  float* minmax_ws, float* E, float* C_out, float* sigma_out, int32_t* info_out, hipStream_t st);
+int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st);
+int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, const int32_t* order, void* X_out,
+                 int32_t* kept_idx, int32_t* merge_dst, float* rnorm, float* sim, int32_t* mlist, hipStream_t st);
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? TC_OK : TC_ERR_HIP; }
+
+// ---- small device helpers ---------------------------------------------------------------
+__device__ inline float bf16_bits_to_float(uint16_t h) { return __uint_as_float(uint32_t(h) << 16); }
+
+__device__ inline uint16_t float_to_bf16_bits(float f) {  // round to nearest even; NaN stays NaN
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return uint16_t((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+// Round-robin tournament on n (even) players: pair `i` (0 <= i < n/2) of round `s` (0 <= s < n-1).
+__host__ __device__ inline void round_robin_pair(int n, int s, int i, int* a, int* b) {
+  const int m = n - 1;
+  int x, y;
+  if (i == 0) {
+    x = n - 1;
+    y = s % m;
+  } else {
+    x = (s + i) % m;
+    y = (s - i + m) % m;
+  }
+  *a = x < y ? x : y;
+  *b = x < y ? y : x;
+}
+
+template <typename T>
+__device__ inline T wave_sum(T v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+}  // namespace tc
