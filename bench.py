@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the TokenCarve compression path on one MI355X.
+
+One step = one tc_compress call (attention output -> IPGS score -> prune -> merge) over one batch of
+synthetic LLaVA-1.5-7B-shaped inputs (batch 64, 576 visual + 64 text tokens, D = 4096, bf16,
+576 -> 128 -> 64 tokens), inputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llava7b_b64] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix-core peak
+PEAK_FP32_MFMA_TFLOPS = 157.3
+
+
+def jacobi_update_flops_per_image_step(n_vis):
+    """Algorithmic flops of one block-Jacobi tile-update step for one image.
+
+    b = 32, a pair tile is 64x64.  With P pairs, symmetry leaves P(P+1)/2 tiles of G, each two
+    64x64x64 products (R_I^T G_IJ, then times R_J); U has (Np/64) x P tiles with one product each.
+    """
+    np_ = (n_vis + 63) // 64 * 64
+    P = np_ // 64
+    gemm = 2 * 64 ** 3
+    return (P * (P + 1) // 2 * 2 + (np_ // 64) * P) * gemm
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llava7b_b64")
+    ap.add_argument("--eig", default="f64", choices=["f64", "f32"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=12, help="images timed through the CPU oracle")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards by image with no exchange; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_10501_amd import binding as tc
+    from workloads import CONFIGS, make_batch
+
+    tc.load_library()  # fails loudly when the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    w = CONFIGS[args.workload]
+    t0 = time.time()
+    batch = make_batch(w)
+    gen_s = time.time() - t0
+    eig = tc.TC_EIG_F64 if args.eig == "f64" else tc.TC_EIG_F32
+    p = tc.params_for(w, eig_dtype=eig)
+    sd = tc.storage_dtype(p)
+
+    def dev(a):
+        return torch.from_numpy(a).cuda().to(sd).contiguous()
+
+    Q, K, V = dev(batch["Q"]), dev(batch["K"]), dev(batch["V"])
+    X = dev(np.ascontiguousarray(batch["X"][:, w.n_sys:w.n_sys + w.n_vis]))
+    B, N = w.batch, w.n_vis
+    X_out = torch.empty(B, w.k_final, w.hidden, dtype=sd, device="cuda")
+    kept = torch.empty(B, w.k_final, dtype=torch.int32, device="cuda")
+    dst = torch.empty(B, N, dtype=torch.int32, device="cuda")
+    info = torch.empty(B, dtype=torch.int32, device="cuda")
+    ws = tc.new_workspace(p)
+
+    # calibration: how many eigensolver sweeps does the slowest image need?  The timed runs launch
+    # exactly that many (+1 so that every image reports convergence), not the library default of 30.
+    tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, info=info)
+    torch.cuda.synchronize()
+    sweeps = info.cpu().numpy()
+    if (sweeps <= 0).any():
+        print("bench.py: eigensolver did not converge for some image: %s" % sweeps, file=sys.stderr)
+        sys.exit(1)
+    p.jacobi_max_sweeps = int(sweeps.max())
+    kept_ref = kept.clone()
+
+    for _ in range(args.warmup):
+        tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, info=info)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, info=info)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    if (info.cpu().numpy() <= 0).any() or not torch.equal(kept, kept_ref):
+        print("bench.py: timed runs disagree with the calibration run", file=sys.stderr)
+        sys.exit(1)
+
+    # per-kernel durations, measured live with HIP events on the launch stream
+    kinds, upd_by_sweep = tc.tc_profile_compress(p, Q, K, V, X, X_out, kept, dst, info, ws)
+    kinds, upd_by_sweep = tc.tc_profile_compress(p, Q, K, V, X, X_out, kept, dst, info, ws)
+    upd_ms, upd_launches = kinds["jacobi_update"]
+    steps_per_sweep = (N + 63) // 64 * 2 - 1
+    per_img = jacobi_update_flops_per_image_step(N)
+    flops = 0.0
+    for s in range(p.jacobi_max_sweeps):
+        active = int((sweeps > s).sum())            # images still iterating in sweep s
+        flops += active * per_img * steps_per_sweep
+    achieved = flops / (upd_ms * 1e-3) / 1e12
+    peak = PEAK_FP64_MFMA_TFLOPS if args.eig == "f64" else PEAK_FP32_MFMA_TFLOPS
+    total_kernel_ms = sum(v[0] for v in kinds.values())
+
+    out = {
+        "metric": "images/sec compressed (576x4096 -> k_prune -> k_final tokens, batch 64)",
+        "value": round(B / (ms_per_step * 1e-3), 2),
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 storage; fp32-accumulate bf16 MFMA (attention, similarity); %s Gram + eigensolver" % args.eig,
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "n_vis": N, "n_text": w.n_sys + w.n_prompt,
+                   "hidden": w.hidden, "heads": w.n_heads, "head_dim": w.head_dim,
+                   "k_prune": w.k_prune, "k_final": w.k_final, "lambda": w.lam, "causal": w.causal,
+                   "qkv": w.qkv_mode, "jacobi_max_sweeps": int(p.jacobi_max_sweeps),
+                   "sweeps_used_min_max": [int(sweeps.min()), int(sweeps.max())],
+                   "input_generation_s": round(gen_s, 1)},
+        "roofline": {"kernel": "jacobi_update", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                     "avg_launch_us": round(upd_ms * 1e3 / max(upd_launches, 1), 2), "launches": upd_launches},
+        "kernel_ms": {k: round(v[0], 3) for k, v in kinds.items()},
+        "kernel_ms_total": round(total_kernel_ms, 3),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import tokencarve_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        n = min(args.cpu_sample, B)
+        t0 = time.perf_counter()
+        for i in range(n):
+            orc.compress(batch["Q"][i], batch["K"][i], batch["V"][i], batch["X"][i, w.n_sys:w.n_sys + w.n_vis],
+                         w.n_sys, w.n_vis, w.k_prune, w.k_final, lam=w.lam, causal=bool(w.causal), dtype=w.dtype)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n / cpu_s, 3), "unit": "images/s", "cores": int(cores),
+                               "kind": "oracle",
+                               "sample": "first %d images of the same batch, float64 numpy oracle, one image at a "
+                                         "time with BLAS/LAPACK threads" % n}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

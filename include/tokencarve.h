@@ -147,6 +147,24 @@ TC_API int tc_compress(const tc_params* p, const void* Q, const void* K, const v
                 void* X_out, int32_t* kept_idx, int32_t* merge_dst, void* O_opt, float* score_opt,
                 int32_t* order_opt, int32_t* info_opt, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Measurement aid (not part of the method): runs tc_compress with a pair of HIP events around every
+ * kernel launch, waits for the stream, and returns on the HOST the summed duration in milliseconds
+ * and the number of launches per kernel kind (arrays of TC_PROF_KINDS entries, order of tc_prof_kind).
+ * jacobi_update_ms_by_sweep (host, max_sweeps_out floats, may be NULL) receives the tile-update time
+ * of each eigensolver sweep.  Unlike every other entry point this one blocks the calling thread and
+ * creates and destroys HIP events.
+ */
+typedef enum {
+  TC_PROF_ATTN = 0, TC_PROF_ATTN_REDUCE, TC_PROF_GRAM, TC_PROF_JACOBI_INIT, TC_PROF_JACOBI_SOLVE,
+  TC_PROF_JACOBI_UPDATE, TC_PROF_JACOBI_SWEEP_END, TC_PROF_SIGMA, TC_PROF_ICS, TC_PROF_COMBINE, TC_PROF_TOPK,
+  TC_PROF_ROWNORM, TC_PROF_SIM, TC_PROF_ASSIGN, TC_PROF_AVERAGE, TC_PROF_KINDS
+} tc_prof_kind;
+TC_API int tc_profile_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X,
+                               void* X_out, int32_t* kept_idx, int32_t* merge_dst, int32_t* info, void* ws,
+                               size_t ws_bytes, void* stream, float* ms_by_kind, int32_t* launches_by_kind,
+                               float* jacobi_update_ms_by_sweep, int32_t max_sweeps_out);
+
 #ifdef __cplusplus
 }
 #endif

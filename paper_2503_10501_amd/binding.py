@@ -18,7 +18,9 @@ TC_NORM_NONE, TC_NORM_MINMAX = 0, 1
 TC_EIG_F64, TC_EIG_F32 = 0, 1
 
 SYMBOLS = ("tc_workspace_bytes", "tc_status_string", "tc_attn_output", "tc_ipgs_score", "tc_select_topk",
-           "tc_merge", "tc_compress")
+           "tc_merge", "tc_compress", "tc_profile_compress")
+PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_sweep_end",
+              "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average")
 
 
 class TokenCarveError(RuntimeError):
@@ -78,6 +80,7 @@ def load_library():
     lib.tc_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.tc_merge.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tc_profile_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, ctypes.c_int32]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -155,3 +158,17 @@ def tc_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, ws, O=None, score=Non
                                       _ptr(X_out, sd), _ptr(kept_idx, torch.int32), _ptr(merge_dst, torch.int32),
                                       _ptr(O, sd), _ptr(score, torch.float32), _ptr(order, torch.int32),
                                       _ptr(info, torch.int32), _ptr(ws), ws.numel(), _stream(stream)))
+
+
+def tc_profile_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, info, ws, max_sweeps_out=64, stream=None):
+    """Returns ({kind: (total_ms, launches)}, [jacobi_update ms per sweep]); blocks until the stream is idle."""
+    sd = storage_dtype(p)
+    n = len(PROF_KINDS)
+    ms = (ctypes.c_float * n)()
+    cnt = (ctypes.c_int32 * n)()
+    per_sweep = (ctypes.c_float * max_sweeps_out)()
+    _check(load_library().tc_profile_compress(ctypes.byref(p), _ptr(Q, sd), _ptr(K, sd), _ptr(V, sd), _ptr(X, sd),
+                                              _ptr(X_out, sd), _ptr(kept_idx, torch.int32),
+                                              _ptr(merge_dst, torch.int32), _ptr(info, torch.int32), _ptr(ws),
+                                              ws.numel(), _stream(stream), ms, cnt, per_sweep, max_sweeps_out))
+    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(PROF_KINDS)}, [float(x) for x in per_sweep]

@@ -115,10 +115,10 @@ int tc_attn_output(const tc_params* p, const void* Q, const void* K, const void*
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;  // an empty batch: nothing to check, nothing to launch
   if (!Q || !K || !V || !O) return TC_ERR_NULL;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(attn_score)) return TC_ERR_ALIGN;
   if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
-  if (pl.B == 0) return TC_OK;
   return launch_attention(pl, p->dtype, p->causal, Q, K, V, O, attn_score, at<float>(ws, pl.off_Spart),
                           (hipStream_t)stream);
 }
@@ -128,13 +128,13 @@ int tc_ipgs_score(const tc_params* p, const void* O, const float* attn_score, fl
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;  // an empty batch: nothing to check, nothing to launch
   if (!O || !score) return TC_ERR_NULL;
   if (!attn_score && p->lambda != 0.f) return TC_ERR_NULL;
   if (misaligned(O) || misaligned(attn_score) || misaligned(score) || misaligned(ics) || misaligned(sigma) ||
       misaligned(info))
     return TC_ERR_ALIGN;
   if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
-  if (pl.B == 0) return TC_OK;
   return ipgs_chain(pl, p, O, attn_score, score, ics, sigma, info, ws, (hipStream_t)stream);
 }
 
@@ -142,10 +142,10 @@ int tc_select_topk(const tc_params* p, const float* score, int32_t* order, void*
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;  // an empty batch: nothing to check, nothing to launch
   if (!score || !order) return TC_ERR_NULL;
   if (misaligned(score) || misaligned(order)) return TC_ERR_ALIGN;
   if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
-  if (pl.B == 0) return TC_OK;
   return launch_topk(pl, score, order, (hipStream_t)stream);
 }
 
@@ -154,12 +154,12 @@ int tc_merge(const tc_params* p, const void* X, const void* metric, const int32_
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;  // an empty batch: nothing to check, nothing to launch
   if (!X || !metric || !order || !X_out || !kept_idx || !merge_dst) return TC_ERR_NULL;
   if (misaligned(X) || misaligned(metric) || misaligned(order) || misaligned(X_out) || misaligned(kept_idx) ||
       misaligned(merge_dst))
     return TC_ERR_ALIGN;
   if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
-  if (pl.B == 0) return TC_OK;
   return launch_merge(pl, p->dtype, X, metric, order, X_out, kept_idx, merge_dst, at<float>(ws, pl.off_rnorm),
                       at<float>(ws, pl.off_sim), at<int32_t>(ws, pl.off_mlist), (hipStream_t)stream);
 }
@@ -170,13 +170,13 @@ int tc_compress(const tc_params* p, const void* Q, const void* K, const void* V,
   Plan pl;
   int rc = make_plan(p, &pl);
   if (rc != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;  // an empty batch: nothing to check, nothing to launch
   if (!Q || !K || !V || !X || !X_out || !kept_idx || !merge_dst) return TC_ERR_NULL;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(X) || misaligned(X_out) || misaligned(kept_idx) ||
       misaligned(merge_dst) || misaligned(O_opt) || misaligned(score_opt) || misaligned(order_opt) ||
       misaligned(info_opt))
     return TC_ERR_ALIGN;
   if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
-  if (pl.B == 0) return TC_OK;
   hipStream_t st = (hipStream_t)stream;
   void* O = O_opt ? O_opt : at<char>(ws, pl.off_O);
   float* S = at<float>(ws, pl.off_S);

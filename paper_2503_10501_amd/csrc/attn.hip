@@ -349,26 +349,26 @@ int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const
     const dim3 grid(pl.n_qtiles, pl.H, pl.B);
     const float sl2 = pl.scale * 1.4426950408889634f;
     if (pl.dh == 128)
-      attn_bf16_kernel<128><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
+      TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<128><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
                                                   (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
-                                                  pl.n_qtiles);
+                                                  pl.n_qtiles)));
     else
-      attn_bf16_kernel<64><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
+      TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<64><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
                                                  (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
-                                                 pl.n_qtiles);
-    if (S) attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.H, pl.n_qtiles);
+                                                 pl.n_qtiles)));
+    if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.H, pl.n_qtiles)));
   } else {
     const dim3 grid(pl.N, pl.H, pl.B);
     if (pl.dh == 128) {
-      attn_f32_rows<128><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart,
-                                              pl.L, pl.Ls, pl.N, pl.H, causal, pl.scale);
-      if (S) attn_f32_cols<128><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
-                                                                   pl.Ls, pl.N, pl.H, causal, pl.scale);
+      TC_TIMED(PK_ATTN, 0, st, (attn_f32_rows<128><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart,
+                                              pl.L, pl.Ls, pl.N, pl.H, causal, pl.scale)));
+      if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_f32_cols<128><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
+                                                                   pl.Ls, pl.N, pl.H, causal, pl.scale)));
     } else {
-      attn_f32_rows<64><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart, pl.L,
-                                             pl.Ls, pl.N, pl.H, causal, pl.scale);
-      if (S) attn_f32_cols<64><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
-                                                                  pl.Ls, pl.N, pl.H, causal, pl.scale);
+      TC_TIMED(PK_ATTN, 0, st, (attn_f32_rows<64><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart, pl.L,
+                                             pl.Ls, pl.N, pl.H, causal, pl.scale)));
+      if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_f32_cols<64><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
+                                                                  pl.Ls, pl.N, pl.H, causal, pl.scale)));
     }
   }
   return check_launch();

@@ -106,14 +106,14 @@ int launch_gram(const Plan& pl, int dtype, int eig_dtype, const void* O, void* G
   dim3 grid(nt * (nt + 1) / 2, pl.B), block(256);
   if (dtype == TC_BF16) {
     if (eig_dtype == TC_EIG_F64)
-      gram_kernel<uint16_t, double><<<grid, block, 0, st>>>((const uint16_t*)O, (double*)G, pl.N, pl.D, pl.Np);
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, double><<<grid, block, 0, st>>>((const uint16_t*)O, (double*)G, pl.N, pl.D, pl.Np)));
     else
-      gram_kernel<uint16_t, float><<<grid, block, 0, st>>>((const uint16_t*)O, (float*)G, pl.N, pl.D, pl.Np);
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, float><<<grid, block, 0, st>>>((const uint16_t*)O, (float*)G, pl.N, pl.D, pl.Np)));
   } else {
     if (eig_dtype == TC_EIG_F64)
-      gram_kernel<float, double><<<grid, block, 0, st>>>((const float*)O, (double*)G, pl.N, pl.D, pl.Np);
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<float, double><<<grid, block, 0, st>>>((const float*)O, (double*)G, pl.N, pl.D, pl.Np)));
     else
-      gram_kernel<float, float><<<grid, block, 0, st>>>((const float*)O, (float*)G, pl.N, pl.D, pl.Np);
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<float, float><<<grid, block, 0, st>>>((const float*)O, (float*)G, pl.N, pl.D, pl.Np)));
   }
   return check_launch();
 }

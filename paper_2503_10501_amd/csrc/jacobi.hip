@@ -282,15 +282,15 @@ __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* _
 template <typename T>
 static int run_jacobi(const Plan& pl, T* G, T* U, T* R, double* offpart, EigState* state, hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
-  jacobi_init_u<T><<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np);
-  jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np);
+  TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<T><<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));
+  TC_TIMED(PK_JINIT, 1, st, (jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np)));
   const dim3 gs(P, pl.B), gu(P * P + (Np / JT) * P, pl.B);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
-      jacobi_solve<T><<<gs, 256, 0, st>>>(G, R, offpart, state, Np, nblk, step);
-      jacobi_update<T><<<gu, 256, 0, st>>>(G, U, R, state, Np, nblk, step);
+      TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T><<<gs, 256, 0, st>>>(G, R, offpart, state, Np, nblk, step)));
+      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update<T><<<gu, 256, 0, st>>>(G, U, R, state, Np, nblk, step)));
     }
-    jacobi_sweep_end<<<(pl.B + 63) / 64, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, pl.B);
+    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<(pl.B + 63) / 64, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, pl.B)));
   }
   return check_launch();
 }

@@ -270,25 +270,25 @@ int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, c
   const dim3 gn((pl.kp + 3) / 4, pl.B);
   if (pl.nA > 0) {
     if (dtype == TC_BF16) {
-      rownorm_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp);
+      TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
       const dim3 gsim(((pl.nB + 63) / 64) * ((pl.nA + 63) / 64), pl.B);
-      sim_bf16_kernel<<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA,
-                                            pl.nB);
+      TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA,
+                                            pl.nB)));
     } else {
-      rownorm_kernel<float><<<gn, 256, 0, st>>>((const float*)metric, order, rnorm, pl.N, pl.D, pl.kp);
+      TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<float><<<gn, 256, 0, st>>>((const float*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
       const dim3 gsim(((pl.nB + 15) / 16) * ((pl.nA + 15) / 16), pl.B);
-      sim_f32_kernel<<<gsim, 256, 0, st>>>((const float*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB);
+      TC_TIMED(PK_SIM, 0, st, (sim_f32_kernel<<<gsim, 256, 0, st>>>((const float*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
     }
   }
   const size_t lds = ((size_t)pl.N + 2 * (size_t)pl.nB + 512) * 4;
-  assign_kernel<<<pl.B, 256, lds, st>>>(sim, order, kept_idx, merge_dst, mlist, pl.N, pl.kp, pl.kf, pl.nA, pl.nB);
+  TC_TIMED(PK_ASSIGN, 0, st, (assign_kernel<<<pl.B, 256, lds, st>>>(sim, order, kept_idx, merge_dst, mlist, pl.N, pl.kp, pl.kf, pl.nA, pl.nB)));
   const dim3 ga(pl.kf, pl.B);
   if (dtype == TC_BF16)
-    average_kernel<uint16_t><<<ga, 256, 0, st>>>((const uint16_t*)X, kept_idx, mlist, (uint16_t*)X_out, pl.N, pl.hidden,
-                                                pl.kf, pl.m);
+    TC_TIMED(PK_AVERAGE, 0, st, (average_kernel<uint16_t><<<ga, 256, 0, st>>>((const uint16_t*)X, kept_idx, mlist, (uint16_t*)X_out, pl.N, pl.hidden,
+                                                pl.kf, pl.m)));
   else
-    average_kernel<float><<<ga, 256, 0, st>>>((const float*)X, kept_idx, mlist, (float*)X_out, pl.N, pl.hidden, pl.kf,
-                                             pl.m);
+    TC_TIMED(PK_AVERAGE, 0, st, (average_kernel<float><<<ga, 256, 0, st>>>((const float*)X, kept_idx, mlist, (float*)X_out, pl.N, pl.hidden, pl.kf,
+                                             pl.m)));
   return check_launch();
 }
 

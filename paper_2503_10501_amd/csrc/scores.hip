@@ -114,9 +114,9 @@ static int run_scores(const Plan& pl, const T* G, const T* U, const EigState* st
                       int32_t* info_out, hipStream_t st) {
   int n2 = 1;
   while (n2 < pl.Np) n2 <<= 1;
-  sigma_kernel<T><<<pl.B, 256, sigma_out ? n2 * sizeof(float) : 0, st>>>(G, state, sig, sigma_out, info_out, pl.N, pl.Np);
-  ics_kernel<T><<<dim3((pl.N + 3) / 4, pl.B), 256, 0, st>>>(U, sig, sv_rtol, C_ws, C_out, pl.N, pl.Np);
-  combine_kernel<<<pl.B, 256, 0, st>>>(C_ws, S, lambda, norm_mode, E, pl.N);
+  TC_TIMED(PK_SIGMA, 0, st, (sigma_kernel<T><<<pl.B, 256, sigma_out ? n2 * sizeof(float) : 0, st>>>(G, state, sig, sigma_out, info_out, pl.N, pl.Np)));
+  TC_TIMED(PK_ICS, 0, st, (ics_kernel<T><<<dim3((pl.N + 3) / 4, pl.B), 256, 0, st>>>(U, sig, sv_rtol, C_ws, C_out, pl.N, pl.Np)));
+  TC_TIMED(PK_COMBINE, 0, st, (combine_kernel<<<pl.B, 256, 0, st>>>(C_ws, S, lambda, norm_mode, E, pl.N)));
   return check_launch();
 }
 

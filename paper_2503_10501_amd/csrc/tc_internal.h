@@ -60,6 +60,21 @@ int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st);
 int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, const int32_t* order, void* X_out,
                  int32_t* kept_idx, int32_t* merge_dst, float* rnorm, float* sim, int32_t* mlist, hipStream_t st);
 
+// ---- optional per-kernel timing (only active inside tc_profile_compress) ----------------------
+enum ProfKind {
+  PK_ATTN = 0, PK_ATTN_REDUCE, PK_GRAM, PK_JINIT, PK_JSOLVE, PK_JUPDATE, PK_JSWEEPEND, PK_SIGMA, PK_ICS, PK_COMBINE,
+  PK_TOPK, PK_ROWNORM, PK_SIM, PK_ASSIGN, PK_AVERAGE, PK_COUNT
+};
+static_assert((int)PK_COUNT == (int)TC_PROF_KINDS, "internal and public kernel kinds must match");
+void prof_begin(int kind, int tag, hipStream_t st);  // no-ops unless a profile run is active on this thread
+void prof_end(hipStream_t st);
+#define TC_TIMED(kind, tag, st, ...) \
+  do {                               \
+    tc::prof_begin(kind, tag, st);   \
+    __VA_ARGS__;                     \
+    tc::prof_end(st);                \
+  } while (0)
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? TC_OK : TC_ERR_HIP; }
 
 // ---- small device helpers ---------------------------------------------------------------

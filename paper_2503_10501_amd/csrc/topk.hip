@@ -40,7 +40,7 @@ int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st) 
   int n2 = 64;
   while (n2 < pl.N) n2 <<= 1;
   const int threads = n2 / 2 < 1024 ? (n2 / 2 < 64 ? 64 : n2 / 2) : 1024;
-  topk_kernel<<<pl.B, threads, (size_t)n2 * 8, st>>>(E, order, pl.N, n2, pl.kp);
+  TC_TIMED(PK_TOPK, 0, st, (topk_kernel<<<pl.B, threads, (size_t)n2 * 8, st>>>(E, order, pl.N, n2, pl.kp)));
   return check_launch();
 }
 
