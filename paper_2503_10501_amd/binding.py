@@ -19,7 +19,7 @@ TC_EIG_F64, TC_EIG_F32 = 0, 1
 
 SYMBOLS = ("tc_workspace_bytes", "tc_status_string", "tc_attn_output", "tc_ipgs_score", "tc_select_topk",
            "tc_merge", "tc_compress", "tc_profile_compress")
-PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_sweep_end",
+PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_update_u", "jacobi_sweep_end",
               "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average")
 
 

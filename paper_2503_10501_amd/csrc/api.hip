@@ -33,7 +33,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.esize = p->dtype == TC_BF16 ? 2 : 4;
   q.tsize = p->eig_dtype == TC_EIG_F64 ? 8 : 4;
   q.max_sweeps = p->jacobi_max_sweeps > 0 ? p->jacobi_max_sweeps : 30;
-  q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 1e-10 : 2e-6);
+  q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 1e-7 : 3e-6);
   q.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)q.dh);
 
   size_t off = 0;
@@ -43,7 +43,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.off_S = take(B * N * 4);
   q.off_Spart = take(B * q.H * (size_t)(q.n_qtiles > 2 ? q.n_qtiles : 2) * N * 4);  // also holds the float path's (max, sum) pairs
   q.off_G = take(B * Np * Np * q.tsize);
-  q.off_U = take(B * Np * Np * q.tsize);
+  q.off_U = take(B * Np * Np * 4);  // eigenvectors are kept in float32
   q.off_R = take(B * q.P * JT * JT * q.tsize);
   q.off_offpart = take(B * (size_t)q.P * q.steps * 8);
   q.off_state = take(B * sizeof(EigState));

@@ -10,6 +10,8 @@
 // image, with the iteration count fixed on the host and converged images skipped on the device.
 // On exit diag(G) holds the eigenvalues sigma_i^2 and U the left singular vectors of O
 // (Section 3.3.1: Z = U Sigma V^T  =>  Z Z^T = U Sigma^2 U^T).
+#include <mutex>
+
 #include "tc_internal.h"
 
 namespace tc {
@@ -38,12 +40,11 @@ template <> struct MM<float> {
 constexpr int SLD = JT + 1;  // padded leading dimension of the LDS tiles
 
 // ---------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void jacobi_init_u(T* __restrict__ U, int Np) {
+__global__ __launch_bounds__(256) void jacobi_init_u(float* __restrict__ U, int Np) {
   const size_t n2 = (size_t)Np * Np;
-  T* Ub = U + (size_t)blockIdx.y * n2;
+  float* Ub = U + (size_t)blockIdx.y * n2;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += (size_t)gridDim.x * blockDim.x)
-    Ub[i] = (i / Np == i % Np) ? T(1) : T(0);
+    Ub[i] = (i / Np == i % Np) ? 1.f : 0.f;
 }
 
 template <typename T>
@@ -67,145 +68,251 @@ __global__ __launch_bounds__(1024) void jacobi_init_state(const T* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------
-// One workgroup per block pair: load the 64x64 subproblem, one cyclic sweep of rotations, emit R.
+// Plane rotation that annihilates a_ij of [[a_ii a_ij][a_ij a_jj]] (i < j): J = [[c s][-s c]].
+// tan(theta) only has to be accurate to single precision (a less exact angle leaves a residual of
+// relative size 1e-7, removed by the next sweep), so it comes from the hardware reciprocal and
+// square-root approximations; c is then refined to full precision so that c^2 + s^2 = 1 holds to
+// the rounding of T and the accumulated transformation stays orthogonal.
+// Of the two rotations that annihilate a_ij the one that leaves the larger diagonal entry at the
+// smaller index is taken (it differs from the small-angle one by a quarter turn): keeping the
+// diagonal sorted while it converges saves sweeps.
+__device__ inline void rotation(double aii, double ajj, double aij, double* c, double* s) {
+  double t = 0.0;
+  if (aij != 0.0) {
+    const double z = (ajj - aii) * __builtin_amdgcn_rcp(2.0 * aij);
+    const double az = fabs(z);
+    if (az < 1e150) {  // false for inf and NaN: no rotation
+      t = __builtin_amdgcn_rcp(az + __builtin_amdgcn_sqrt(1.0 + az * az));
+      t = z < 0.0 ? -t : t;
+    }
+  }
+  const double x = 1.0 + t * t;  // in [1, 2]
+  double y = __builtin_amdgcn_rsq(x);
+  y = y * (1.5 - 0.5 * x * y * y);
+  y = y * (1.5 - 0.5 * x * y * y);
+  const double cc = y, ss = y * t;
+  const bool swap = (aii - t * aij) < (ajj + t * aij);  // new a_ii < new a_jj
+  *c = swap ? -ss : cc;
+  *s = swap ? cc : ss;
+}
+__device__ inline void rotation(float aii, float ajj, float aij, float* c, float* s) {
+  float t = 0.f;
+  if (aij != 0.f) {
+    const float z = (ajj - aii) * __builtin_amdgcn_rcpf(2.f * aij);
+    const float az = fabsf(z);
+    if (az < 1e18f) {
+      t = __builtin_amdgcn_rcpf(az + __builtin_amdgcn_sqrtf(1.f + az * az));
+      t = z < 0.f ? -t : t;
+    }
+  }
+  const float x = 1.f + t * t;
+  float y = __builtin_amdgcn_rsqf(x);
+  y = y * (1.5f - 0.5f * x * y * y);
+  const float cc = y, ss = y * t;
+  const bool swap = (aii - t * aij) < (ajj + t * aij);
+  *c = swap ? -ss : cc;
+  *s = swap ? cc : ss;
+}
+
+// One workgroup (8 wavefronts) per block pair: load the 64x64 subproblem, one cyclic sweep of plane
+// rotations in the round-robin order, emit the accumulated orthogonal matrix R.
+//
+// The 64 indices sit in 32 "seats" of a round-robin tournament: seat i of step st holds the indices
+// top = (st+i) mod 63 (63 for seat 0) and bottom = (st-i) mod 63, every index advances by one per
+// step, and the 32 seats of a step are its 32 disjoint rotations (the pairs round_robin_pair()
+// enumerates).  A rotation is stored in seat orientation: top' = c top - s bottom,
+// bottom' = s top + c bottom.
+//   * S is symmetric and lives in LDS, element {x,y} stored once at S[min][max].  A step acts on it
+//     as 2x2 blocks (rows of seat I) x (columns of seat J), I <= J: 528 blocks, one per lane, the
+//     seat pair of a lane fixed for the whole kernel.
+//   * R never touches LDS for arithmetic: lane r holds row r of R in registers with the columns in
+//     seat order -- wavefront w owns seats 4w..4w+3 -- so every step rotates fixed register pairs;
+//     afterwards the columns move one seat along the tournament cycle, a register renaming inside a
+//     wavefront plus one column handed to each neighbouring wavefront through a small LDS buffer.
+//     After 63 steps the seats are back in their starting order.
+//   * Per step: lanes 0..31 of wavefront 0 compute the 32 rotations (barrier), all lanes apply
+//     them (barrier).  The kernel is bound by vector-ALU issue, so index and address arithmetic is
+//     kept to a minimum.
+constexpr int SOLVE_WAVES = 8;
+constexpr int SEATS = JB / SOLVE_WAVES;  // seats per wavefront
+constexpr int N_BLOCKS = JB * (JB + 1) / 2;
+
+__device__ inline int next63(int x) { return x == 62 ? 0 : x + 1; }
+
 template <typename T>
-__global__ __launch_bounds__(256) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
-                                                    double* __restrict__ offpart, const EigState* __restrict__ state,
-                                                    int Np, int nblk, int step) {
-  const int b = blockIdx.y, pair = blockIdx.x, P = nblk / 2;
+__global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
+                                                                 double* __restrict__ offpart,
+                                                                 const EigState* __restrict__ state, int Np, int nblk,
+                                                                 int step, int img0, int inner_steps) {
+  const int b = img0 + blockIdx.y, pair = blockIdx.x, P = nblk / 2;
   if (state[b].done) return;
   __shared__ T S[JT][SLD];
-  __shared__ T Rm[JT][SLD];
+  __shared__ T xtop[SOLVE_WAVES][JT], xbot[SOLVE_WAVES][JT];
   __shared__ T rc[JB], rs[JB];
-  __shared__ int ri[JB], rj[JB];
-  __shared__ double red[4];
+  __shared__ double red[SOLVE_WAVES];
   int p, q;
   round_robin_pair(nblk, step, pair, &p, &q);
   const T* Gb = G + (size_t)b * Np * Np;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   {
-    const int c = tid & 63, gc = (c < JB ? p * JB + c : q * JB + c - JB);
+    const int c = lane, gc = (c < JB ? p * JB + c : q * JB + c - JB);
     double off = 0.0;
-    for (int r = tid >> 6; r < JT; r += 4) {
+    for (int r = wave; r < JT; r += SOLVE_WAVES) {
       const int gr = (r < JB ? p * JB + r : q * JB + r - JB);
       const T v = Gb[(size_t)gr * Np + gc];
-      S[r][c] = v;
-      Rm[r][c] = (r == c) ? T(1) : T(0);
+      S[r][c] = v;  // only r <= c is used afterwards
       const double dv = (double)v;
       if ((r < JB) != (c < JB)) off += dv * dv;                       // the G_pq / G_qp blocks
       else if (r != c) off += dv * dv / (double)(nblk - 1);           // inside G_pp, G_qq (seen nblk-1 times)
     }
     off = wave_sum(off);
-    if ((tid & 63) == 0) red[tid >> 6] = off;
+    if (lane == 0) red[wave] = off;
+  }
+  // R = I in seat order (step 0: top_i = i, top_0 = 63, bottom_i = (63 - i) mod 63)
+  T rtop[SEATS], rbot[SEATS];
+#pragma unroll
+  for (int k = 0; k < SEATS; k++) {
+    const int i = SEATS * wave + k;
+    rtop[k] = (lane == (i == 0 ? 63 : i)) ? T(1) : T(0);
+    rbot[k] = (lane == (63 - i) % 63) ? T(1) : T(0);
+  }
+  // blocks of this lane: task tid (all 512 lanes) and, on the last wavefront, task 512 + lane
+  int tI[2], bI[2], tJ[2], bJ[2], sI[2], sJ[2];
+  bool act[2];
+#pragma unroll
+  for (int g = 0; g < 2; g++) {
+    const int t = g == 0 ? tid : 512 + lane;
+    act[g] = g == 0 || (wave == SOLVE_WAVES - 1 && t < N_BLOCKS);
+    int I = 0, J = act[g] ? t : 0;  // row I of the upper triangle holds JB - I blocks
+    while (J >= JB - I) { J -= JB - I; I++; }
+    J += I;
+    sI[g] = I; sJ[g] = J;
+    tI[g] = I == 0 ? 63 : I; bI[g] = (63 - I) % 63;
+    tJ[g] = J == 0 ? 63 : J; bJ[g] = (63 - J) % 63;
+  }
+  int rt = lane == 0 ? 63 : (lane & 31), rb = (63 - (lane & 31)) % 63;  // seat lane%32, for the rotations
+  __syncthreads();
+  if (tid == 0) {
+    double tot = 0.0;
+    for (int w = 0; w < SOLVE_WAVES; w++) tot += red[w];
+    offpart[((size_t)b * (nblk - 1) + step) * P + pair] = tot;
+  }
+
+  for (int st = 0; st < inner_steps; st++) {  // JT - 1 steps bring the seats back to their starting order
+    if (tid < JB) {
+      const int a = min(rt, rb), bq = max(rt, rb);
+      T c, s;
+      rotation(S[a][a], S[bq][bq], S[a][bq], &c, &s);
+      rc[tid] = c;
+      rs[tid] = rt > rb ? -s : s;  // seat orientation: the top index is the larger one
+    }
+    if (st > 0) {  // columns handed over by the neighbours at the end of the previous step
+      if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
+      if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+    }
+    __syncthreads();
+    // ---- S <- J^T S J -----------------------------------------------------------------------------
+#pragma unroll
+    for (int g = 0; g < 2; g++) {
+      if (act[g]) {
+        const T cI = rc[sI[g]], zI = rs[sI[g]], cJ = rc[sJ[g]], zJ = rs[sJ[g]];
+        T* ptt = &S[min(tI[g], tJ[g])][max(tI[g], tJ[g])];
+        T* ptb = &S[min(tI[g], bJ[g])][max(tI[g], bJ[g])];
+        T* pbt = &S[min(bI[g], tJ[g])][max(bI[g], tJ[g])];
+        T* pbb = &S[min(bI[g], bJ[g])][max(bI[g], bJ[g])];
+        const T ett = *ptt, etb = *ptb, ebt = *pbt, ebb = *pbb;
+        const T ftt = cI * ett - zI * ebt, fbt = zI * ett + cI * ebt;  // rows of seat I
+        const T ftb = cI * etb - zI * ebb, fbb = zI * etb + cI * ebb;
+        *ptt = cJ * ftt - zJ * ftb;                                     // columns of seat J
+        *ptb = zJ * ftt + cJ * ftb;
+        *pbt = cJ * fbt - zJ * fbb;
+        *pbb = zJ * fbt + cJ * fbb;
+      }
+      if (tI[g] != 63) tI[g] = next63(tI[g]);
+      bI[g] = next63(bI[g]);
+      if (tJ[g] != 63) tJ[g] = next63(tJ[g]);
+      bJ[g] = next63(bJ[g]);
+    }
+    // ---- R <- R J on this wavefront's seats -------------------------------------------------------
+#pragma unroll
+    for (int k = 0; k < SEATS; k++) {
+      const T c = rc[SEATS * wave + k], z = rs[SEATS * wave + k];
+      const T x = rtop[k], y = rbot[k];
+      rtop[k] = c * x - z * y;
+      rbot[k] = z * x + c * y;
+    }
+    // move the columns one seat along the cycle: tops towards seat 1, bottoms away from seat 0
+    {
+      const T out_top = rtop[0], out_bot = rbot[SEATS - 1], top1 = rtop[1];
+      if (wave == 0) {
+#pragma unroll
+        for (int k = 1; k < SEATS - 1; k++) rtop[k] = rtop[k + 1];  // seat 0's top (index 63) never moves
+      } else {
+#pragma unroll
+        for (int k = 0; k < SEATS - 1; k++) rtop[k] = rtop[k + 1];
+      }
+      if (wave == SOLVE_WAVES - 1) rtop[SEATS - 1] = rbot[SEATS - 1];  // top_31 <- bottom_31
+#pragma unroll
+      for (int k = SEATS - 1; k > 0; k--) rbot[k] = rbot[k - 1];
+      if (wave == 0) rbot[0] = top1;                                    // bottom_0 <- top_1
+      if (wave > 0) xtop[wave][lane] = out_top;                         // becomes the last top of wave-1
+      if (wave < SOLVE_WAVES - 1) xbot[wave][lane] = out_bot;           // becomes the first bottom of wave+1
+    }
+    if (rt != 63) rt = next63(rt);
+    rb = next63(rb);
+    __syncthreads();  // S, the rotation table and the hand-over buffers are free for the next step
+  }
+  if (inner_steps > 0) {
+    if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
+    if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+  }
+  // after JT - 1 steps the seats are back in their step-0 order; stage R through LDS for
+  // row-contiguous stores
+#pragma unroll
+  for (int k = 0; k < SEATS; k++) {
+    const int i = SEATS * wave + k;
+    S[lane][i == 0 ? 63 : i] = rtop[k];
+    S[lane][(63 - i) % 63] = rbot[k];
   }
   __syncthreads();
-  if (tid == 0) offpart[((size_t)b * (nblk - 1) + step) * P + pair] = red[0] + red[1] + red[2] + red[3];
-
-  for (int st = 0; st < JT - 1; st++) {
-    if (tid < JB) {
-      int i, j;
-      round_robin_pair(JT, st, tid, &i, &j);
-      const T aii = S[i][i], ajj = S[j][j], aij = S[i][j];
-      T c = T(1), s = T(0);
-      if (aij != T(0)) {
-        const T zeta = (ajj - aii) / (T(2) * aij);
-        const T az = fabs(zeta);
-        T t = T(1) / (az + sqrt(T(1) + az * az));  // az = inf gives t = 0
-        if (!(az < T(1e150))) t = T(0);            // also catches NaN
-        if (zeta < T(0)) t = -t;
-        c = T(1) / sqrt(T(1) + t * t);
-        s = c * t;
-      }
-      rc[tid] = c; rs[tid] = s; ri[tid] = i; rj[tid] = j;
-    }
-    __syncthreads();
-    // S <- J^T S J on 2x2 blocks (rows of pair I) x (columns of pair J); R <- R J
-    {
-      const int J = tid & 31;
-      const int jc0 = ri[J], jc1 = rj[J];
-      const T cJ = rc[J], sJ = rs[J];
-#pragma unroll
-      for (int u = 0; u < 4; u++) {
-        const int I = (tid >> 5) + 8 * u;
-        const int ir0 = ri[I], ir1 = rj[I];
-        const T cI = rc[I], sI = rs[I];
-        const T a = S[ir0][jc0], bb = S[ir0][jc1], cc = S[ir1][jc0], d = S[ir1][jc1];
-        const T a1 = cI * a - sI * cc, b1 = cI * bb - sI * d, c1 = sI * a + cI * cc, d1 = sI * bb + cI * d;
-        S[ir0][jc0] = cJ * a1 - sJ * b1;
-        S[ir0][jc1] = sJ * a1 + cJ * b1;
-        S[ir1][jc0] = cJ * c1 - sJ * d1;
-        S[ir1][jc1] = sJ * c1 + cJ * d1;
-      }
-#pragma unroll
-      for (int u = 0; u < 8; u++) {
-        const int r = (tid >> 5) + 8 * u;
-        const T x = Rm[r][jc0], y = Rm[r][jc1];
-        Rm[r][jc0] = cJ * x - sJ * y;
-        Rm[r][jc1] = sJ * x + cJ * y;
-      }
-    }
-    __syncthreads();
-  }
   T* Rb = R + ((size_t)b * P + pair) * JT * JT;
-  for (int e = tid; e < JT * JT; e += 256) Rb[e] = Rm[e >> 6][e & 63];
+  for (int e = tid; e < JT * JT; e += 64 * SOLVE_WAVES) Rb[e] = S[e >> 6][e & 63];
 }
 
 // ---------------------------------------------------------------------------------------
-// Tile update.  blockIdx.x < P*P: tile (I,J) of G becomes R_I^T G_IJ R_J.  The remaining
-// (Np/64)*P workgroups update a 64-row slab of U's columns of pair J: U_J <- U_J R_J.
+// Tile update of G.  One workgroup per pair of block pairs I <= J: the 64x64 tile spanned by the
+// rows of pair I and the columns of pair J becomes R_I^T G_IJ R_J; the mirror tile (J,I) receives the
+// transpose, so G stays exactly symmetric and only the upper triangle of tiles is computed.
 template <typename T>
-__global__ __launch_bounds__(256) void jacobi_update(T* __restrict__ G, T* __restrict__ U, const T* __restrict__ R,
-                                                     const EigState* __restrict__ state, int Np, int nblk, int step) {
+__global__ __launch_bounds__(256) void jacobi_update_g(T* __restrict__ G, const T* __restrict__ R,
+                                                       const EigState* __restrict__ state, int Np, int nblk, int step,
+                                                       int img0) {
   typedef typename MM<T>::acc_t acc_t;
-  const int b = blockIdx.y, P = nblk / 2;
+  const int b = img0 + blockIdx.y, P = nblk / 2;
   if (state[b].done) return;
   __shared__ T X[JT][SLD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  const bool isG = (int)blockIdx.x < P * P;
-  int I, J;
-  T* M;
-  int rowbase[2];  // global row of local rows 0..31 and 32..63
-  if (isG) {
-    I = blockIdx.x / P; J = blockIdx.x % P;
-    M = G + (size_t)b * Np * Np;
-    int p, q;
-    round_robin_pair(nblk, step, I, &p, &q);
-    rowbase[0] = p * JB; rowbase[1] = q * JB;
-  } else {
-    const int t = blockIdx.x - P * P;
-    I = -1; J = t % P;
-    M = U + (size_t)b * Np * Np;
-    rowbase[0] = (t / P) * JT; rowbase[1] = rowbase[0] + JB;
-  }
-  int colbase[2];
-  {
-    int p, q;
-    round_robin_pair(nblk, step, J, &p, &q);
-    colbase[0] = p * JB; colbase[1] = q * JB;
-  }
+  int I = 0, J = blockIdx.x;  // decode the upper-triangular tile index: row I holds P - I tiles
+  while (J >= P - I) { J -= P - I; I++; }
+  J += I;
+  T* M = G + (size_t)b * Np * Np;
+  int rowbase[2], colbase[2];
+  round_robin_pair(nblk, step, I, &rowbase[0], &rowbase[1]);
+  round_robin_pair(nblk, step, J, &colbase[0], &colbase[1]);
+  rowbase[0] *= JB; rowbase[1] *= JB; colbase[0] *= JB; colbase[1] *= JB;
+  const T* RI = R + ((size_t)b * P + I) * JT * JT;
   const T* RJ = R + ((size_t)b * P + J) * JT * JT;
-  // Right factor as matrix-core B fragments kept in registers: this wave needs R_J[:, wc*32 .. +32).
-  T rjf[16][2];
+  // Left factor R_I^T as matrix-core A fragments: A[i][k] = R_I[k][i], rows i in wr*32 .. +32.
+  T rf[16][2];
 #pragma unroll
   for (int ks = 0; ks < 16; ks++) {
     const int k = 4 * ks + (lane >> 4);
-    rjf[ks][0] = RJ[k * JT + wc * 32 + (lane & 15)];
-    rjf[ks][1] = RJ[k * JT + wc * 32 + 16 + (lane & 15)];
+    rf[ks][0] = RI[k * JT + wr * 32 + (lane & 15)];
+    rf[ks][1] = RI[k * JT + wr * 32 + 16 + (lane & 15)];
   }
-  // Left factor R_I^T as A fragments: A[i][k] = R_I[k][i], rows i in wr*32 .. +32.
-  T rif[16][2];
-  if (isG) {
-    const T* RI = R + ((size_t)b * P + I) * JT * JT;
-#pragma unroll
-    for (int ks = 0; ks < 16; ks++) {
-      const int k = 4 * ks + (lane >> 4);
-      rif[ks][0] = RI[k * JT + wr * 32 + (lane & 15)];
-      rif[ks][1] = RI[k * JT + wr * 32 + 16 + (lane & 15)];
-    }
-  }
-  // Gather the tile: lanes 0..15 read 16 consecutive columns of one row.
-  {
+  {  // gather the tile: lanes 0..15 read 16 consecutive columns of one row
     const int c = (lane & 15) + 16 * wave;
     const int gc = colbase[c >> 5] + (c & 31);
 #pragma unroll
@@ -216,32 +323,32 @@ __global__ __launch_bounds__(256) void jacobi_update(T* __restrict__ G, T* __res
   }
   __syncthreads();
   acc_t acc[2][2];
-  if (isG) {
-    // W = R_I^T X
 #pragma unroll
-    for (int i = 0; i < 2; i++)
+  for (int i = 0; i < 2; i++)
 #pragma unroll
-      for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
+    for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
+  // W = R_I^T X; each used fragment register is refilled with the right factor R_J[:, wc*32 .. +32)
 #pragma unroll
-    for (int ks = 0; ks < 16; ks++) {
-      const int k = 4 * ks + (lane >> 4);
-      const T b0 = X[k][wc * 32 + (lane & 15)], b1 = X[k][wc * 32 + 16 + (lane & 15)];
-      acc[0][0] = MM<T>::mma(rif[ks][0], b0, acc[0][0]);
-      acc[0][1] = MM<T>::mma(rif[ks][0], b1, acc[0][1]);
-      acc[1][0] = MM<T>::mma(rif[ks][1], b0, acc[1][0]);
-      acc[1][1] = MM<T>::mma(rif[ks][1], b1, acc[1][1]);
-    }
-    __syncthreads();  // every wave has finished reading X
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int nt = 0; nt < 2; nt++)
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-          X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + nt * 16 + (lane & 15)] = acc[mt][nt][j];
-    __syncthreads();
+  for (int ks = 0; ks < 16; ks++) {
+    const int k = 4 * ks + (lane >> 4);
+    const T b0 = X[k][wc * 32 + (lane & 15)], b1 = X[k][wc * 32 + 16 + (lane & 15)];
+    acc[0][0] = MM<T>::mma(rf[ks][0], b0, acc[0][0]);
+    acc[0][1] = MM<T>::mma(rf[ks][0], b1, acc[0][1]);
+    acc[1][0] = MM<T>::mma(rf[ks][1], b0, acc[1][0]);
+    acc[1][1] = MM<T>::mma(rf[ks][1], b1, acc[1][1]);
+    rf[ks][0] = RJ[k * JT + wc * 32 + (lane & 15)];
+    rf[ks][1] = RJ[k * JT + wc * 32 + 16 + (lane & 15)];
   }
-  // Y = X R_J
+  __syncthreads();  // every wave has finished reading X
+#pragma unroll
+  for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+      for (int j = 0; j < 4; j++)
+        X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + nt * 16 + (lane & 15)] = acc[mt][nt][j];
+  __syncthreads();
+  // Y = W R_J
 #pragma unroll
   for (int i = 0; i < 2; i++)
 #pragma unroll
@@ -250,11 +357,12 @@ __global__ __launch_bounds__(256) void jacobi_update(T* __restrict__ G, T* __res
   for (int ks = 0; ks < 16; ks++) {
     const int k = 4 * ks + (lane >> 4);
     const T a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
-    acc[0][0] = MM<T>::mma(a0, rjf[ks][0], acc[0][0]);
-    acc[0][1] = MM<T>::mma(a0, rjf[ks][1], acc[0][1]);
-    acc[1][0] = MM<T>::mma(a1, rjf[ks][0], acc[1][0]);
-    acc[1][1] = MM<T>::mma(a1, rjf[ks][1], acc[1][1]);
+    acc[0][0] = MM<T>::mma(a0, rf[ks][0], acc[0][0]);
+    acc[0][1] = MM<T>::mma(a0, rf[ks][1], acc[0][1]);
+    acc[1][0] = MM<T>::mma(a1, rf[ks][0], acc[1][0]);
+    acc[1][1] = MM<T>::mma(a1, rf[ks][1], acc[1][1]);
   }
+  if (I != J) __syncthreads();  // W fully consumed before Y overwrites it (uniform branch)
 #pragma unroll
   for (int mt = 0; mt < 2; mt++)
 #pragma unroll
@@ -264,14 +372,89 @@ __global__ __launch_bounds__(256) void jacobi_update(T* __restrict__ G, T* __res
         const int r = wr * 32 + mt * 16 + MM<T>::row(j, lane);
         const int c = wc * 32 + nt * 16 + (lane & 15);
         M[(size_t)(rowbase[r >> 5] + (r & 31)) * Np + colbase[c >> 5] + (c & 31)] = acc[mt][nt][j];
+        if (I != J) X[r][c] = acc[mt][nt][j];
+      }
+  if (I != J) {
+    __syncthreads();
+    // mirror tile (J,I) = Y^T, written row by row (lanes 0..15 cover 16 consecutive columns)
+    const int c = (lane & 15) + 16 * wave;  // column of the mirror tile = row of Y
+    const int gc = rowbase[c >> 5] + (c & 31);
+#pragma unroll
+    for (int it = 0; it < 16; it++) {
+      const int r = (lane >> 4) + 4 * it;   // row of the mirror tile = column of Y
+      M[(size_t)(colbase[r >> 5] + (r & 31)) * Np + gc] = X[c][r];
+    }
+  }
+}
+
+// Eigenvector update in float32: a 64-row slab of the columns of pair J, U_J <- U_J R_J.
+// U only feeds Eq. 3-6, where an absolute error of 1e-6 per entry is far below the tolerance, so it
+// is stored and multiplied in float32 whatever the type of G; R is rounded to float32 on load.
+template <typename T>
+__global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, const T* __restrict__ R,
+                                                       const EigState* __restrict__ state, int Np, int nblk, int step,
+                                                       int img0) {
+  const int b = img0 + blockIdx.y, P = nblk / 2;
+  if (state[b].done) return;
+  __shared__ float X[JT][SLD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 1, wc = wave & 1;
+  const int J = blockIdx.x % P, slab = blockIdx.x / P;
+  float* M = U + (size_t)b * Np * Np;
+  int colbase[2];
+  round_robin_pair(nblk, step, J, &colbase[0], &colbase[1]);
+  colbase[0] *= JB; colbase[1] *= JB;
+  const int row0 = slab * JT;
+  const T* RJ = R + ((size_t)b * P + J) * JT * JT;
+  float rf[16][2];
+#pragma unroll
+  for (int ks = 0; ks < 16; ks++) {
+    const int k = 4 * ks + (lane >> 4);
+    rf[ks][0] = (float)RJ[k * JT + wc * 32 + (lane & 15)];
+    rf[ks][1] = (float)RJ[k * JT + wc * 32 + 16 + (lane & 15)];
+  }
+  {
+    const int c = (lane & 15) + 16 * wave;
+    const int gc = colbase[c >> 5] + (c & 31);
+#pragma unroll
+    for (int it = 0; it < 16; it++) {
+      const int r = (lane >> 4) + 4 * it;
+      X[r][c] = M[(size_t)(row0 + r) * Np + gc];
+    }
+  }
+  __syncthreads();
+  f4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; i++)
+#pragma unroll
+    for (int j = 0; j < 2; j++) acc[i][j] = f4{0, 0, 0, 0};
+#pragma unroll
+  for (int ks = 0; ks < 16; ks++) {
+    const int k = 4 * ks + (lane >> 4);
+    const float a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
+    acc[0][0] = MM<float>::mma(a0, rf[ks][0], acc[0][0]);
+    acc[0][1] = MM<float>::mma(a0, rf[ks][1], acc[0][1]);
+    acc[1][0] = MM<float>::mma(a1, rf[ks][0], acc[1][0]);
+    acc[1][1] = MM<float>::mma(a1, rf[ks][1], acc[1][1]);
+  }
+#pragma unroll
+  for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+    for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const int r = wr * 32 + mt * 16 + MM<float>::row(j, lane);
+        const int c = wc * 32 + nt * 16 + (lane & 15);
+        M[(size_t)(row0 + r) * Np + colbase[c >> 5] + (c & 31)] = acc[mt][nt][j];
       }
 }
 
 // ---------------------------------------------------------------------------------------
 __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* __restrict__ state, int count,
-                                 double tol, int B) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B || state[b].done) return;
+                                 double tol, int img0, int nimg) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = img0 + i;
+  if (i >= nimg || state[b].done) return;
   const double* op = offpart + (size_t)b * count;
   double s = 0.0;
   for (int i = 0; i < count; i++) s += op[i];  // fixed order: the decision is reproducible
@@ -279,25 +462,88 @@ __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* _
   if (s <= tol * tol * state[b].norm2) state[b].done = 1;
 }
 
+// ---------------------------------------------------------------------------------------
+// Helper streams.  The rotation kernel is bound by the vector ALUs and by latency, the tile updates
+// by the matrix cores, and images are independent, so the batch is cut into up to MAX_GROUPS groups
+// whose step sequences run on different streams and overlap on the GPU.  The helper streams are
+// created once per device and kept for the life of the process (no device memory); the events that
+// tie them to the caller's stream live only for the duration of one call.
+constexpr int MAX_GROUPS = 4;
+struct StreamPool {
+  hipStream_t s[MAX_GROUPS - 1];
+  bool ok = false;
+};
+static std::mutex g_pool_mutex;
+static StreamPool g_pools[64];
+
+static StreamPool* helper_streams() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(g_pool_mutex);
+  StreamPool& pool = g_pools[dev];
+  if (!pool.ok) {
+    for (int i = 0; i < MAX_GROUPS - 1; i++)
+      if (hipStreamCreateWithFlags(&pool.s[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
+    pool.ok = true;
+  }
+  return &pool;
+}
+
 template <typename T>
-static int run_jacobi(const Plan& pl, T* G, T* U, T* R, double* offpart, EigState* state, hipStream_t st) {
+static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart, EigState* state, int img0, int nimg,
+                          hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
-  TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<T><<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));
-  TC_TIMED(PK_JINIT, 1, st, (jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np)));
-  const dim3 gs(P, pl.B), gu(P * P + (Np / JT) * P, pl.B);
+  const dim3 gs(P, nimg), gg(P * (P + 1) / 2, nimg), gu((Np / JT) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
-      TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T><<<gs, 256, 0, st>>>(G, R, offpart, state, Np, nblk, step)));
-      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update<T><<<gu, 256, 0, st>>>(G, U, R, state, Np, nblk, step)));
+      TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
+      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0)));
+      TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0)));
     }
-    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<(pl.B + 63) / 64, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, pl.B)));
+    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<(nimg + 63) / 64, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, img0, nimg)));
   }
+}
+
+template <typename T>
+static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, EigState* state, hipStream_t st) {
+  const int Np = pl.Np;
+  TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));
+  TC_TIMED(PK_JINIT, 1, st, (jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np)));
+  int groups = pl.B >= 4 * MAX_GROUPS ? MAX_GROUPS : (pl.B >= 4 ? 2 : 1);
+  if (profiling_active()) groups = 1;  // per-kernel timing wants kernels that run alone
+  StreamPool* pool = groups > 1 ? helper_streams() : nullptr;
+  hipEvent_t fork = nullptr, join[MAX_GROUPS - 1] = {};
+  if (pool) {
+    bool ok = hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
+    for (int g = 0; ok && g < groups - 1; g++) ok = hipEventCreateWithFlags(&join[g], hipEventDisableTiming) == hipSuccess;
+    if (!ok) pool = nullptr;
+  }
+  if (!pool) groups = 1;
+  if (groups > 1) {
+    (void)hipEventRecord(fork, st);
+    for (int g = 0; g < groups - 1; g++) (void)hipStreamWaitEvent(pool->s[g], fork, 0);
+  }
+  const int per = (pl.B + groups - 1) / groups;
+  for (int g = 0; g < groups; g++) {
+    const int img0 = g * per, nimg = pl.B - img0 < per ? pl.B - img0 : per;
+    if (nimg <= 0) continue;
+    enqueue_group<T>(pl, G, U, R, offpart, state, img0, nimg, g == 0 ? st : pool->s[g - 1]);
+  }
+  if (groups > 1) {
+    for (int g = 0; g < groups - 1; g++) {
+      (void)hipEventRecord(join[g], pool->s[g]);
+      (void)hipStreamWaitEvent(st, join[g], 0);
+    }
+  }
+  if (fork) (void)hipEventDestroy(fork);  // released by the runtime once the recorded work has finished
+  for (int g = 0; g < MAX_GROUPS - 1; g++)
+    if (join[g]) (void)hipEventDestroy(join[g]);
   return check_launch();
 }
 
 int launch_jacobi(const Plan& pl, int eig_dtype, void* G, void* U, void* R, double* offpart, EigState* state,
                   hipStream_t st) {
-  if (eig_dtype == TC_EIG_F64) return run_jacobi<double>(pl, (double*)G, (double*)U, (double*)R, offpart, state, st);
+  if (eig_dtype == TC_EIG_F64) return run_jacobi<double>(pl, (double*)G, (float*)U, (double*)R, offpart, state, st);
   return run_jacobi<float>(pl, (float*)G, (float*)U, (float*)R, offpart, state, st);
 }
 

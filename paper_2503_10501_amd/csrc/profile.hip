@@ -9,6 +9,8 @@ struct ProfRecord { int kind, tag; hipEvent_t start, stop; };
 struct Profiler { std::vector<ProfRecord> recs; };
 static thread_local Profiler* g_prof = nullptr;
 
+bool profiling_active() { return g_prof != nullptr; }
+
 void prof_begin(int kind, int tag, hipStream_t st) {
   if (!g_prof) return;
   ProfRecord r{kind, tag, nullptr, nullptr};

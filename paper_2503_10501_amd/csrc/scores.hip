@@ -41,8 +41,7 @@ __global__ __launch_bounds__(256) void sigma_kernel(const T* __restrict__ G, con
 }
 
 // C(x) = sum_i |U[x][i]| sigma_i, one wavefront per token, float64 accumulation.
-template <typename T>
-__global__ __launch_bounds__(256) void ics_kernel(const T* __restrict__ U, const double* __restrict__ sig,
+__global__ __launch_bounds__(256) void ics_kernel(const float* __restrict__ U, const double* __restrict__ sig,
                                                   float sv_rtol, float* __restrict__ C, float* __restrict__ C_out,
                                                   int N, int Np) {
   __shared__ double smax[4];
@@ -60,7 +59,7 @@ __global__ __launch_bounds__(256) void ics_kernel(const T* __restrict__ U, const
   }
   const int x = blockIdx.x * 4 + wave;
   if (x >= N) return;
-  const T* Ux = U + ((size_t)b * Np + x) * Np;
+  const float* Ux = U + ((size_t)b * Np + x) * Np;
   double acc = 0.0;
   for (int i = lane; i < Np; i += 64) {
     const double s = sb[i];
@@ -109,13 +108,13 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 }
 
 template <typename T>
-static int run_scores(const Plan& pl, const T* G, const T* U, const EigState* state, const float* S, float lambda,
+static int run_scores(const Plan& pl, const T* G, const float* U, const EigState* state, const float* S, float lambda,
                       int norm_mode, float sv_rtol, double* sig, float* C_ws, float* E, float* C_out, float* sigma_out,
                       int32_t* info_out, hipStream_t st) {
   int n2 = 1;
   while (n2 < pl.Np) n2 <<= 1;
   TC_TIMED(PK_SIGMA, 0, st, (sigma_kernel<T><<<pl.B, 256, sigma_out ? n2 * sizeof(float) : 0, st>>>(G, state, sig, sigma_out, info_out, pl.N, pl.Np)));
-  TC_TIMED(PK_ICS, 0, st, (ics_kernel<T><<<dim3((pl.N + 3) / 4, pl.B), 256, 0, st>>>(U, sig, sv_rtol, C_ws, C_out, pl.N, pl.Np)));
+  TC_TIMED(PK_ICS, 0, st, (ics_kernel<<<dim3((pl.N + 3) / 4, pl.B), 256, 0, st>>>(U, sig, sv_rtol, C_ws, C_out, pl.N, pl.Np)));
   TC_TIMED(PK_COMBINE, 0, st, (combine_kernel<<<pl.B, 256, 0, st>>>(C_ws, S, lambda, norm_mode, E, pl.N)));
   return check_launch();
 }
@@ -125,7 +124,7 @@ int launch_scores(const Plan& pl, int eig_dtype, const void* G, const void* U, c
                   float* C_out, float* sigma_out, int32_t* info_out, hipStream_t st) {
   (void)minmax_ws;
   if (eig_dtype == TC_EIG_F64)
-    return run_scores<double>(pl, (const double*)G, (const double*)U, state, S, lambda, norm_mode, sv_rtol,
+    return run_scores<double>(pl, (const double*)G, (const float*)U, state, S, lambda, norm_mode, sv_rtol,
                               (double*)sig_ws, C_ws, E, C_out, sigma_out, info_out, st);
   return run_scores<float>(pl, (const float*)G, (const float*)U, state, S, lambda, norm_mode, sv_rtol, (double*)sig_ws,
                            C_ws, E, C_out, sigma_out, info_out, st);

@@ -62,12 +62,13 @@ int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, c
 
 // ---- optional per-kernel timing (only active inside tc_profile_compress) ----------------------
 enum ProfKind {
-  PK_ATTN = 0, PK_ATTN_REDUCE, PK_GRAM, PK_JINIT, PK_JSOLVE, PK_JUPDATE, PK_JSWEEPEND, PK_SIGMA, PK_ICS, PK_COMBINE,
+  PK_ATTN = 0, PK_ATTN_REDUCE, PK_GRAM, PK_JINIT, PK_JSOLVE, PK_JUPDATE, PK_JUPDATE_U, PK_JSWEEPEND, PK_SIGMA, PK_ICS, PK_COMBINE,
   PK_TOPK, PK_ROWNORM, PK_SIM, PK_ASSIGN, PK_AVERAGE, PK_COUNT
 };
 static_assert((int)PK_COUNT == (int)TC_PROF_KINDS, "internal and public kernel kinds must match");
 void prof_begin(int kind, int tag, hipStream_t st);  // no-ops unless a profile run is active on this thread
 void prof_end(hipStream_t st);
+bool profiling_active();
 #define TC_TIMED(kind, tag, st, ...) \
   do {                               \
     tc::prof_begin(kind, tag, st);   \

@@ -6,7 +6,8 @@ choices (sort, argmax) of the next one.  Tolerances:
   O      bf16 storage: 1 unit in the last place, |dO| <= 2^-7 |O| + 1e-5 rms;
          float32 storage (accumulated in float32): |dO| <= 2^-22 |O| + 1e-5 rms
   S      1e-4 relative
-  C      1e-3 relative per token (spec tolerance; `tight` asks for 2e-5 on the fp64 solver)
+  C      1e-3 relative per token (spec tolerance; `tight` asks for 1e-4 on the fp64 solver,
+         whose eigenvectors are accumulated in float32)
   E      1e-3 of max|E|; sigma: 1e-3 sigma_1
   order  exact on the GPU's own E; against the oracle's E exact outside the 1e-4 tie band
   kept_idx / merge_dst exact unless an argmax or top-m margin of the oracle is <= 1e-4
@@ -48,7 +49,7 @@ def check_attention(p, w, batch, images, O_dev, S_dev, report):
 def check_ipgs(p, w, images, O_dev, S_dev, E_dev, C_dev, sig_dev, info_dev, report, tight=True):
     Oh, Sh = gu.host(O_dev).astype(np.float64), gu.host(S_dev).astype(np.float64) if S_dev is not None else None
     Eh, Ch, sh, ih = gu.host(E_dev), gu.host(C_dev), gu.host(sig_dev), gu.host(info_dev)
-    c_tol = 2e-5 if tight else 1e-3
+    c_tol = 1e-4 if tight else 1e-3
     for i in images:
         assert ih[i] > 0, "image %d: eigensolver reported %d" % (i, ih[i])
         E, C, s = orc.ipgs_score(Oh[i], None if Sh is None else Sh[i], p.lambda_, p.norm_mode, p.sv_rtol)
