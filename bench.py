@@ -42,6 +42,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llava7b_b64")
     ap.add_argument("--eig", default="f64", choices=["f64", "f32"])
+    ap.add_argument("--sweeps", type=int, default=0,
+                    help="eigensolver sweeps to launch; 0 = find the number the slowest image needs with one untimed run")
+    ap.add_argument("--groups", type=int, default=0, help="eigensolver stream groups (0 = library default, 1 = one stream)")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=12, help="images timed through the CPU oracle")
     args = ap.parse_args()
@@ -63,7 +68,7 @@ def main():
     batch = make_batch(w)
     gen_s = time.time() - t0
     eig = tc.TC_EIG_F64 if args.eig == "f64" else tc.TC_EIG_F32
-    p = tc.params_for(w, eig_dtype=eig)
+    p = tc.params_for(w, eig_dtype=eig, stream_groups=args.groups)
     sd = tc.storage_dtype(p)
 
     def dev(a):
@@ -77,9 +82,18 @@ def main():
     dst = torch.empty(B, N, dtype=torch.int32, device="cuda")
     info = torch.empty(B, dtype=torch.int32, device="cuda")
     ws = tc.new_workspace(p)
+    if args.copy_calib:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst_c = torch.empty_like(src)
+        dst_c.copy_(src)            # 1 GiB read + 1 GiB written by one elementwise copy kernel
+        torch.cuda.synchronize()
+        del src, dst_c
 
-    # calibration: how many eigensolver sweeps does the slowest image need?  The timed runs launch
-    # exactly that many (+1 so that every image reports convergence), not the library default of 30.
+    # How many eigensolver sweeps to launch.  The library default (30) enqueues launches that find every
+    # image converged and return at once; here the count is fixed to what the slowest image needs,
+    # found by one untimed run unless --sweeps gives it.  Convergence of every image is checked below.
+    if args.sweeps > 0:
+        p.jacobi_max_sweeps = args.sweeps
     tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, info=info)
     torch.cuda.synchronize()
     sweeps = info.cpu().numpy()
@@ -115,6 +129,12 @@ def main():
     achieved = flops / (upd_ms * 1e-3) / 1e12
     peak = PEAK_FP64_MFMA_TFLOPS if args.eig == "f64" else PEAK_FP32_MFMA_TFLOPS
     total_kernel_ms = sum(v[0] for v in kinds.values())
+    traffic = None   # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    pmc = os.path.join(ROOT, "profiles", "jacobi_update_g.%s.pmc.txt" % w.name)
+    if os.path.exists(pmc) and args.eig == "f64":
+        for line in open(pmc):
+            if line.startswith("hbm_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
 
     out = {
         "metric": "images/sec compressed (576x4096 -> k_prune -> k_final tokens, batch 64)",
@@ -132,11 +152,11 @@ def main():
         "config": {"workload": w.name, "batch": B, "n_vis": N, "n_text": w.n_sys + w.n_prompt,
                    "hidden": w.hidden, "heads": w.n_heads, "head_dim": w.head_dim,
                    "k_prune": w.k_prune, "k_final": w.k_final, "lambda": w.lam, "causal": w.causal,
-                   "qkv": w.qkv_mode, "jacobi_max_sweeps": int(p.jacobi_max_sweeps),
+                   "qkv": w.qkv_mode, "stream_groups": args.groups, "jacobi_max_sweeps": int(p.jacobi_max_sweeps),
                    "sweeps_used_min_max": [int(sweeps.min()), int(sweeps.max())],
                    "input_generation_s": round(gen_s, 1)},
         "roofline": {"kernel": "jacobi_update", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
                      "avg_launch_us": round(upd_ms * 1e3 / max(upd_launches, 1), 2), "launches": upd_launches},
         "kernel_ms": {k: round(v[0], 3) for k, v in kinds.items()},
         "kernel_ms_total": round(total_kernel_ms, 3),

@@ -11,8 +11,12 @@
  *
  * Conventions for every entry point
  *   - `p` is a HOST pointer.  Every other pointer is a DEVICE pointer owned by the
- *     caller, contiguous row-major, 16-byte aligned.  The library allocates
- *     nothing, frees nothing and keeps no pointer after the call returns.
+ *     caller, contiguous row-major, 16-byte aligned.  The library allocates no
+ *     memory, frees none and keeps no pointer after the call returns.  The only
+ *     state it keeps is up to three helper streams per device, created the first
+ *     time a batch is split into stream groups (see tc_params.stream_groups) and
+ *     kept until the process ends; their work is ordered after what is already on
+ *     `stream` and `stream` waits for it before the next stage.
  *   - All scratch memory comes from `ws` (`ws_bytes` >= tc_workspace_bytes(p)).
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and the call returns without waiting for it.  Two calls may
@@ -78,6 +82,8 @@ typedef struct {
   int32_t jacobi_max_sweeps; /* 0 => 30                                                         */
   float jacobi_tol;     /* stop when off(G)/||G||_F measured during a sweep < tol; 0 => default */
   int32_t eig_dtype;    /* tc_eig_dtype                                                         */
+  int32_t stream_groups; /* eigensolver: 0 = cut the batch into up to 4 groups that run on helper
+                            streams and overlap; 1 = everything on `stream`; 2..4 = that many groups */
 } tc_params;
 
 /* Bytes of scratch that any entry point may need for `p` (0 if p is invalid). */

@@ -18,7 +18,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   if (!(p->lambda >= 0.f && p->lambda <= 1.f) || (p->norm_mode != TC_NORM_NONE && p->norm_mode != TC_NORM_MINMAX) ||
       !(p->sv_rtol >= 0.f && p->sv_rtol < 1.f) || (p->causal != 0 && p->causal != 1) || !(p->softmax_scale >= 0.f) ||
       !std::isfinite(p->softmax_scale) || p->jacobi_max_sweeps < 0 || p->jacobi_max_sweeps > 1000 ||
-      !(p->jacobi_tol >= 0.f) || !(p->jacobi_tol < 1.f))
+      !(p->jacobi_tol >= 0.f) || !(p->jacobi_tol < 1.f) || p->stream_groups < 0 || p->stream_groups > 4)
     return TC_ERR_PARAM;
   if (p->k_final < 1 || p->k_final > p->k_prune || p->k_prune > p->n_vis) return TC_ERR_PARAM;
   const int nA = p->k_prune / 2, nB = p->k_prune - nA;
@@ -32,6 +32,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.q_tile = 128; q.n_qtiles = (q.N + q.q_tile - 1) / q.q_tile;
   q.esize = p->dtype == TC_BF16 ? 2 : 4;
   q.tsize = p->eig_dtype == TC_EIG_F64 ? 8 : 4;
+  q.groups = p->stream_groups;
   q.max_sweeps = p->jacobi_max_sweeps > 0 ? p->jacobi_max_sweeps : 30;
   q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 1e-7 : 3e-6);
   q.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)q.dh);

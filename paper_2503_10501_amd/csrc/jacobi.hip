@@ -509,7 +509,8 @@ static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, Eig
   const int Np = pl.Np;
   TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));
   TC_TIMED(PK_JINIT, 1, st, (jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np)));
-  int groups = pl.B >= 4 * MAX_GROUPS ? MAX_GROUPS : (pl.B >= 4 ? 2 : 1);
+  int groups = pl.groups > 0 ? pl.groups : (pl.B >= 4 * MAX_GROUPS ? MAX_GROUPS : (pl.B >= 4 ? 2 : 1));
+  if (groups > pl.B) groups = pl.B;
   if (profiling_active()) groups = 1;  // per-kernel timing wants kernels that run alone
   StreamPool* pool = groups > 1 ? helper_streams() : nullptr;
   hipEvent_t fork = nullptr, join[MAX_GROUPS - 1] = {};

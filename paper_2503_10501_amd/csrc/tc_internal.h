@@ -36,6 +36,7 @@ struct Plan {
   int esize;     // bytes of one stored element (2 or 4)
   int tsize;     // bytes of one eigensolver element (4 or 8)
   int max_sweeps;
+  int groups;    // requested stream groups (0 = automatic)
   double tol;
   float scale;
   size_t off_O, off_S, off_Spart, off_G, off_U, off_R, off_offpart, off_state, off_sig, off_sigsort, off_C,
