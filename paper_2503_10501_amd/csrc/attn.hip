@@ -90,16 +90,19 @@ __device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const bf8* qf,
 }
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                         const uint16_t* __restrict__ V, uint16_t* __restrict__ O,
                                                         float* __restrict__ Spart, int L, int Ls, int N, int H,
-                                                        int causal, float scale_log2e, int n_qtiles) {
+                                                        int causal, float scale_log2e, int n_qtiles, int B) {
   typedef AttnSmem<DH> SM;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SM::MAIN];
   __shared__ float cs[4][AK];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
   uint16_t* Vt = reinterpret_cast<uint16_t*>(smem + SM::K_BYTES);
-  const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int bh, qt;  // the query tiles of one (image, head) share K and V: keep them on one XCD
+  if (!group_on_xcd(blockIdx.x, n_qtiles, B * H, &bh, &qt)) return;
+  qt = n_qtiles - 1 - qt;  // longest (latest) query tile first
+  const int h = bh % H, b = bh / H;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
   const size_t head_off = ((size_t)b * H + h) * (size_t)L * DH;
   const uint16_t* Qh = Q + head_off;
@@ -171,20 +174,20 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
     store_k_tile<DH>(Ks, kr);
     store_v_tile_transposed<DH>(Vt, vr);
     __syncthreads();
-    float pr[32];
+    // one 32-key sub-tile at a time keeps the live register set small (two wavefronts per SIMD)
 #pragma unroll
     for (int sub = 0; sub < 2; sub++) {
-      const f16v acc = score_subtile<DH>(Ks, sub, qf, lane);
+      float pr[16];
+      {
+        const f16v acc = score_subtile<DH>(Ks, sub, qf, lane);
 #pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        pr[sub * 16 + r] = key < kend_q ? exp2f(acc[r] * scale_log2e - m_run) * inv_l : 0.f;
+        for (int r = 0; r < 16; r++) {
+          const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          pr[r] = key < kend_q ? exp2f(acc[r] * scale_log2e - m_run) * inv_l : 0.f;
+        }
       }
-    }
-    // O^T += V^T P^T.  Matrix-core k-slot (half, i) of product (sub, u) is key
-    // sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
-#pragma unroll
-    for (int sub = 0; sub < 2; sub++)
+      // O^T += V^T P^T.  Matrix-core k-slot (half, i) of product u is key
+      // sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
 #pragma unroll
       for (int u = 0; u < 2; u++) {
         // probabilities enter the matrix cores as a bf16 head plus a bf16 remainder (16 significant
@@ -192,7 +195,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
         bf8 pb, pl;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-          const float pv = pr[sub * 16 + 8 * u + i];
+          const float pv = pr[8 * u + i];
           pb[i] = (__bf16)pv;
           pl[i] = (__bf16)(pv - (float)pb[i]);
         }
@@ -207,20 +210,23 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t* __restri
           oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pl, oacc[mt], 0, 0, 0);
         }
       }
-    // column sums over this wavefront's 32 queries: recursive halving across lanes 0..31 of each half
+      // column sums over this wavefront's 32 queries: recursive halving across the 32 lanes of each
+      // half (16 values -> 1 value per lane pair), then the two lanes of a pair are added
 #pragma unroll
-    for (int o = 16, n = 32; o >= 1; o >>= 1, n >>= 1) {
-      const bool up = (lane & o) != 0;
+      for (int o = 16, n = 16; o >= 2; o >>= 1, n >>= 1) {
+        const bool up = (lane & o) != 0;
 #pragma unroll
-      for (int i = 0; i < n / 2; i++) {
-        const float send = up ? pr[i] : pr[i + n / 2];
-        const float keep = up ? pr[i + n / 2] : pr[i];
-        pr[i] = keep + __shfl_xor(send, o, 64);
+        for (int i = 0; i < n / 2; i++) {
+          const float send = up ? pr[i] : pr[i + n / 2];
+          const float keep = up ? pr[i + n / 2] : pr[i];
+          pr[i] = keep + __shfl_xor(send, o, 64);
+        }
       }
-    }
-    {
-      const int vi = lane & 31, sub = vi >> 4, r = vi & 15;
-      cs[wave][sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = pr[0];
+      pr[0] += __shfl_xor(pr[0], 1, 64);
+      if ((lane & 1) == 0) {
+        const int r = (lane >> 1) & 15;  // accumulator element whose column sum this lane pair holds
+        cs[wave][sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = pr[0];
+      }
     }
     __syncthreads();
     if (tid < AK) {
@@ -346,16 +352,16 @@ __global__ __launch_bounds__(256) void attn_f32_cols(const float* __restrict__ Q
 int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const void* K, const void* V, void* O,
                      float* S, float* Spart, hipStream_t st) {
   if (dtype == TC_BF16) {
-    const dim3 grid(pl.n_qtiles, pl.H, pl.B);
+    const dim3 grid(grid_for_groups(pl.n_qtiles, pl.B * pl.H));
     const float sl2 = pl.scale * 1.4426950408889634f;
     if (pl.dh == 128)
       TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<128><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
                                                   (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
-                                                  pl.n_qtiles)));
+                                                  pl.n_qtiles, pl.B)));
     else
       TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<64><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
                                                  (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
-                                                 pl.n_qtiles)));
+                                                 pl.n_qtiles, pl.B)));
     if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.H, pl.n_qtiles)));
   } else {
     const dim3 grid(pl.N, pl.H, pl.B);

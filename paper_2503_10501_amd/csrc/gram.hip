@@ -35,14 +35,15 @@ __device__ inline void load8<float>(const float* src, double* dst) {
 // One workgroup: a 64x64 tile (ti >= tj) of G for image blockIdx.y, mirrored into (tj, ti).
 template <typename TIn, typename TOut>
 __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TOut* __restrict__ G, int N, int D,
-                                                   int Np) {
+                                                   int Np, int B) {
   __shared__ double As[GK][GLD];
   __shared__ double Bs[GK][GLD];
-  // decode the lower-triangular tile index
-  int t = blockIdx.x, ti = 0;
+  const int ntile = Np / 64;
+  int b, t;
+  if (!group_on_xcd(blockIdx.x, ntile * (ntile + 1) / 2, B, &b, &t)) return;
+  int ti = 0;  // decode the lower-triangular tile index
   while (t >= ti + 1) { t -= ti + 1; ti++; }
   const int tj = t;
-  const int b = blockIdx.y;
   const TIn* Ob = O + (size_t)b * N * D;
   TOut* Gb = G + (size_t)b * Np * Np;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -103,17 +104,17 @@ __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TO
 
 int launch_gram(const Plan& pl, int dtype, int eig_dtype, const void* O, void* G, hipStream_t st) {
   const int nt = pl.Np / 64;
-  dim3 grid(nt * (nt + 1) / 2, pl.B), block(256);
+  dim3 grid(grid_for_groups(nt * (nt + 1) / 2, pl.B)), block(256);
   if (dtype == TC_BF16) {
     if (eig_dtype == TC_EIG_F64)
-      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, double><<<grid, block, 0, st>>>((const uint16_t*)O, (double*)G, pl.N, pl.D, pl.Np)));
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, double><<<grid, block, 0, st>>>((const uint16_t*)O, (double*)G, pl.N, pl.D, pl.Np, pl.B)));
     else
-      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, float><<<grid, block, 0, st>>>((const uint16_t*)O, (float*)G, pl.N, pl.D, pl.Np)));
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, float><<<grid, block, 0, st>>>((const uint16_t*)O, (float*)G, pl.N, pl.D, pl.Np, pl.B)));
   } else {
     if (eig_dtype == TC_EIG_F64)
-      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<float, double><<<grid, block, 0, st>>>((const float*)O, (double*)G, pl.N, pl.D, pl.Np)));
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<float, double><<<grid, block, 0, st>>>((const float*)O, (double*)G, pl.N, pl.D, pl.Np, pl.B)));
     else
-      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<float, float><<<grid, block, 0, st>>>((const float*)O, (float*)G, pl.N, pl.D, pl.Np)));
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<float, float><<<grid, block, 0, st>>>((const float*)O, (float*)G, pl.N, pl.D, pl.Np, pl.B)));
   }
   return check_launch();
 }

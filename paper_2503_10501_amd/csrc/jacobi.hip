@@ -8,6 +8,8 @@
 // (jacobi_update), both as small matrix products on the matrix cores.  nblk-1 steps make a sweep;
 // sweeps repeat until the off-diagonal mass measured during a sweep is below the tolerance, per
 // image, with the iteration count fixed on the host and converged images skipped on the device.
+// After the Gram kernel has filled G in full, only its blocks on and above the block diagonal are
+// maintained.
 // On exit diag(G) holds the eigenvalues sigma_i^2 and U the left singular vectors of O
 // (Section 3.3.1: Z = U Sigma V^T  =>  Z Z^T = U Sigma^2 U^T).
 #include <mutex>
@@ -131,8 +133,10 @@ __device__ inline void rotation(float aii, float ajj, float aij, float* c, float
 //     wavefront plus one column handed to each neighbouring wavefront through a small LDS buffer.
 //     After 63 steps the seats are back in their starting order.
 //   * Per step: lanes 0..31 of wavefront 0 compute the 32 rotations (barrier), all lanes apply
-//     them (barrier).  The kernel is bound by vector-ALU issue, so index and address arithmetic is
-//     kept to a minimum.
+//     them (barrier).  Measured alternatives that were slower on MI355X: every lane computing its own
+//     rotation, wavefronts specialised for S and for R, one block per lane on 12 wavefronts, and
+//     index/address lookup tables in LDS or global memory -- the step time is set by LDS traffic and
+//     the barrier-to-barrier chain, which this arrangement keeps shortest.
 constexpr int SOLVE_WAVES = 8;
 constexpr int SEATS = JB / SOLVE_WAVES;  // seats per wavefront
 constexpr int N_BLOCKS = JB * (JB + 1) / 2;
@@ -159,12 +163,13 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
     const int c = lane, gc = (c < JB ? p * JB + c : q * JB + c - JB);
     double off = 0.0;
     for (int r = wave; r < JT; r += SOLVE_WAVES) {
+      if (r >= JB && c < JB) continue;  // block (q,p) is not stored; S is only used for r <= c
       const int gr = (r < JB ? p * JB + r : q * JB + r - JB);
       const T v = Gb[(size_t)gr * Np + gc];
-      S[r][c] = v;  // only r <= c is used afterwards
+      S[r][c] = v;
       const double dv = (double)v;
-      if ((r < JB) != (c < JB)) off += dv * dv;                       // the G_pq / G_qp blocks
-      else if (r != c) off += dv * dv / (double)(nblk - 1);           // inside G_pp, G_qq (seen nblk-1 times)
+      if (r < JB && c >= JB) off += 2.0 * dv * dv;                           // G_pq and its mirror
+      else if (r < c) off += 2.0 * dv * dv / (double)(nblk - 1);             // inside G_pp, G_qq (seen nblk-1 times)
     }
     off = wave_sum(off);
     if (lane == 0) red[wave] = off;
@@ -281,27 +286,32 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
 }
 
 // ---------------------------------------------------------------------------------------
-// Tile update of G.  One workgroup per pair of block pairs I <= J: the 64x64 tile spanned by the
-// rows of pair I and the columns of pair J becomes R_I^T G_IJ R_J; the mirror tile (J,I) receives the
-// transpose, so G stays exactly symmetric and only the upper triangle of tiles is computed.
+// Tile update of G.  Only the 32x32 blocks (r,c) with r <= c are kept up to date (diagonal blocks in
+// full), which halves the traffic and keeps the working set of a step inside the last-level cache.
+// One workgroup per pair of block pairs I <= J: the 64x64 tile spanned by the rows of pair I and the
+// columns of pair J is gathered (a quadrant whose block lies below the diagonal is read from its
+// mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and is scattered back the
+// same way.  The mirror tile (J,I) is never formed.
 template <typename T>
 __global__ __launch_bounds__(256) void jacobi_update_g(T* __restrict__ G, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
-                                                       int img0) {
+                                                       int img0, int nimg) {
   typedef typename MM<T>::acc_t acc_t;
-  const int b = img0 + blockIdx.y, P = nblk / 2;
+  const int P = nblk / 2;
+  int img, tile;
+  if (!group_on_xcd(blockIdx.x, P * (P + 1) / 2, nimg, &img, &tile)) return;
+  const int b = img0 + img;
   if (state[b].done) return;
   __shared__ T X[JT][SLD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  int I = 0, J = blockIdx.x;  // decode the upper-triangular tile index: row I holds P - I tiles
+  int I = 0, J = tile;  // decode the upper-triangular tile index: row I holds P - I tiles
   while (J >= P - I) { J -= P - I; I++; }
   J += I;
   T* M = G + (size_t)b * Np * Np;
-  int rowbase[2], colbase[2];
-  round_robin_pair(nblk, step, I, &rowbase[0], &rowbase[1]);
-  round_robin_pair(nblk, step, J, &colbase[0], &colbase[1]);
-  rowbase[0] *= JB; rowbase[1] *= JB; colbase[0] *= JB; colbase[1] *= JB;
+  int rowblk[2], colblk[2];
+  round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
+  round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
   const T* RI = R + ((size_t)b * P + I) * JT * JT;
   const T* RJ = R + ((size_t)b * P + J) * JT * JT;
   // Left factor R_I^T as matrix-core A fragments: A[i][k] = R_I[k][i], rows i in wr*32 .. +32.
@@ -312,13 +322,17 @@ __global__ __launch_bounds__(256) void jacobi_update_g(T* __restrict__ G, const 
     rf[ks][0] = RI[k * JT + wr * 32 + (lane & 15)];
     rf[ks][1] = RI[k * JT + wr * 32 + 16 + (lane & 15)];
   }
-  {  // gather the tile: lanes 0..15 read 16 consecutive columns of one row
-    const int c = (lane & 15) + 16 * wave;
-    const int gc = colbase[c >> 5] + (c & 31);
+  // This thread moves, for it = 0..15, the element (r, c) = (lane/16 + 4 it, lane%16 + 16 wave) of the
+  // tile if its block is stored, else the element of the mirror block that sits at the same place of
+  // the stored block; 16 consecutive lanes always touch 16 consecutive columns in memory.
+  const int c = (lane & 15) + 16 * wave, cq = c >> 5, ci = c & 31;
+  {
 #pragma unroll
     for (int it = 0; it < 16; it++) {
-      const int r = (lane >> 4) + 4 * it;
-      X[r][c] = M[(size_t)(rowbase[r >> 5] + (r & 31)) * Np + gc];
+      const int r = (lane >> 4) + 4 * it, rq = r >> 5, ri = r & 31;
+      const int br = rowblk[rq], bc = colblk[cq];
+      if (br <= bc) X[r][c] = M[(size_t)(br * JB + ri) * Np + bc * JB + ci];
+      else X[rq * JB + ci][cq * JB + ri] = M[(size_t)(bc * JB + ri) * Np + br * JB + ci];
     }
   }
   __syncthreads();
@@ -362,28 +376,22 @@ __global__ __launch_bounds__(256) void jacobi_update_g(T* __restrict__ G, const 
     acc[1][0] = MM<T>::mma(a1, rf[ks][0], acc[1][0]);
     acc[1][1] = MM<T>::mma(a1, rf[ks][1], acc[1][1]);
   }
-  if (I != J) __syncthreads();  // W fully consumed before Y overwrites it (uniform branch)
+  __syncthreads();  // W fully consumed before Y overwrites it
 #pragma unroll
   for (int mt = 0; mt < 2; mt++)
 #pragma unroll
     for (int nt = 0; nt < 2; nt++)
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const int r = wr * 32 + mt * 16 + MM<T>::row(j, lane);
-        const int c = wc * 32 + nt * 16 + (lane & 15);
-        M[(size_t)(rowbase[r >> 5] + (r & 31)) * Np + colbase[c >> 5] + (c & 31)] = acc[mt][nt][j];
-        if (I != J) X[r][c] = acc[mt][nt][j];
-      }
-  if (I != J) {
-    __syncthreads();
-    // mirror tile (J,I) = Y^T, written row by row (lanes 0..15 cover 16 consecutive columns)
-    const int c = (lane & 15) + 16 * wave;  // column of the mirror tile = row of Y
-    const int gc = rowbase[c >> 5] + (c & 31);
+      for (int j = 0; j < 4; j++)
+        X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + nt * 16 + (lane & 15)] = acc[mt][nt][j];
+  __syncthreads();
 #pragma unroll
-    for (int it = 0; it < 16; it++) {
-      const int r = (lane >> 4) + 4 * it;   // row of the mirror tile = column of Y
-      M[(size_t)(colbase[r >> 5] + (r & 31)) * Np + gc] = X[c][r];
-    }
+  for (int it = 0; it < 16; it++) {
+    const int r = (lane >> 4) + 4 * it, rq = r >> 5, ri = r & 31;
+    const int br = rowblk[rq], bc = colblk[cq];
+    if (I == J && rq == 1 && cq == 0) continue;  // mirror of quadrant (0,1) of a diagonal tile
+    if (br <= bc) M[(size_t)(br * JB + ri) * Np + bc * JB + ci] = X[r][c];
+    else M[(size_t)(bc * JB + ri) * Np + br * JB + ci] = X[rq * JB + ci][cq * JB + ri];
   }
 }
 
@@ -393,13 +401,16 @@ __global__ __launch_bounds__(256) void jacobi_update_g(T* __restrict__ G, const 
 template <typename T>
 __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
-                                                       int img0) {
-  const int b = img0 + blockIdx.y, P = nblk / 2;
+                                                       int img0, int nimg) {
+  const int P = nblk / 2;
+  int img, tile;
+  if (!group_on_xcd(blockIdx.x, (Np / JT) * P, nimg, &img, &tile)) return;
+  const int b = img0 + img;
   if (state[b].done) return;
   __shared__ float X[JT][SLD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  const int J = blockIdx.x % P, slab = blockIdx.x / P;
+  const int J = tile % P, slab = tile / P;
   float* M = U + (size_t)b * Np * Np;
   int colbase[2];
   round_robin_pair(nblk, step, J, &colbase[0], &colbase[1]);
@@ -452,14 +463,17 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
 // ---------------------------------------------------------------------------------------
 __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* __restrict__ state, int count,
                                  double tol, int img0, int nimg) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  const int b = img0 + i;
-  if (i >= nimg || state[b].done) return;
+  const int b = img0 + blockIdx.x, lane = threadIdx.x;  // one wavefront per image
+  (void)nimg;
+  if (state[b].done) return;
   const double* op = offpart + (size_t)b * count;
   double s = 0.0;
-  for (int i = 0; i < count; i++) s += op[i];  // fixed order: the decision is reproducible
-  state[b].sweeps += 1;
-  if (s <= tol * tol * state[b].norm2) state[b].done = 1;
+  for (int i = lane; i < count; i += 64) s += op[i];
+  s = wave_sum(s);  // fixed association: the decision is reproducible
+  if (lane == 0) {
+    state[b].sweeps += 1;
+    if (s <= tol * tol * state[b].norm2) state[b].done = 1;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -493,14 +507,15 @@ template <typename T>
 static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart, EigState* state, int img0, int nimg,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
-  const dim3 gs(P, nimg), gg(P * (P + 1) / 2, nimg), gu((Np / JT) * P, nimg);
+  const dim3 gs(P, nimg);
+  const int gg = grid_for_groups(P * (P + 1) / 2, nimg), gu = grid_for_groups((Np / JT) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
       TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
-      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0)));
-      TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0)));
+      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg)));
+      TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg)));
     }
-    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<(nimg + 63) / 64, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, img0, nimg)));
+    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<nimg, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, img0, nimg)));
   }
 }
 
