@@ -23,6 +23,9 @@ typedef __attribute__((ext_vector_type(4))) float f4;
 
 // 16x16x4 matrix-core product for both element types.  A: lane holds A[lane%16][lane/16];
 // B: lane holds B[lane/16][lane%16]; accumulator element j of a lane is C[row(j)][lane%16].
+// Which four of the 64 contraction indices one product covers is free as long as A and B agree; the
+// update kernels give product ks the indices ks, ks+16, ks+32, ks+48 so that the four LDS rows a
+// wavefront reads at once fall into different banks with the 65-element row pitch.
 template <typename T> struct MM;
 template <> struct MM<double> {
   typedef d4 acc_t;
@@ -119,10 +122,12 @@ __device__ inline void rotation(float aii, float ajj, float aij, float* c, float
 // One workgroup (8 wavefronts) per block pair: load the 64x64 subproblem, one cyclic sweep of plane
 // rotations in the round-robin order, emit the accumulated orthogonal matrix R.
 //
-// The 64 indices sit in 32 "seats" of a round-robin tournament: seat i of step st holds the indices
-// top = (st+i) mod 63 (63 for seat 0) and bottom = (st-i) mod 63, every index advances by one per
-// step, and the 32 seats of a step are its 32 disjoint rotations (the pairs round_robin_pair()
-// enumerates).  A rotation is stored in seat orientation: top' = c top - s bottom,
+// The 64 indices sit in 32 "seats": the 32 seats of a step are its 32 disjoint rotations.  In a
+// full sweep (CROSS = false, 63 steps, every index pair once) the seats follow a round-robin
+// tournament: seat i of step st holds top = (st+i) mod 63 (63 for seat 0) and bottom = (st-i) mod 63,
+// every index advances by one per step (the pairs round_robin_pair() enumerates).  In a cross sweep
+// (CROSS = true, 32 steps) only pairs with one index in each of the two blocks are rotated:
+// top = i, bottom = 32 + (i + st) mod 32.  A rotation is stored in seat orientation: top' = c top - s bottom,
 // bottom' = s top + c bottom.
 //   * S is symmetric and lives in LDS, element {x,y} stored once at S[min][max].  A step acts on it
 //     as 2x2 blocks (rows of seat I) x (columns of seat J), I <= J: 528 blocks, one per lane, the
@@ -143,7 +148,7 @@ constexpr int N_BLOCKS = JB * (JB + 1) / 2;
 
 __device__ inline int next63(int x) { return x == 62 ? 0 : x + 1; }
 
-template <typename T>
+template <typename T, bool CROSS>
 __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
                                                                  double* __restrict__ offpart,
                                                                  const EigState* __restrict__ state, int Np, int nblk,
@@ -174,13 +179,18 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
     off = wave_sum(off);
     if (lane == 0) red[wave] = off;
   }
-  // R = I in seat order (step 0: top_i = i, top_0 = 63, bottom_i = (63 - i) mod 63)
+  // R = I in seat order.  Full sweep, step 0: top_i = i, top_0 = 63, bottom_i = (63 - i) mod 63.
+  // Cross sweep: top_i = i stays, bottom_i = 32 + (i + st) mod 32.
+  auto top0 = [](int i) { return CROSS ? i : (i == 0 ? 63 : i); };
+  auto bot0 = [](int i) { return CROSS ? JB + i : (63 - i) % 63; };
+  auto next_top = [](int x) { return CROSS || x == 63 ? x : next63(x); };
+  auto next_bot = [](int x) { return CROSS ? (x == JT - 1 ? JB : x + 1) : next63(x); };
   T rtop[SEATS], rbot[SEATS];
 #pragma unroll
   for (int k = 0; k < SEATS; k++) {
     const int i = SEATS * wave + k;
-    rtop[k] = (lane == (i == 0 ? 63 : i)) ? T(1) : T(0);
-    rbot[k] = (lane == (63 - i) % 63) ? T(1) : T(0);
+    rtop[k] = (lane == top0(i)) ? T(1) : T(0);
+    rbot[k] = (lane == bot0(i)) ? T(1) : T(0);
   }
   // blocks of this lane: task tid (all 512 lanes) and, on the last wavefront, task 512 + lane
   int tI[2], bI[2], tJ[2], bJ[2], sI[2], sJ[2];
@@ -193,10 +203,10 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
     while (J >= JB - I) { J -= JB - I; I++; }
     J += I;
     sI[g] = I; sJ[g] = J;
-    tI[g] = I == 0 ? 63 : I; bI[g] = (63 - I) % 63;
-    tJ[g] = J == 0 ? 63 : J; bJ[g] = (63 - J) % 63;
+    tI[g] = top0(I); bI[g] = bot0(I);
+    tJ[g] = top0(J); bJ[g] = bot0(J);
   }
-  int rt = lane == 0 ? 63 : (lane & 31), rb = (63 - (lane & 31)) % 63;  // seat lane%32, for the rotations
+  int rt = top0(lane & 31), rb = bot0(lane & 31);  // seat lane%32, for the rotations
   __syncthreads();
   if (tid == 0) {
     double tot = 0.0;
@@ -204,7 +214,7 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
     offpart[((size_t)b * (nblk - 1) + step) * P + pair] = tot;
   }
 
-  for (int st = 0; st < inner_steps; st++) {  // JT - 1 steps bring the seats back to their starting order
+  for (int st = 0; st < inner_steps; st++) {  // a whole sweep brings the seats back to their starting order
     if (tid < JB) {
       const int a = min(rt, rb), bq = max(rt, rb);
       T c, s;
@@ -213,8 +223,12 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
       rs[tid] = rt > rb ? -s : s;  // seat orientation: the top index is the larger one
     }
     if (st > 0) {  // columns handed over by the neighbours at the end of the previous step
-      if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
-      if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+      if (CROSS) {
+        rbot[SEATS - 1] = xbot[(wave + 1) % SOLVE_WAVES][lane];
+      } else {
+        if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
+        if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+      }
     }
     __syncthreads();
     // ---- S <- J^T S J -----------------------------------------------------------------------------
@@ -234,10 +248,8 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
         *pbt = cJ * fbt - zJ * fbb;
         *pbb = zJ * fbt + cJ * fbb;
       }
-      if (tI[g] != 63) tI[g] = next63(tI[g]);
-      bI[g] = next63(bI[g]);
-      if (tJ[g] != 63) tJ[g] = next63(tJ[g]);
-      bJ[g] = next63(bJ[g]);
+      tI[g] = next_top(tI[g]); bI[g] = next_bot(bI[g]);
+      tJ[g] = next_top(tJ[g]); bJ[g] = next_bot(bJ[g]);
     }
     // ---- R <- R J on this wavefront's seats -------------------------------------------------------
 #pragma unroll
@@ -247,8 +259,13 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
       rtop[k] = c * x - z * y;
       rbot[k] = z * x + c * y;
     }
-    // move the columns one seat along the cycle: tops towards seat 1, bottoms away from seat 0
-    {
+    // move the columns one seat along the cycle
+    if (CROSS) {  // tops stay, every bottom moves to the seat before it (seat 0's to seat 31)
+      const T out_bot = rbot[0];
+#pragma unroll
+      for (int k = 0; k < SEATS - 1; k++) rbot[k] = rbot[k + 1];
+      xbot[wave][lane] = out_bot;  // becomes the last bottom of the wavefront before
+    } else {  // tops move towards seat 1, bottoms away from seat 0
       const T out_top = rtop[0], out_bot = rbot[SEATS - 1], top1 = rtop[1];
       if (wave == 0) {
 #pragma unroll
@@ -264,21 +281,25 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
       if (wave > 0) xtop[wave][lane] = out_top;                         // becomes the last top of wave-1
       if (wave < SOLVE_WAVES - 1) xbot[wave][lane] = out_bot;           // becomes the first bottom of wave+1
     }
-    if (rt != 63) rt = next63(rt);
-    rb = next63(rb);
+    rt = next_top(rt);
+    rb = next_bot(rb);
     __syncthreads();  // S, the rotation table and the hand-over buffers are free for the next step
   }
   if (inner_steps > 0) {
-    if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
-    if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+    if (CROSS) {
+      rbot[SEATS - 1] = xbot[(wave + 1) % SOLVE_WAVES][lane];
+    } else {
+      if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
+      if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+    }
   }
-  // after JT - 1 steps the seats are back in their step-0 order; stage R through LDS for
-  // row-contiguous stores
+  // after a whole sweep (63 or 32 steps) the seats are back in their step-0 order; stage R through
+  // LDS for row-contiguous stores
 #pragma unroll
   for (int k = 0; k < SEATS; k++) {
     const int i = SEATS * wave + k;
-    S[lane][i == 0 ? 63 : i] = rtop[k];
-    S[lane][(63 - i) % 63] = rbot[k];
+    S[lane][top0(i)] = rtop[k];
+    S[lane][bot0(i)] = rbot[k];
   }
   __syncthreads();
   T* Rb = R + ((size_t)b * P + pair) * JT * JT;
@@ -290,108 +311,152 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
 // full), which halves the traffic and keeps the working set of a step inside the last-level cache.
 // One workgroup per pair of block pairs I <= J: the 64x64 tile spanned by the rows of pair I and the
 // columns of pair J is gathered (a quadrant whose block lies below the diagonal is read from its
-// mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and is scattered back the
-// same way.  The mirror tile (J,I) is never formed.
+// mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and is scattered back to
+// the stored blocks.  The mirror tile (J,I) is never formed.
+constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup
+
+// Tile index t (row-major over the upper triangle of pair pairs, row I holds P - I tiles) -> (I, J).
+__device__ inline void decode_tile(int t, int P, int* I, int* J) {
+  int i = 0;
+  while (t >= P - i) { t -= P - i; i++; }
+  *I = i;
+  *J = t + i;
+}
+
+// A workgroup walks over G_CHUNK consecutive tiles and software-pipelines them: while the matrix
+// cores work on tile k, the gather of tile k+1 and the right factor of tile k are already in flight
+// in registers, so only the first tile of a chunk waits for memory.
 template <typename T>
-__global__ __launch_bounds__(256) void jacobi_update_g(T* __restrict__ G, const T* __restrict__ R,
+__global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
                                                        int img0, int nimg) {
   typedef typename MM<T>::acc_t acc_t;
-  const int P = nblk / 2;
-  int img, tile;
-  if (!group_on_xcd(blockIdx.x, P * (P + 1) / 2, nimg, &img, &tile)) return;
+  const int P = nblk / 2, ntiles = P * (P + 1) / 2, nchunks = (ntiles + G_CHUNK - 1) / G_CHUNK;
+  int img, chunk;
+  if (!group_on_xcd(blockIdx.x, nchunks, nimg, &img, &chunk)) return;
   const int b = img0 + img;
   if (state[b].done) return;
   __shared__ T X[JT][SLD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  int I = 0, J = tile;  // decode the upper-triangular tile index: row I holds P - I tiles
-  while (J >= P - I) { J -= P - I; I++; }
-  J += I;
   T* M = G + (size_t)b * Np * Np;
-  int rowblk[2], colblk[2];
-  round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
-  round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
-  const T* RI = R + ((size_t)b * P + I) * JT * JT;
-  const T* RJ = R + ((size_t)b * P + J) * JT * JT;
-  // Left factor R_I^T as matrix-core A fragments: A[i][k] = R_I[k][i], rows i in wr*32 .. +32.
-  T rf[16][2];
-#pragma unroll
-  for (int ks = 0; ks < 16; ks++) {
-    const int k = 4 * ks + (lane >> 4);
-    rf[ks][0] = RI[k * JT + wr * 32 + (lane & 15)];
-    rf[ks][1] = RI[k * JT + wr * 32 + 16 + (lane & 15)];
-  }
-  // This thread moves, for it = 0..15, the element (r, c) = (lane/16 + 4 it, lane%16 + 16 wave) of the
+  const T* Rimg = R + (size_t)b * P * JT * JT;
+  const int t0 = chunk * G_CHUNK, t1 = min(ntiles, t0 + G_CHUNK);
+  // This thread moves, for it = 0..15, the element (r, c) = (lane/16 + 4 it, lane%16 + 16 wave) of a
   // tile if its block is stored, else the element of the mirror block that sits at the same place of
   // the stored block; 16 consecutive lanes always touch 16 consecutive columns in memory.
   const int c = (lane & 15) + 16 * wave, cq = c >> 5, ci = c & 31;
-  {
+  auto gather = [&](int I, int J, T* x) {
+    int rowblk[2], colblk[2];
+    round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
+    round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
 #pragma unroll
     for (int it = 0; it < 16; it++) {
       const int r = (lane >> 4) + 4 * it, rq = r >> 5, ri = r & 31;
       const int br = rowblk[rq], bc = colblk[cq];
-      if (br <= bc) X[r][c] = M[(size_t)(br * JB + ri) * Np + bc * JB + ci];
-      else X[rq * JB + ci][cq * JB + ri] = M[(size_t)(bc * JB + ri) * Np + br * JB + ci];
+      x[it] = br <= bc ? M[(size_t)(br * JB + ri) * Np + bc * JB + ci] : M[(size_t)(bc * JB + ri) * Np + br * JB + ci];
     }
-  }
-  __syncthreads();
-  acc_t acc[2][2];
+  };
+  auto load_left = [&](int I, T (*f)[2]) {  // R_I^T as A fragments: A[i][k] = R_I[k][i], rows wr*32 .. +32
+    const T* RI = Rimg + (size_t)I * JT * JT;
 #pragma unroll
-  for (int i = 0; i < 2; i++)
+    for (int ks = 0; ks < 16; ks++) {
+      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
+      f[ks][0] = RI[k * JT + wr * 32 + (lane & 15)];
+      f[ks][1] = RI[k * JT + wr * 32 + 16 + (lane & 15)];
+    }
+  };
+  auto load_right = [&](int J, T (*f)[2]) {  // R_J[:, wc*32 .. +32) as B fragments
+    const T* RJ = Rimg + (size_t)J * JT * JT;
 #pragma unroll
-    for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
-  // W = R_I^T X; each used fragment register is refilled with the right factor R_J[:, wc*32 .. +32)
+    for (int ks = 0; ks < 16; ks++) {
+      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
+      f[ks][0] = RJ[k * JT + wc * 32 + (lane & 15)];
+      f[ks][1] = RJ[k * JT + wc * 32 + 16 + (lane & 15)];
+    }
+  };
+  int I, J;
+  decode_tile(t0, P, &I, &J);
+  T left[16][2], right[16][2], xpre[16];
+  load_left(I, left);
+  gather(I, J, xpre);
+  for (int t = t0; t < t1; t++) {
+    int rowblk[2], colblk[2];
+    round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
+    round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
+    // tile into LDS (a quadrant read from its mirror block is transposed here)
 #pragma unroll
-  for (int ks = 0; ks < 16; ks++) {
-    const int k = 4 * ks + (lane >> 4);
-    const T b0 = X[k][wc * 32 + (lane & 15)], b1 = X[k][wc * 32 + 16 + (lane & 15)];
-    acc[0][0] = MM<T>::mma(rf[ks][0], b0, acc[0][0]);
-    acc[0][1] = MM<T>::mma(rf[ks][0], b1, acc[0][1]);
-    acc[1][0] = MM<T>::mma(rf[ks][1], b0, acc[1][0]);
-    acc[1][1] = MM<T>::mma(rf[ks][1], b1, acc[1][1]);
-    rf[ks][0] = RJ[k * JT + wc * 32 + (lane & 15)];
-    rf[ks][1] = RJ[k * JT + wc * 32 + 16 + (lane & 15)];
-  }
-  __syncthreads();  // every wave has finished reading X
+    for (int it = 0; it < 16; it++) {
+      const int r = (lane >> 4) + 4 * it, rq = r >> 5, ri = r & 31;
+      if (rowblk[rq] <= colblk[cq]) X[r][c] = xpre[it];
+      else X[rq * JB + ci][cq * JB + ri] = xpre[it];
+    }
+    __syncthreads();
+    // memory traffic for later: right factor of this tile, gather of the next one
+    load_right(J, right);
+    int In = I, Jn = J;
+    const bool more = t + 1 < t1;
+    if (more) {
+      decode_tile(t + 1, P, &In, &Jn);
+      gather(In, Jn, xpre);
+    }
+    acc_t acc[2][2];
 #pragma unroll
-  for (int mt = 0; mt < 2; mt++)
+    for (int i = 0; i < 2; i++)
 #pragma unroll
-    for (int nt = 0; nt < 2; nt++)
+      for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
+    // W = R_I^T X
 #pragma unroll
-      for (int j = 0; j < 4; j++)
-        X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + nt * 16 + (lane & 15)] = acc[mt][nt][j];
-  __syncthreads();
-  // Y = W R_J
+    for (int ks = 0; ks < 16; ks++) {
+      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
+      const T b0 = X[k][wc * 32 + (lane & 15)], b1 = X[k][wc * 32 + 16 + (lane & 15)];
+      acc[0][0] = MM<T>::mma(left[ks][0], b0, acc[0][0]);
+      acc[0][1] = MM<T>::mma(left[ks][0], b1, acc[0][1]);
+      acc[1][0] = MM<T>::mma(left[ks][1], b0, acc[1][0]);
+      acc[1][1] = MM<T>::mma(left[ks][1], b1, acc[1][1]);
+    }
+    if (more && In != I) load_left(In, left);  // next tile starts a new row of tiles
+    __syncthreads();  // every wave has finished reading X
 #pragma unroll
-  for (int i = 0; i < 2; i++)
+    for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-    for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
+      for (int nt = 0; nt < 2; nt++)
 #pragma unroll
-  for (int ks = 0; ks < 16; ks++) {
-    const int k = 4 * ks + (lane >> 4);
-    const T a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
-    acc[0][0] = MM<T>::mma(a0, rf[ks][0], acc[0][0]);
-    acc[0][1] = MM<T>::mma(a0, rf[ks][1], acc[0][1]);
-    acc[1][0] = MM<T>::mma(a1, rf[ks][0], acc[1][0]);
-    acc[1][1] = MM<T>::mma(a1, rf[ks][1], acc[1][1]);
-  }
-  __syncthreads();  // W fully consumed before Y overwrites it
+        for (int j = 0; j < 4; j++)
+          X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + nt * 16 + (lane & 15)] = acc[mt][nt][j];
+    __syncthreads();
+    // Y = W R_J
 #pragma unroll
-  for (int mt = 0; mt < 2; mt++)
+    for (int i = 0; i < 2; i++)
 #pragma unroll
-    for (int nt = 0; nt < 2; nt++)
+      for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < 4; j++)
-        X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + nt * 16 + (lane & 15)] = acc[mt][nt][j];
-  __syncthreads();
+    for (int ks = 0; ks < 16; ks++) {
+      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
+      const T a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
+      acc[0][0] = MM<T>::mma(a0, right[ks][0], acc[0][0]);
+      acc[0][1] = MM<T>::mma(a0, right[ks][1], acc[0][1]);
+      acc[1][0] = MM<T>::mma(a1, right[ks][0], acc[1][0]);
+      acc[1][1] = MM<T>::mma(a1, right[ks][1], acc[1][1]);
+    }
+    // Each wavefront holds one quadrant of Y (rows of block rowblk[wr], columns of block colblk[wc])
+    // in its accumulators and stores it straight from registers: as it is when the block is stored,
+    // else transposed into the mirror block (32-byte pieces that the L2 merges into full lines).
+    const int br = rowblk[wr], bc = colblk[wc];
+    if (!(I == J && wr == 1 && wc == 0)) {  // (1,0) of a diagonal tile mirrors its quadrant (0,1)
 #pragma unroll
-  for (int it = 0; it < 16; it++) {
-    const int r = (lane >> 4) + 4 * it, rq = r >> 5, ri = r & 31;
-    const int br = rowblk[rq], bc = colblk[cq];
-    if (I == J && rq == 1 && cq == 0) continue;  // mirror of quadrant (0,1) of a diagonal tile
-    if (br <= bc) M[(size_t)(br * JB + ri) * Np + bc * JB + ci] = X[r][c];
-    else M[(size_t)(bc * JB + ri) * Np + br * JB + ci] = X[rq * JB + ci][cq * JB + ri];
+      for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) {
+            const int r = mt * 16 + MM<T>::row(j, lane), cc = nt * 16 + (lane & 15);  // inside the quadrant
+            if (br <= bc) M[(size_t)(br * JB + r) * Np + bc * JB + cc] = acc[mt][nt][j];
+            else M[(size_t)(bc * JB + cc) * Np + br * JB + r] = acc[mt][nt][j];
+          }
+    }
+    __syncthreads();  // W fully consumed before the next tile overwrites it
+    I = In; J = Jn;
   }
 }
 
@@ -420,7 +485,7 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
   float rf[16][2];
 #pragma unroll
   for (int ks = 0; ks < 16; ks++) {
-    const int k = 4 * ks + (lane >> 4);
+    const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
     rf[ks][0] = (float)RJ[k * JT + wc * 32 + (lane & 15)];
     rf[ks][1] = (float)RJ[k * JT + wc * 32 + 16 + (lane & 15)];
   }
@@ -441,7 +506,7 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
     for (int j = 0; j < 2; j++) acc[i][j] = f4{0, 0, 0, 0};
 #pragma unroll
   for (int ks = 0; ks < 16; ks++) {
-    const int k = 4 * ks + (lane >> 4);
+    const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
     const float a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
     acc[0][0] = MM<float>::mma(a0, rf[ks][0], acc[0][0]);
     acc[0][1] = MM<float>::mma(a0, rf[ks][1], acc[0][1]);
@@ -508,10 +573,17 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
   const dim3 gs(P, nimg);
-  const int gg = grid_for_groups(P * (P + 1) / 2, nimg), gu = grid_for_groups((Np / JT) * P, nimg);
+  const int gg = grid_for_groups((P * (P + 1) / 2 + G_CHUNK - 1) / G_CHUNK, nimg), gu = grid_for_groups((Np / JT) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
-      TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
+      // After the first sweep the diagonal blocks are nearly diagonal: two visits out of three only
+      // rotate index pairs across the two blocks (32 steps instead of 63); the full sweep every third
+      // step keeps the entries inside the diagonal blocks converging (cross-only sweeps stall).
+      // (float32 solver: always full sweeps; its rounding noise inside the diagonal blocks needs them)
+      if (sweep == 0 || step % 3 == 0 || sizeof(T) == 4)
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
+      else
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JB)));
       TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg)));
       TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg)));
     }
@@ -524,7 +596,7 @@ static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, Eig
   const int Np = pl.Np;
   TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));
   TC_TIMED(PK_JINIT, 1, st, (jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np)));
-  int groups = pl.groups > 0 ? pl.groups : (pl.B >= 4 * MAX_GROUPS ? MAX_GROUPS : (pl.B >= 4 ? 2 : 1));
+  int groups = pl.groups > 0 ? pl.groups : (pl.B >= 16 ? 4 : (pl.B >= 4 ? 2 : 1));
   if (groups > pl.B) groups = pl.B;
   if (profiling_active()) groups = 1;  // per-kernel timing wants kernels that run alone
   StreamPool* pool = groups > 1 ? helper_streams() : nullptr;
