@@ -51,8 +51,8 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=12, help="images timed through the CPU oracle")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the path shards by image with no exchange; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (the path shards by image with no exchange "
+              "between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -129,6 +129,7 @@ def main():
     achieved = flops / (upd_ms * 1e-3) / 1e12
     peak = PEAK_FP64_MFMA_TFLOPS if args.eig == "f64" else PEAK_FP32_MFMA_TFLOPS
     total_kernel_ms = sum(v[0] for v in kinds.values())
+    sustained = tc.tc_probe_rates()   # what this GPU delivers on register-only MFMA loops and a plain copy
     traffic = None   # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
     pmc = os.path.join(ROOT, "profiles", "jacobi_update_g.%s.pmc.txt" % w.name)
     if os.path.exists(pmc) and args.eig == "f64":
@@ -157,7 +158,9 @@ def main():
                    "input_generation_s": round(gen_s, 1)},
         "roofline": {"kernel": "jacobi_update", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
-                     "avg_launch_us": round(upd_ms * 1e3 / max(upd_launches, 1), 2), "launches": upd_launches},
+                     "avg_launch_us": round(upd_ms * 1e3 / max(upd_launches, 1), 2), "launches": upd_launches,
+                     "frac_of_sustained_mfma": round(achieved / sustained["mfma_f64_tflops" if args.eig == "f64" else "mfma_f32_tflops"], 4)},
+        "sustained_rates": {k: round(v, 1) for k, v in sustained.items()},
         "kernel_ms": {k: round(v[0], 3) for k, v in kinds.items()},
         "kernel_ms_total": round(total_kernel_ms, 3),
     }

@@ -61,7 +61,9 @@ typedef enum {
 
 typedef enum { TC_F32 = 0, TC_BF16 = 1 } tc_dtype;          /* storage of Q,K,V,O,X,X_out */
 typedef enum { TC_NORM_NONE = 0, TC_NORM_MINMAX = 1 } tc_norm;
-typedef enum { TC_EIG_F64 = 0, TC_EIG_F32 = 1 } tc_eig_dtype; /* arithmetic of Gram + eigensolver */
+/* arithmetic of the Gram matrix and of the eigenvalue iteration (the eigenvectors are accumulated in
+   float32 either way); TC_EIG_F32 is only accurate enough for well-conditioned spectra */
+typedef enum { TC_EIG_F64 = 0, TC_EIG_F32 = 1 } tc_eig_dtype;
 
 typedef struct {
   int32_t batch;        /* B >= 0 (B == 0: nothing is launched, TC_OK)                         */
@@ -80,7 +82,8 @@ typedef struct {
   int32_t k_prune;      /* k_p: 1 <= k_final <= k_prune <= n_vis, k_prune - k_final <= |B|      */
   int32_t k_final;      /* k_f                                                                  */
   int32_t jacobi_max_sweeps; /* 0 => 30                                                         */
-  float jacobi_tol;     /* stop when off(G)/||G||_F measured during a sweep < tol; 0 => default */
+  float jacobi_tol;     /* stop when off(G)/||G||_F measured during a sweep < tol;
+                           0 => 1e-8 (3e-6 for TC_EIG_F32)                                      */
   int32_t eig_dtype;    /* tc_eig_dtype                                                         */
   int32_t stream_groups; /* eigensolver: 0 = cut the batch into up to 4 groups that run on helper
                             streams and overlap; 1 = everything on `stream`; 2..4 = that many groups */
@@ -170,6 +173,15 @@ TC_API int tc_profile_compress(const tc_params* p, const void* Q, const void* K,
                                void* X_out, int32_t* kept_idx, int32_t* merge_dst, int32_t* info, void* ws,
                                size_t ws_bytes, void* stream, float* ms_by_kind, int32_t* launches_by_kind,
                                float* jacobi_update_ms_by_sweep, int32_t max_sweeps_out);
+
+/*
+ * Measurement aid: sustained rates of this GPU, for reading roofline fractions against what the part
+ * actually delivers.  Runs register-only loops of independent matrix-core products (fp64 16x16x4,
+ * fp32 16x16x4, bf16 32x32x16) and a streaming copy of 128 MiB inside `ws` (ws_bytes >= 256 MiB,
+ * contents destroyed), waits for them, and writes to the HOST array rates[4]:
+ * TFLOP/s fp64, TFLOP/s fp32, TFLOP/s bf16, GB/s copied (read + written).  Blocks the calling thread.
+ */
+TC_API int tc_probe_rates(void* ws, size_t ws_bytes, void* stream, float* rates);
 
 #ifdef __cplusplus
 }

@@ -18,7 +18,7 @@ TC_NORM_NONE, TC_NORM_MINMAX = 0, 1
 TC_EIG_F64, TC_EIG_F32 = 0, 1
 
 SYMBOLS = ("tc_workspace_bytes", "tc_status_string", "tc_attn_output", "tc_ipgs_score", "tc_select_topk",
-           "tc_merge", "tc_compress", "tc_profile_compress")
+           "tc_merge", "tc_compress", "tc_profile_compress", "tc_probe_rates")
 PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_update_u", "jacobi_sweep_end",
               "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average")
 
@@ -82,6 +82,7 @@ def load_library():
     lib.tc_merge.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_profile_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, ctypes.c_int32]
+    lib.tc_probe_rates.argtypes = [vp, sz, vp, vp]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -173,3 +174,12 @@ def tc_profile_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, info, ws, max
                                               _ptr(merge_dst, torch.int32), _ptr(info, torch.int32), _ptr(ws),
                                               ws.numel(), _stream(stream), ms, cnt, per_sweep, max_sweeps_out))
     return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(PROF_KINDS)}, [float(x) for x in per_sweep]
+
+
+def tc_probe_rates(stream=None):
+    """Sustained {fp64, fp32, bf16} matrix-core TFLOP/s and streaming-copy GB/s of the current GPU."""
+    ws = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    rates = (ctypes.c_float * 4)()
+    _check(load_library().tc_probe_rates(_ptr(ws), ws.numel(), _stream(stream), rates))
+    return {"mfma_f64_tflops": float(rates[0]), "mfma_f32_tflops": float(rates[1]),
+            "mfma_bf16_tflops": float(rates[2]), "copy_gbps": float(rates[3])}

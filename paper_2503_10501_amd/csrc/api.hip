@@ -49,7 +49,6 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.off_offpart = take(B * (size_t)q.P * q.steps * 8);
   q.off_state = take(B * sizeof(EigState));
   q.off_sig = take(B * Np * 8);
-  q.off_sigsort = take(B * Np * 4);
   q.off_C = take(B * N * 4);
   q.off_E = take(B * N * 4);
   q.off_order = take(B * q.kp * 4);
@@ -57,7 +56,6 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.off_sim = take(B * (size_t)q.nB * (q.nA > 0 ? q.nA : 1) * 4);
   q.off_mlist = take(B * (size_t)(q.m > 0 ? q.m : 1) * 8);
   q.off_info = take(B * 4);
-  q.off_minmax = take(B * 16);
   q.total = off > 0 ? off : 256;
   return TC_OK;
 }
@@ -82,7 +80,7 @@ static int ipgs_chain(const Plan& pl, const tc_params* p, const void* O, const f
   rc = launch_jacobi(pl, p->eig_dtype, G, U, at<char>(ws, pl.off_R), at<double>(ws, pl.off_offpart), state, st);
   if (rc != TC_OK) return rc;
   return launch_scores(pl, p->eig_dtype, G, U, state, S, p->lambda, p->norm_mode, p->sv_rtol, at<char>(ws, pl.off_sig),
-                       at<float>(ws, pl.off_C), at<float>(ws, pl.off_minmax), score, ics, sigma, info, st);
+                       at<float>(ws, pl.off_C), score, ics, sigma, info, st);
 }
 
 }  // namespace tc

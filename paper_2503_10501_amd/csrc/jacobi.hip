@@ -142,6 +142,16 @@ __device__ inline void rotation(float aii, float ajj, float aij, float* c, float
 //     rotation, wavefronts specialised for S and for R, one block per lane on 12 wavefronts, and
 //     index/address lookup tables in LDS or global memory -- the step time is set by LDS traffic and
 //     the barrier-to-barrier chain, which this arrangement keeps shortest.
+// Value held by lane `l` (l uniform over the wavefront), delivered through a scalar register.
+__device__ inline float lane_value(float v, int l) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ inline double lane_value(double v, int l) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), l);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), l);
+  return __hiloint2double(hi, lo);
+}
+
 constexpr int SOLVE_WAVES = 8;
 constexpr int SEATS = JB / SOLVE_WAVES;  // seats per wavefront
 constexpr int N_BLOCKS = JB * (JB + 1) / 2;
@@ -252,12 +262,16 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
       tJ[g] = next_top(tJ[g]); bJ[g] = next_bot(bJ[g]);
     }
     // ---- R <- R J on this wavefront's seats -------------------------------------------------------
+    {
+      // one LDS read per lane, then scalar broadcasts: lane k (k < SEATS) holds the rotation of seat k
+      const T myc = rc[SEATS * wave + (lane & (SEATS - 1))], myz = rs[SEATS * wave + (lane & (SEATS - 1))];
 #pragma unroll
-    for (int k = 0; k < SEATS; k++) {
-      const T c = rc[SEATS * wave + k], z = rs[SEATS * wave + k];
-      const T x = rtop[k], y = rbot[k];
-      rtop[k] = c * x - z * y;
-      rbot[k] = z * x + c * y;
+      for (int k = 0; k < SEATS; k++) {
+        const T c = lane_value(myc, k), z = lane_value(myz, k);
+        const T x = rtop[k], y = rbot[k];
+        rtop[k] = c * x - z * y;
+        rbot[k] = z * x + c * y;
+      }
     }
     // move the columns one seat along the cycle
     if (CROSS) {  // tops stay, every bottom moves to the seat before it (seat 0's to seat 31)
@@ -313,6 +327,7 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
 // columns of pair J is gathered (a quadrant whose block lies below the diagonal is read from its
 // mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and is scattered back to
 // the stored blocks.  The mirror tile (J,I) is never formed.
+constexpr int FULL_EVERY = 6;  // after the first sweep, one solve in FULL_EVERY is a full 63-step sweep
 constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup
 
 // Tile index t (row-major over the upper triangle of pair pairs, row I holds P - I tiles) -> (I, J).
@@ -576,11 +591,11 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
   const int gg = grid_for_groups((P * (P + 1) / 2 + G_CHUNK - 1) / G_CHUNK, nimg), gu = grid_for_groups((Np / JT) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
-      // After the first sweep the diagonal blocks are nearly diagonal: two visits out of three only
-      // rotate index pairs across the two blocks (32 steps instead of 63); the full sweep every third
-      // step keeps the entries inside the diagonal blocks converging (cross-only sweeps stall).
+      // After the first sweep the diagonal blocks are nearly diagonal: most visits only rotate index
+      // pairs across the two blocks (32 steps instead of 63); a full sweep every FULL_EVERY-th step
+      // keeps the entries inside the diagonal blocks converging (cross-only sweeps stall).
       // (float32 solver: always full sweeps; its rounding noise inside the diagonal blocks needs them)
-      if (sweep == 0 || step % 3 == 0 || sizeof(T) == 4)
+      if (sweep == 0 || step % FULL_EVERY == 0 || sizeof(T) == 4)
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
       else
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JB)));

@@ -120,9 +120,8 @@ static int run_scores(const Plan& pl, const T* G, const float* U, const EigState
 }
 
 int launch_scores(const Plan& pl, int eig_dtype, const void* G, const void* U, const EigState* state, const float* S,
-                  float lambda, int norm_mode, float sv_rtol, void* sig_ws, float* C_ws, float* minmax_ws, float* E,
-                  float* C_out, float* sigma_out, int32_t* info_out, hipStream_t st) {
-  (void)minmax_ws;
+                  float lambda, int norm_mode, float sv_rtol, void* sig_ws, float* C_ws, float* E, float* C_out,
+                  float* sigma_out, int32_t* info_out, hipStream_t st) {
   if (eig_dtype == TC_EIG_F64)
     return run_scores<double>(pl, (const double*)G, (const float*)U, state, S, lambda, norm_mode, sv_rtol,
                               (double*)sig_ws, C_ws, E, C_out, sigma_out, info_out, st);

@@ -39,8 +39,8 @@ struct Plan {
   int groups;    // requested stream groups (0 = automatic)
   double tol;
   float scale;
-  size_t off_O, off_S, off_Spart, off_G, off_U, off_R, off_offpart, off_state, off_sig, off_sigsort, off_C,
-      off_E, off_order, off_rnorm, off_sim, off_mlist, off_info, off_minmax;
+  size_t off_O, off_S, off_Spart, off_G, off_U, off_R, off_offpart, off_state, off_sig, off_C, off_E, off_order,
+      off_rnorm, off_sim, off_mlist, off_info;
   size_t total;
 };
 
@@ -55,8 +55,8 @@ int launch_gram(const Plan& pl, int dtype, int eig_dtype, const void* O, void* G
 int launch_jacobi(const Plan& pl, int eig_dtype, void* G, void* U, void* R, double* offpart, EigState* state,
                   hipStream_t st);
 int launch_scores(const Plan& pl, int eig_dtype, const void* G, const void* U, const EigState* state,
-                  const float* S, float lambda, int norm_mode, float sv_rtol, void* sig_ws, float* C_ws,
-                  float* minmax_ws, float* E, float* C_out, float* sigma_out, int32_t* info_out, hipStream_t st);
+                  const float* S, float lambda, int norm_mode, float sv_rtol, void* sig_ws, float* C_ws, float* E,
+                  float* C_out, float* sigma_out, int32_t* info_out, hipStream_t st);
 int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st);
 int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, const int32_t* order, void* X_out,
                  int32_t* kept_idx, int32_t* merge_dst, float* rnorm, float* sim, int32_t* mlist, hipStream_t st);

@@ -40,6 +40,24 @@ def test_tiny_config_all_stages():
     assert min(rep["jaccard_vs_independent_oracle"]) == 1.0
 
 
+def test_tiny_config_matches_the_stored_oracle_fixture():
+    import json
+    import os
+    tc, gu, _, CONFIGS, _ = _mods()
+    from workloads import make_batch
+    doc = json.load(open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_oracle.json")))
+    w = CONFIGS["tiny"]
+    b = make_batch(w, [0])
+    p = tc.params_for(w, batch=1)
+    out = gu.compress(p, gu.dev(b["Q"], p), gu.dev(b["K"], p), gu.dev(b["V"], p),
+                      gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p))
+    np.testing.assert_allclose(gu.host(out["E"])[0], doc["E"], rtol=0, atol=1e-4)
+    assert gu.host(out["order"])[0].tolist() == doc["order"]
+    assert gu.host(out["kept_idx"])[0].tolist() == doc["kept_idx"]
+    assert gu.host(out["merge_dst"])[0].tolist() == doc["merge_dst"]
+    np.testing.assert_allclose(gu.host(out["X_out"])[0][0][:8], doc["X_out_row0_first8"], rtol=1e-5)
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 @pytest.mark.parametrize("causal", [1, 0])
 def test_small_shapes_all_stages(name, causal):
