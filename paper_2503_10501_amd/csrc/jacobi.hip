@@ -129,19 +129,27 @@ __device__ inline void rotation(float aii, float ajj, float aij, float* c, float
 // (CROSS = true, 32 steps) only pairs with one index in each of the two blocks are rotated:
 // top = i, bottom = 32 + (i + st) mod 32.  A rotation is stored in seat orientation: top' = c top - s bottom,
 // bottom' = s top + c bottom.
-//   * S is symmetric and lives in LDS, element {x,y} stored once at S[min][max].  A step acts on it
-//     as 2x2 blocks (rows of seat I) x (columns of seat J), I <= J: 528 blocks, one per lane, the
-//     seat pair of a lane fixed for the whole kernel.
+//   * S is symmetric and lives in LDS as the 528 2x2 blocks (rows of seat I) x (columns of seat J),
+//     I <= J, one block per lane, the seat pair of a lane fixed for the whole kernel.  Storage is by
+//     seat, not by index: plane 0 holds the (top,top),(top,bottom) pair of every block, plane 1 the
+//     (bottom,top),(bottom,bottom) pair, so a lane reads its block with two 16-byte loads that are
+//     contiguous across lanes.  Since the indices move between seats by the same permutation every
+//     step, each rotated element has a fixed destination slot (computed once per lane); it is
+//     written there in a second buffer, and the two buffers swap roles every step.  Of a diagonal
+//     block (I,I) only tt, tb and bb are kept.
 //   * R never touches LDS for arithmetic: lane r holds row r of R in registers with the columns in
 //     seat order -- wavefront w owns seats 4w..4w+3 -- so every step rotates fixed register pairs;
 //     afterwards the columns move one seat along the tournament cycle, a register renaming inside a
 //     wavefront plus one column handed to each neighbouring wavefront through a small LDS buffer.
 //     After 63 steps the seats are back in their starting order.
-//   * Per step: lanes 0..31 of wavefront 0 compute the 32 rotations (barrier), all lanes apply
-//     them (barrier).  Measured alternatives that were slower on MI355X: every lane computing its own
+//   * A ninth wavefront computes the 32 rotations of step st+1 while the other eight apply the
+//     rotations of step st to R (which needs no S), so a step is: S update (barrier) then
+//     {next rotations | R update} (barrier).  The ninth wavefront also holds the 16 blocks of S that
+//     do not fit one-per-lane on eight wavefronts.  Measured alternatives that were slower on
+//     MI355X: rotations and R update in sequence on eight wavefronts, every lane computing its own
 //     rotation, wavefronts specialised for S and for R, one block per lane on 12 wavefronts, and
-//     index/address lookup tables in LDS or global memory -- the step time is set by LDS traffic and
-//     the barrier-to-barrier chain, which this arrangement keeps shortest.
+//     index/address lookup tables in LDS or global memory -- the step time is the barrier-to-barrier
+//     latency chain (LDS is about one third busy), which this arrangement keeps shortest.
 // Value held by lane `l` (l uniform over the wavefront), delivered through a scalar register.
 __device__ inline float lane_value(float v, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
@@ -152,87 +160,205 @@ __device__ inline double lane_value(double v, int l) {
   return __hiloint2double(hi, lo);
 }
 
-constexpr int SOLVE_WAVES = 8;
-constexpr int SEATS = JB / SOLVE_WAVES;  // seats per wavefront
+constexpr int SOLVE_WAVES = 8;                          // wavefronts that hold blocks of S and columns of R
+constexpr int SOLVE_THREADS = 64 * (SOLVE_WAVES + 1);   // plus the rotation wavefront
+// Declared bound of the kernel.  With a bound of 9 wavefronts the compiler derives "at most 7
+// wavefronts per SIMD" from the wave slots and pads the register allocation to 65 (72 allocated),
+// after which only two workgroups fit a compute unit; a bound of 10 leaves the allocation at 64 and
+// three fit.
+constexpr int SOLVE_BOUND = 64 * (SOLVE_WAVES + 2);
+constexpr int SEATS = JB / SOLVE_WAVES;                 // seats per wavefront
 constexpr int N_BLOCKS = JB * (JB + 1) / 2;
+static_assert(N_BLOCKS - 64 * SOLVE_WAVES <= 32, "left-over blocks go to lanes 32..63 of the rotation wavefront");
 
 __device__ inline int next63(int x) { return x == 62 ? 0 : x + 1; }
 
+template <typename T>
+struct alignas(2 * sizeof(T)) Pair2 {
+  T x, y;
+};
+
+// Seat position p in [0,64): p < 32 is the top of seat p, p >= 32 the bottom of seat p - 32.
+// Where the index sitting at position p moves in one step.
+template <bool CROSS>
+__device__ inline int next_position(int p) {
+  if (CROSS) return p < JB ? p : JB + ((p - JB) + JB - 1) % JB;  // tops stay, bottoms move one seat down
+  if (p == 0) return 0;                                          // seat 0's top never moves
+  if (p == 1) return JB;                                         // top of seat 1 -> bottom of seat 0
+  if (p < JB) return p - 1;                                      // tops move towards seat 1
+  if (p == JT - 1) return JB - 1;                                // bottom of seat 31 -> top of seat 31
+  return p + 1;                                                  // bottoms move away from seat 0
+}
+
+__device__ inline int block_id(int I, int J) { return I * JB - I * (I - 1) / 2 + (J - I); }  // I <= J
+
+// Slot (in elements of one buffer) of the symmetric element whose row sits at position a and whose
+// column sits at position b.
+__device__ inline int slot_of(int a, int b) {
+  int I = a & (JB - 1), kr = a >> 5, J = b & (JB - 1), kc = b >> 5;
+  if (I > J || (I == J && kr > kc)) { int t = I; I = J; J = t; t = kr; kr = kc; kc = t; }
+  return kr * (2 * N_BLOCKS) + 2 * block_id(I, J) + kc;
+}
+
 template <typename T, bool CROSS>
-__global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
-                                                                 double* __restrict__ offpart,
-                                                                 const EigState* __restrict__ state, int Np, int nblk,
-                                                                 int step, int img0, int inner_steps) {
+__global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
+                                                            double* __restrict__ offpart,
+                                                            const EigState* __restrict__ state, int Np, int nblk,
+                                                            int step, int img0, int inner_steps) {
   const int b = img0 + blockIdx.y, pair = blockIdx.x, P = nblk / 2;
   if (state[b].done) return;
-  __shared__ T S[JT][SLD];
+  constexpr int BUF = 4 * N_BLOCKS;  // elements of one buffer: two planes of N_BLOCKS pairs
+  constexpr int STAGE = JT * SLD;    // the finished R is staged here for row-contiguous stores
+  __shared__ __attribute__((aligned(16))) T SB[(2 * BUF > STAGE ? 2 * BUF : STAGE)];
   __shared__ T xtop[SOLVE_WAVES][JT], xbot[SOLVE_WAVES][JT];
-  __shared__ T rc[JB], rs[JB];
-  __shared__ double red[SOLVE_WAVES];
+  __shared__ Pair2<T> rcs[JB];  // (c, z) of every seat
+  __shared__ double red[SOLVE_WAVES + 1];
   int p, q;
   round_robin_pair(nblk, step, pair, &p, &q);
   const T* Gb = G + (size_t)b * Np * Np;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  {
-    const int c = lane, gc = (c < JB ? p * JB + c : q * JB + c - JB);
-    double off = 0.0;
-    for (int r = wave; r < JT; r += SOLVE_WAVES) {
-      if (r >= JB && c < JB) continue;  // block (q,p) is not stored; S is only used for r <= c
-      const int gr = (r < JB ? p * JB + r : q * JB + r - JB);
-      const T v = Gb[(size_t)gr * Np + gc];
-      S[r][c] = v;
-      const double dv = (double)v;
-      if (r < JB && c >= JB) off += 2.0 * dv * dv;                           // G_pq and its mirror
-      else if (r < c) off += 2.0 * dv * dv / (double)(nblk - 1);             // inside G_pp, G_qq (seen nblk-1 times)
-    }
-    off = wave_sum(off);
-    if (lane == 0) red[wave] = off;
-  }
-  // R = I in seat order.  Full sweep, step 0: top_i = i, top_0 = 63, bottom_i = (63 - i) mod 63.
+  const bool rwave = wave == SOLVE_WAVES;  // the rotation wavefront
+  // Indices at step 0.  Full sweep: top_i = i, top_0 = 63, bottom_i = (63 - i) mod 63.
   // Cross sweep: top_i = i stays, bottom_i = 32 + (i + st) mod 32.
   auto top0 = [](int i) { return CROSS ? i : (i == 0 ? 63 : i); };
   auto bot0 = [](int i) { return CROSS ? JB + i : (63 - i) % 63; };
   auto next_top = [](int x) { return CROSS || x == 63 ? x : next63(x); };
   auto next_bot = [](int x) { return CROSS ? (x == JT - 1 ? JB : x + 1) : next63(x); };
-  T rtop[SEATS], rbot[SEATS];
+  // the block of S this lane owns: task tid on wavefronts 0..7, task 512 + lane - 32 on the rotation wavefront
+  const int task = rwave ? 64 * SOLVE_WAVES + lane - 32 : tid;
+  const bool act = !rwave || (lane >= 32 && task < N_BLOCKS);
+  int sI = 0, sJ = act ? task : 0;  // row I of the upper triangle holds JB - I blocks
+  while (sJ >= JB - sI) { sJ -= JB - sI; sI++; }
+  sJ += sI;
+  const bool diag = sI == sJ;
+  const int rd = 2 * block_id(sI, sJ);  // this lane's (tt,tb) pair; (bt,bb) sits 2*N_BLOCKS further
+  // destinations of the four rotated elements in the other buffer
+  const int pTI = next_position<CROSS>(sI), pBI = next_position<CROSS>(JB + sI);
+  const int pTJ = next_position<CROSS>(sJ), pBJ = next_position<CROSS>(JB + sJ);
+  const int wtt = slot_of(pTI, pTJ), wtb = slot_of(pTI, pBJ), wbb = slot_of(pBI, pBJ);
+  const int wbt = diag ? 2 * N_BLOCKS + rd : slot_of(pBI, pTJ);  // (a diagonal block's bt is a copy of tb: parked in an unused slot)
+  double off = 0.0;
+  if (act) {
+    // Load the block from G: element {r,c} of the subproblem, r and c in 0..63 (first the rows and
+    // columns of block p, then of block q).  Block (q,p) is not stored: read its mirror.
+    auto gload = [&](int r, int c) {
+      if (r >= JB && c < JB) { const int t = r; r = c; c = t; }
+      const int gr = (r < JB ? p * JB + r : q * JB + r - JB), gc = (c < JB ? p * JB + c : q * JB + c - JB);
+      return Gb[(size_t)gr * Np + gc];
+    };
+    auto weight = [&](int r, int c) {  // share of v^2 in the off-diagonal mass of this visit
+      if (r == c) return 0.0;
+      return ((r < JB) == (c < JB)) ? 2.0 / (double)(nblk - 1) : 2.0;  // inside G_pp, G_qq: seen nblk-1 times per sweep
+    };
+    const int iTI = top0(sI), iBI = bot0(sI), iTJ = top0(sJ), iBJ = bot0(sJ);
+    const T ett = gload(iTI, iTJ), etb = gload(iTI, iBJ), ebt = gload(iBI, iTJ), ebb = gload(iBI, iBJ);
+    *reinterpret_cast<Pair2<T>*>(&SB[rd]) = Pair2<T>{ett, etb};
+    *reinterpret_cast<Pair2<T>*>(&SB[2 * N_BLOCKS + rd]) = Pair2<T>{ebt, ebb};
+    off = weight(iTI, iTJ) * (double)ett * (double)ett + weight(iTI, iBJ) * (double)etb * (double)etb +
+          weight(iBI, iBJ) * (double)ebb * (double)ebb;
+    if (!diag) off += weight(iBI, iTJ) * (double)ebt * (double)ebt;
+  }
+  off = wave_sum(off);
+  if (lane == 0) red[wave] = off;
+  T rtop[SEATS], rbot[SEATS];  // columns of R in seat order (wavefronts 0..7), R = I at the start
 #pragma unroll
   for (int k = 0; k < SEATS; k++) {
-    const int i = SEATS * wave + k;
+    const int i = SEATS * (rwave ? 0 : wave) + k;
     rtop[k] = (lane == top0(i)) ? T(1) : T(0);
     rbot[k] = (lane == bot0(i)) ? T(1) : T(0);
   }
-  // blocks of this lane: task tid (all 512 lanes) and, on the last wavefront, task 512 + lane
-  int tI[2], bI[2], tJ[2], bJ[2], sI[2], sJ[2];
-  bool act[2];
-#pragma unroll
-  for (int g = 0; g < 2; g++) {
-    const int t = g == 0 ? tid : 512 + lane;
-    act[g] = g == 0 || (wave == SOLVE_WAVES - 1 && t < N_BLOCKS);
-    int I = 0, J = act[g] ? t : 0;  // row I of the upper triangle holds JB - I blocks
-    while (J >= JB - I) { J -= JB - I; I++; }
-    J += I;
-    sI[g] = I; sJ[g] = J;
-    tI[g] = top0(I); bI[g] = bot0(I);
-    tJ[g] = top0(J); bJ[g] = bot0(J);
-  }
-  int rt = top0(lane & 31), rb = bot0(lane & 31);  // seat lane%32, for the rotations
+  int rt = top0(lane & 31), rb = bot0(lane & 31);  // indices in seat lane%32, for the rotations
+  const int rdd = 2 * block_id(lane & 31, lane & 31);
   __syncthreads();
   if (tid == 0) {
     double tot = 0.0;
-    for (int w = 0; w < SOLVE_WAVES; w++) tot += red[w];
+    for (int w = 0; w <= SOLVE_WAVES; w++) tot += red[w];
     offpart[((size_t)b * (nblk - 1) + step) * P + pair] = tot;
   }
+  auto make_rotations = [&](int buf) {  // lanes 0..31 of the rotation wavefront; S is read from buffer buf
+    const Pair2<T> d = *reinterpret_cast<const Pair2<T>*>(&SB[buf * BUF + rdd]);
+    const T abb = SB[buf * BUF + 2 * N_BLOCKS + rdd + 1];
+    // rotation() wants the pair ordered by index; a rotation is stored in seat orientation
+    // (top' = c top - z bottom, bottom' = z top + c bottom)
+    const bool flip = rt > rb;
+    T c, s;
+    rotation(flip ? abb : d.x, flip ? d.x : abb, d.y, &c, &s);
+    rcs[lane] = Pair2<T>{c, flip ? -s : s};
+    rt = next_top(rt);
+    rb = next_bot(rb);
+  };
+  if (rwave && lane < JB && inner_steps > 0) make_rotations(0);
+  __syncthreads();
 
   for (int st = 0; st < inner_steps; st++) {  // a whole sweep brings the seats back to their starting order
-    if (tid < JB) {
-      const int a = min(rt, rb), bq = max(rt, rb);
-      T c, s;
-      rotation(S[a][a], S[bq][bq], S[a][bq], &c, &s);
-      rc[tid] = c;
-      rs[tid] = rt > rb ? -s : s;  // seat orientation: the top index is the larger one
+    const int cur = (st & 1) * BUF, nxt = BUF - cur;
+    // ---- S <- J^T S J (not needed after the last step: only R leaves the kernel) ------------------
+    if (act && st + 1 < inner_steps) {
+      const Pair2<T> rI = rcs[sI], rJ = rcs[sJ];
+      const Pair2<T> et = *reinterpret_cast<const Pair2<T>*>(&SB[cur + rd]);
+      const Pair2<T> eb = *reinterpret_cast<const Pair2<T>*>(&SB[cur + 2 * N_BLOCKS + rd]);
+      const T cI = rI.x, zI = rI.y, cJ = rJ.x, zJ = rJ.y;
+      const T ett = et.x, etb = et.y, ebt = diag ? et.y : eb.x, ebb = eb.y;
+      const T ftt = cI * ett - zI * ebt, fbt = zI * ett + cI * ebt;  // rows of seat I
+      const T ftb = cI * etb - zI * ebb, fbb = zI * etb + cI * ebb;
+      SB[nxt + wtt] = cJ * ftt - zJ * ftb;                            // columns of seat J
+      SB[nxt + wtb] = zJ * ftt + cJ * ftb;
+      SB[nxt + wbt] = cJ * fbt - zJ * fbb;
+      SB[nxt + wbb] = zJ * fbt + cJ * fbb;
     }
-    if (st > 0) {  // columns handed over by the neighbours at the end of the previous step
+    Pair2<T> mine = {T(0), T(0)};
+    if (!rwave) {
+      // one LDS read per lane, scalar broadcasts later: lane k (k < SEATS) holds the rotation of seat k
+      mine = rcs[SEATS * wave + (lane & (SEATS - 1))];
+      if (st > 0) {  // columns handed over by the neighbours during the previous step
+        if (CROSS) {
+          rbot[SEATS - 1] = xbot[(wave + 1) % SOLVE_WAVES][lane];
+        } else {
+          if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
+          if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+        }
+      }
+    }
+    __syncthreads();  // S is up to date; the rotation table and the hand-over buffers have been read
+    if (rwave) {
+      if (lane < JB && st + 1 < inner_steps) make_rotations(nxt / BUF);
+    } else {
+      // ---- R <- R J on this wavefront's seats -----------------------------------------------------
+#pragma unroll
+      for (int k = 0; k < SEATS; k++) {
+        const T c = lane_value(mine.x, k), z = lane_value(mine.y, k);
+        const T x = rtop[k], y = rbot[k];
+        rtop[k] = c * x - z * y;
+        rbot[k] = z * x + c * y;
+      }
+      // move the columns one seat along the cycle
+      if (CROSS) {  // tops stay, every bottom moves to the seat before it (seat 0's to seat 31)
+        const T out_bot = rbot[0];
+#pragma unroll
+        for (int k = 0; k < SEATS - 1; k++) rbot[k] = rbot[k + 1];
+        xbot[wave][lane] = out_bot;  // becomes the last bottom of the wavefront before
+      } else {  // tops move towards seat 1, bottoms away from seat 0
+        const T out_top = rtop[0], out_bot = rbot[SEATS - 1], top1 = rtop[1];
+        if (wave == 0) {
+#pragma unroll
+          for (int k = 1; k < SEATS - 1; k++) rtop[k] = rtop[k + 1];  // seat 0's top (index 63) never moves
+        } else {
+#pragma unroll
+          for (int k = 0; k < SEATS - 1; k++) rtop[k] = rtop[k + 1];
+        }
+        if (wave == SOLVE_WAVES - 1) rtop[SEATS - 1] = rbot[SEATS - 1];  // top_31 <- bottom_31
+#pragma unroll
+        for (int k = SEATS - 1; k > 0; k--) rbot[k] = rbot[k - 1];
+        if (wave == 0) rbot[0] = top1;                                    // bottom_0 <- top_1
+        if (wave > 0) xtop[wave][lane] = out_top;                         // becomes the last top of wave-1
+        if (wave < SOLVE_WAVES - 1) xbot[wave][lane] = out_bot;           // becomes the first bottom of wave+1
+      }
+    }
+    __syncthreads();  // next rotations and the handed-over columns are visible
+  }
+  if (!rwave) {
+    if (inner_steps > 0) {
       if (CROSS) {
         rbot[SEATS - 1] = xbot[(wave + 1) % SOLVE_WAVES][lane];
       } else {
@@ -240,84 +366,18 @@ __global__ __launch_bounds__(64 * SOLVE_WAVES) void jacobi_solve(const T* __rest
         if (wave > 0) rbot[0] = xbot[wave - 1][lane];
       }
     }
-    __syncthreads();
-    // ---- S <- J^T S J -----------------------------------------------------------------------------
+    // after a whole sweep (63 or 32 steps) the seats are back in their step-0 order; stage R through
+    // LDS (S is no longer needed) for row-contiguous stores
 #pragma unroll
-    for (int g = 0; g < 2; g++) {
-      if (act[g]) {
-        const T cI = rc[sI[g]], zI = rs[sI[g]], cJ = rc[sJ[g]], zJ = rs[sJ[g]];
-        T* ptt = &S[min(tI[g], tJ[g])][max(tI[g], tJ[g])];
-        T* ptb = &S[min(tI[g], bJ[g])][max(tI[g], bJ[g])];
-        T* pbt = &S[min(bI[g], tJ[g])][max(bI[g], tJ[g])];
-        T* pbb = &S[min(bI[g], bJ[g])][max(bI[g], bJ[g])];
-        const T ett = *ptt, etb = *ptb, ebt = *pbt, ebb = *pbb;
-        const T ftt = cI * ett - zI * ebt, fbt = zI * ett + cI * ebt;  // rows of seat I
-        const T ftb = cI * etb - zI * ebb, fbb = zI * etb + cI * ebb;
-        *ptt = cJ * ftt - zJ * ftb;                                     // columns of seat J
-        *ptb = zJ * ftt + cJ * ftb;
-        *pbt = cJ * fbt - zJ * fbb;
-        *pbb = zJ * fbt + cJ * fbb;
-      }
-      tI[g] = next_top(tI[g]); bI[g] = next_bot(bI[g]);
-      tJ[g] = next_top(tJ[g]); bJ[g] = next_bot(bJ[g]);
+    for (int k = 0; k < SEATS; k++) {
+      const int i = SEATS * wave + k;
+      SB[lane * SLD + top0(i)] = rtop[k];
+      SB[lane * SLD + bot0(i)] = rbot[k];
     }
-    // ---- R <- R J on this wavefront's seats -------------------------------------------------------
-    {
-      // one LDS read per lane, then scalar broadcasts: lane k (k < SEATS) holds the rotation of seat k
-      const T myc = rc[SEATS * wave + (lane & (SEATS - 1))], myz = rs[SEATS * wave + (lane & (SEATS - 1))];
-#pragma unroll
-      for (int k = 0; k < SEATS; k++) {
-        const T c = lane_value(myc, k), z = lane_value(myz, k);
-        const T x = rtop[k], y = rbot[k];
-        rtop[k] = c * x - z * y;
-        rbot[k] = z * x + c * y;
-      }
-    }
-    // move the columns one seat along the cycle
-    if (CROSS) {  // tops stay, every bottom moves to the seat before it (seat 0's to seat 31)
-      const T out_bot = rbot[0];
-#pragma unroll
-      for (int k = 0; k < SEATS - 1; k++) rbot[k] = rbot[k + 1];
-      xbot[wave][lane] = out_bot;  // becomes the last bottom of the wavefront before
-    } else {  // tops move towards seat 1, bottoms away from seat 0
-      const T out_top = rtop[0], out_bot = rbot[SEATS - 1], top1 = rtop[1];
-      if (wave == 0) {
-#pragma unroll
-        for (int k = 1; k < SEATS - 1; k++) rtop[k] = rtop[k + 1];  // seat 0's top (index 63) never moves
-      } else {
-#pragma unroll
-        for (int k = 0; k < SEATS - 1; k++) rtop[k] = rtop[k + 1];
-      }
-      if (wave == SOLVE_WAVES - 1) rtop[SEATS - 1] = rbot[SEATS - 1];  // top_31 <- bottom_31
-#pragma unroll
-      for (int k = SEATS - 1; k > 0; k--) rbot[k] = rbot[k - 1];
-      if (wave == 0) rbot[0] = top1;                                    // bottom_0 <- top_1
-      if (wave > 0) xtop[wave][lane] = out_top;                         // becomes the last top of wave-1
-      if (wave < SOLVE_WAVES - 1) xbot[wave][lane] = out_bot;           // becomes the first bottom of wave+1
-    }
-    rt = next_top(rt);
-    rb = next_bot(rb);
-    __syncthreads();  // S, the rotation table and the hand-over buffers are free for the next step
-  }
-  if (inner_steps > 0) {
-    if (CROSS) {
-      rbot[SEATS - 1] = xbot[(wave + 1) % SOLVE_WAVES][lane];
-    } else {
-      if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
-      if (wave > 0) rbot[0] = xbot[wave - 1][lane];
-    }
-  }
-  // after a whole sweep (63 or 32 steps) the seats are back in their step-0 order; stage R through
-  // LDS for row-contiguous stores
-#pragma unroll
-  for (int k = 0; k < SEATS; k++) {
-    const int i = SEATS * wave + k;
-    S[lane][top0(i)] = rtop[k];
-    S[lane][bot0(i)] = rbot[k];
   }
   __syncthreads();
   T* Rb = R + ((size_t)b * P + pair) * JT * JT;
-  for (int e = tid; e < JT * JT; e += 64 * SOLVE_WAVES) Rb[e] = S[e >> 6][e & 63];
+  for (int e = tid; e < JT * JT; e += SOLVE_THREADS) Rb[e] = SB[(e >> 6) * SLD + (e & 63)];
 }
 
 // ---------------------------------------------------------------------------------------
@@ -596,9 +656,9 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
       // keeps the entries inside the diagonal blocks converging (cross-only sweeps stall).
       // (float32 solver: always full sweeps; its rounding noise inside the diagonal blocks needs them)
       if (sweep == 0 || step % FULL_EVERY == 0 || sizeof(T) == 4)
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
       else
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, 64 * SOLVE_WAVES, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JB)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JB)));
       TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg)));
       TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg)));
     }
