@@ -76,23 +76,26 @@ __global__ __launch_bounds__(1024) void jacobi_init_state(const T* __restrict__ 
 // Plane rotation that annihilates a_ij of [[a_ii a_ij][a_ij a_jj]] (i < j): J = [[c s][-s c]].
 // tan(theta) only has to be accurate to single precision (a less exact angle leaves a residual of
 // relative size 1e-7, removed by the next sweep), so it comes from the hardware reciprocal and
-// square-root approximations; c is then refined to full precision so that c^2 + s^2 = 1 holds to
-// the rounding of T and the accumulated transformation stays orthogonal.
+// square-root approximations in float; c is then refined to full precision so that c^2 + s^2 = 1
+// holds to the rounding of T and the accumulated transformation stays orthogonal.
 // Of the two rotations that annihilate a_ij the one that leaves the larger diagonal entry at the
 // smaller index is taken (it differs from the small-angle one by a quarter turn): keeping the
 // diagonal sorted while it converges saves sweeps.
 __device__ inline void rotation(double aii, double ajj, double aij, double* c, double* s) {
-  double t = 0.0;
+  // tan(theta) and the first guess of cos(theta) in float (the difference a_jj - a_ii is formed in
+  // double first); out-of-range ratios end as inf or NaN and mean "no rotation"
+  float tf = 0.f;
   if (aij != 0.0) {
-    const double z = (ajj - aii) * __builtin_amdgcn_rcp(2.0 * aij);
-    const double az = fabs(z);
-    if (az < 1e150) {  // false for inf and NaN: no rotation
-      t = __builtin_amdgcn_rcp(az + __builtin_amdgcn_sqrt(1.0 + az * az));
-      t = z < 0.0 ? -t : t;
+    const float zf = (float)(ajj - aii) * __builtin_amdgcn_rcpf((float)(2.0 * aij));
+    const float az = fabsf(zf);
+    if (az < 1e18f) {  // false for inf and NaN
+      tf = __builtin_amdgcn_rcpf(az + __builtin_amdgcn_sqrtf(fmaf(az, az, 1.f)));
+      tf = zf < 0.f ? -tf : tf;
     }
   }
+  const double t = (double)tf;
   const double x = 1.0 + t * t;  // in [1, 2]
-  double y = __builtin_amdgcn_rsq(x);
+  double y = (double)__builtin_amdgcn_rsqf(fmaf(tf, tf, 1.f));
   y = y * (1.5 - 0.5 * x * y * y);
   y = y * (1.5 - 0.5 * x * y * y);
   const double cc = y, ss = y * t;
@@ -129,27 +132,32 @@ __device__ inline void rotation(float aii, float ajj, float aij, float* c, float
 // (CROSS = true, 32 steps) only pairs with one index in each of the two blocks are rotated:
 // top = i, bottom = 32 + (i + st) mod 32.  A rotation is stored in seat orientation: top' = c top - s bottom,
 // bottom' = s top + c bottom.
-//   * S is symmetric and lives in LDS as the 528 2x2 blocks (rows of seat I) x (columns of seat J),
-//     I <= J, one block per lane, the seat pair of a lane fixed for the whole kernel.  Storage is by
-//     seat, not by index: plane 0 holds the (top,top),(top,bottom) pair of every block, plane 1 the
-//     (bottom,top),(bottom,bottom) pair, so a lane reads its block with two 16-byte loads that are
-//     contiguous across lanes.  Since the indices move between seats by the same permutation every
-//     step, each rotated element has a fixed destination slot (computed once per lane); it is
-//     written there in a second buffer, and the two buffers swap roles every step.  Of a diagonal
-//     block (I,I) only tt, tb and bb are kept.
+//   * S is symmetric and lives in LDS as 2x2 blocks (rows of seat I) x (columns of seat J), I <= J.
+//     Storage is by seat, not by index: plane 0 holds the (top,top),(top,bottom) pair of every
+//     block, plane 1 the (bottom,top),(bottom,bottom) pair, so a lane reads a block with two
+//     16-byte loads that are contiguous across lanes.  Since the indices move between seats by the
+//     same permutation every step, each rotated element has a fixed destination slot (computed once
+//     per lane); it is written there in a second buffer, and the two buffers swap roles every step.
+//     Of a diagonal block (I,I) only tt, tb and bb are kept.
+//   * The 496 off-diagonal blocks have one lane each on eight wavefronts, the seat pair of a lane
+//     fixed for the whole kernel.
 //   * R never touches LDS for arithmetic: lane r holds row r of R in registers with the columns in
 //     seat order -- wavefront w owns seats 4w..4w+3 -- so every step rotates fixed register pairs;
 //     afterwards the columns move one seat along the tournament cycle, a register renaming inside a
 //     wavefront plus one column handed to each neighbouring wavefront through a small LDS buffer.
 //     After 63 steps the seats are back in their starting order.
-//   * A ninth wavefront computes the 32 rotations of step st+1 while the other eight apply the
-//     rotations of step st to R (which needs no S), so a step is: S update (barrier) then
-//     {next rotations | R update} (barrier).  The ninth wavefront also holds the 16 blocks of S that
-//     do not fit one-per-lane on eight wavefronts.  Measured alternatives that were slower on
-//     MI355X: rotations and R update in sequence on eight wavefronts, every lane computing its own
-//     rotation, wavefronts specialised for S and for R, one block per lane on 12 wavefronts, and
-//     index/address lookup tables in LDS or global memory -- the step time is the barrier-to-barrier
-//     latency chain (LDS is about one third busy), which this arrangement keeps shortest.
+//   * One barrier per step.  While the eight wavefronts apply the rotations of step st to S and to
+//     R, a ninth computes the rotations of step st+1: lane i evaluates the three elements of seat
+//     i's next pivot straight from the old S and the current rotations (three 2x2 blocks, 18
+//     multiply-adds, same operation order as the block lanes) instead of waiting for the updated
+//     S.  These lanes also own the diagonal blocks: the two diagonal elements they evaluate are
+//     the new diagonal of their seat, and the element a rotation annihilates is stored as zero.
+//     The rotation table and the hand-over buffers alternate between two copies like S.
+//     Measured alternatives that were slower on MI355X: rotations computed after the S update (two
+//     barriers per step), every lane computing its own rotation, wavefronts specialised for S and
+//     for R, one block per lane on 12 wavefronts, and index/address lookup tables in LDS or global
+//     memory.  Alone on a compute unit a workgroup is bound by the latency chain of the rotation
+//     wavefront, three per compute unit by LDS bandwidth.
 // Value held by lane `l` (l uniform over the wavefront), delivered through a scalar register.
 __device__ inline float lane_value(float v, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
@@ -164,12 +172,13 @@ constexpr int SOLVE_WAVES = 8;                          // wavefronts that hold 
 constexpr int SOLVE_THREADS = 64 * (SOLVE_WAVES + 1);   // plus the rotation wavefront
 // Declared bound of the kernel.  With a bound of 9 wavefronts the compiler derives "at most 7
 // wavefronts per SIMD" from the wave slots and pads the register allocation to 65 (72 allocated),
-// after which only two workgroups fit a compute unit; a bound of 10 leaves the allocation at 64 and
-// three fit.
+// after which only two workgroups fit a compute unit; a bound of 10 leaves the allocation alone and
+// three fit as long as the kernel needs no more than 64 registers.
 constexpr int SOLVE_BOUND = 64 * (SOLVE_WAVES + 2);
 constexpr int SEATS = JB / SOLVE_WAVES;                 // seats per wavefront
-constexpr int N_BLOCKS = JB * (JB + 1) / 2;
-static_assert(N_BLOCKS - 64 * SOLVE_WAVES <= 32, "left-over blocks go to lanes 32..63 of the rotation wavefront");
+constexpr int N_BLOCKS = JB * (JB + 1) / 2;             // stored blocks, diagonal ones included
+constexpr int N_OFFDIAG = JB * (JB - 1) / 2;            // blocks with a lane of their own
+static_assert(N_OFFDIAG <= 64 * SOLVE_WAVES, "one off-diagonal block per lane");
 
 __device__ inline int next63(int x) { return x == 62 ? 0 : x + 1; }
 
@@ -179,7 +188,8 @@ struct alignas(2 * sizeof(T)) Pair2 {
 };
 
 // Seat position p in [0,64): p < 32 is the top of seat p, p >= 32 the bottom of seat p - 32.
-// Where the index sitting at position p moves in one step.
+// Where the index sitting at position p moves in one step, and where the index that arrives at p
+// comes from.
 template <bool CROSS>
 __device__ inline int next_position(int p) {
   if (CROSS) return p < JB ? p : JB + ((p - JB) + JB - 1) % JB;  // tops stay, bottoms move one seat down
@@ -188,6 +198,15 @@ __device__ inline int next_position(int p) {
   if (p < JB) return p - 1;                                      // tops move towards seat 1
   if (p == JT - 1) return JB - 1;                                // bottom of seat 31 -> top of seat 31
   return p + 1;                                                  // bottoms move away from seat 0
+}
+template <bool CROSS>
+__device__ inline int prev_position(int p) {
+  if (CROSS) return p < JB ? p : JB + ((p - JB) + 1) % JB;
+  if (p == 0) return 0;
+  if (p == JB) return 1;
+  if (p < JB - 1) return p + 1;
+  if (p == JB - 1) return JT - 1;
+  return p - 1;
 }
 
 __device__ inline int block_id(int I, int J) { return I * JB - I * (I - 1) / 2 + (J - I); }  // I <= J
@@ -206,12 +225,13 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
                                                             const EigState* __restrict__ state, int Np, int nblk,
                                                             int step, int img0, int inner_steps) {
   const int b = img0 + blockIdx.y, pair = blockIdx.x, P = nblk / 2;
-  if (state[b].done) return;
+  const int done = state[b].done;  // tested after the loads below have been issued
   constexpr int BUF = 4 * N_BLOCKS;  // elements of one buffer: two planes of N_BLOCKS pairs
   constexpr int STAGE = JT * SLD;    // the finished R is staged here for row-contiguous stores
+  constexpr int XCOPIES = CROSS ? 1 : 2;
   __shared__ __attribute__((aligned(16))) T SB[(2 * BUF > STAGE ? 2 * BUF : STAGE)];
-  __shared__ T xtop[SOLVE_WAVES][JT], xbot[SOLVE_WAVES][JT];
-  __shared__ Pair2<T> rcs[JB];  // (c, z) of every seat
+  __shared__ T xch[2][XCOPIES][SOLVE_WAVES][JT];  // columns of R handed to the neighbouring wavefront: [parity][top/bottom]
+  __shared__ Pair2<T> rcs[2][JB];                  // (c, z) of every seat, [parity]
   __shared__ double red[SOLVE_WAVES + 1];
   int p, q;
   round_robin_pair(nblk, step, pair, &p, &q);
@@ -225,39 +245,59 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
   auto bot0 = [](int i) { return CROSS ? JB + i : (63 - i) % 63; };
   auto next_top = [](int x) { return CROSS || x == 63 ? x : next63(x); };
   auto next_bot = [](int x) { return CROSS ? (x == JT - 1 ? JB : x + 1) : next63(x); };
-  // the block of S this lane owns: task tid on wavefronts 0..7, task 512 + lane - 32 on the rotation wavefront
-  const int task = rwave ? 64 * SOLVE_WAVES + lane - 32 : tid;
-  const bool act = !rwave || (lane >= 32 && task < N_BLOCKS);
-  int sI = 0, sJ = act ? task : 0;  // row I of the upper triangle holds JB - I blocks
-  while (sJ >= JB - sI) { sJ -= JB - sI; sI++; }
-  sJ += sI;
-  const bool diag = sI == sJ;
+  // Element {r,c} of the subproblem, r and c in 0..63 (first the rows and columns of block p, then
+  // of block q).  Block (q,p) is not stored: read its mirror.
+  auto gload = [&](int r, int c) {
+    if (r >= JB && c < JB) { const int t = r; r = c; c = t; }
+    const int gr = (r < JB ? p * JB + r : q * JB + r - JB), gc = (c < JB ? p * JB + c : q * JB + c - JB);
+    return Gb[(size_t)gr * Np + gc];
+  };
+  auto weight = [&](int r, int c) {  // share of v^2 in the off-diagonal mass of this visit
+    return ((r < JB) == (c < JB)) ? 2.0 / (double)(nblk - 1) : 2.0;  // inside G_pp, G_qq: seen nblk-1 times per sweep
+  };
+  // the off-diagonal block of S this lane owns (wavefronts 0..7): row I of the strict upper triangle holds JB-1-I blocks
+  const bool act = !rwave && tid < N_OFFDIAG;
+  int sI = 0, sJ = act ? tid : 0;
+  while (sJ >= JB - 1 - sI) { sJ -= JB - 1 - sI; sI++; }
+  sJ += sI + 1;
+  // the seat of a rotation lane
+  const int seat = lane & (JB - 1);
+  int rt = top0(seat), rb = bot0(seat);  // indices in the seat
+  if (rwave) sI = sJ = seat;
   const int rd = 2 * block_id(sI, sJ);  // this lane's (tt,tb) pair; (bt,bb) sits 2*N_BLOCKS further
-  // destinations of the four rotated elements in the other buffer
+  // destinations of the rotated elements in the other buffer (a rotation lane only uses wtb: where
+  // the element it annihilates goes)
   const int pTI = next_position<CROSS>(sI), pBI = next_position<CROSS>(JB + sI);
   const int pTJ = next_position<CROSS>(sJ), pBJ = next_position<CROSS>(JB + sJ);
-  const int wtt = slot_of(pTI, pTJ), wtb = slot_of(pTI, pBJ), wbb = slot_of(pBI, pBJ);
-  const int wbt = diag ? 2 * N_BLOCKS + rd : slot_of(pBI, pTJ);  // (a diagonal block's bt is a copy of tb: parked in an unused slot)
+  const int wtt = slot_of(pTI, pTJ), wtb = slot_of(pTI, pBJ), wbt = slot_of(pBI, pTJ), wbb = slot_of(pBI, pBJ);
+  // rotation lanes: the next pivot of the seat consists of a_xx, a_xy, a_yy, where x and y are the
+  // positions whose indices arrive in this seat (always in two different seats Sx, Sy).  a_xx and
+  // a_yy come from the diagonal blocks of Sx and Sy, a_xy from the block of the two seats.
+  const int px = prev_position<CROSS>(seat), py = prev_position<CROSS>(JB + seat);
+  const int Sx = px & (JB - 1), Sy = py & (JB - 1);
+  const bool kx = px >= JB, ky = py >= JB;  // bottom of its seat?
+  const bool swp = Sx > Sy;                 // the stored block is (Sy,Sx): a_xy is read as a_yx
+  const int rdx = 2 * block_id(Sx, Sx), rdy = 2 * block_id(Sy, Sy);
+  const int rdxy = 2 * (swp ? block_id(Sy, Sx) : block_id(Sx, Sy));
+
   double off = 0.0;
+  T d_tt = T(0), d_tb = T(0), d_bb = T(0);
   if (act) {
-    // Load the block from G: element {r,c} of the subproblem, r and c in 0..63 (first the rows and
-    // columns of block p, then of block q).  Block (q,p) is not stored: read its mirror.
-    auto gload = [&](int r, int c) {
-      if (r >= JB && c < JB) { const int t = r; r = c; c = t; }
-      const int gr = (r < JB ? p * JB + r : q * JB + r - JB), gc = (c < JB ? p * JB + c : q * JB + c - JB);
-      return Gb[(size_t)gr * Np + gc];
-    };
-    auto weight = [&](int r, int c) {  // share of v^2 in the off-diagonal mass of this visit
-      if (r == c) return 0.0;
-      return ((r < JB) == (c < JB)) ? 2.0 / (double)(nblk - 1) : 2.0;  // inside G_pp, G_qq: seen nblk-1 times per sweep
-    };
     const int iTI = top0(sI), iBI = bot0(sI), iTJ = top0(sJ), iBJ = bot0(sJ);
     const T ett = gload(iTI, iTJ), etb = gload(iTI, iBJ), ebt = gload(iBI, iTJ), ebb = gload(iBI, iBJ);
+    if (done) return;  // uniform over the workgroup
     *reinterpret_cast<Pair2<T>*>(&SB[rd]) = Pair2<T>{ett, etb};
     *reinterpret_cast<Pair2<T>*>(&SB[2 * N_BLOCKS + rd]) = Pair2<T>{ebt, ebb};
     off = weight(iTI, iTJ) * (double)ett * (double)ett + weight(iTI, iBJ) * (double)etb * (double)etb +
-          weight(iBI, iBJ) * (double)ebb * (double)ebb;
-    if (!diag) off += weight(iBI, iTJ) * (double)ebt * (double)ebt;
+          weight(iBI, iTJ) * (double)ebt * (double)ebt + weight(iBI, iBJ) * (double)ebb * (double)ebb;
+  } else if (rwave && lane < JB) {  // the diagonal block of the seat
+    d_tt = gload(rt, rt); d_tb = gload(rt, rb); d_bb = gload(rb, rb);
+    if (done) return;
+    *reinterpret_cast<Pair2<T>*>(&SB[rd]) = Pair2<T>{d_tt, d_tb};
+    SB[2 * N_BLOCKS + rd + 1] = d_bb;
+    off = weight(rt, rb) * (double)d_tb * (double)d_tb;
+  } else if (done) {
+    return;
   }
   off = wave_sum(off);
   if (lane == 0) red[wave] = off;
@@ -268,63 +308,73 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
     rtop[k] = (lane == top0(i)) ? T(1) : T(0);
     rbot[k] = (lane == bot0(i)) ? T(1) : T(0);
   }
-  int rt = top0(lane & 31), rb = bot0(lane & 31);  // indices in seat lane%32, for the rotations
-  const int rdd = 2 * block_id(lane & 31, lane & 31);
-  __syncthreads();
-  if (tid == 0) {
-    double tot = 0.0;
-    for (int w = 0; w <= SOLVE_WAVES; w++) tot += red[w];
-    offpart[((size_t)b * (nblk - 1) + step) * P + pair] = tot;
-  }
-  auto make_rotations = [&](int buf) {  // lanes 0..31 of the rotation wavefront; S is read from buffer buf
-    const Pair2<T> d = *reinterpret_cast<const Pair2<T>*>(&SB[buf * BUF + rdd]);
-    const T abb = SB[buf * BUF + 2 * N_BLOCKS + rdd + 1];
+  auto store_rotation = [&](int par, T att, T atb, T abb) {
     // rotation() wants the pair ordered by index; a rotation is stored in seat orientation
     // (top' = c top - z bottom, bottom' = z top + c bottom)
     const bool flip = rt > rb;
     T c, s;
-    rotation(flip ? abb : d.x, flip ? d.x : abb, d.y, &c, &s);
-    rcs[lane] = Pair2<T>{c, flip ? -s : s};
+    rotation(flip ? abb : att, flip ? att : abb, atb, &c, &s);
+    rcs[par][seat] = Pair2<T>{c, flip ? -s : s};
     rt = next_top(rt);
     rb = next_bot(rb);
   };
-  if (rwave && lane < JB && inner_steps > 0) make_rotations(0);
+  if (rwave && lane < JB && inner_steps > 0) store_rotation(0, d_tt, d_tb, d_bb);  // rotations of step 0
   __syncthreads();
+  if (tid == 0) {
+    double tot = 0.0;
+    for (int w = 0; w < SOLVE_WAVES + 1; w++) tot += red[w];
+    offpart[((size_t)b * (nblk - 1) + step) * P + pair] = tot;
+  }
 
   for (int st = 0; st < inner_steps; st++) {  // a whole sweep brings the seats back to their starting order
-    const int cur = (st & 1) * BUF, nxt = BUF - cur;
-    // ---- S <- J^T S J (not needed after the last step: only R leaves the kernel) ------------------
-    if (act && st + 1 < inner_steps) {
-      const Pair2<T> rI = rcs[sI], rJ = rcs[sJ];
-      const Pair2<T> et = *reinterpret_cast<const Pair2<T>*>(&SB[cur + rd]);
-      const Pair2<T> eb = *reinterpret_cast<const Pair2<T>*>(&SB[cur + 2 * N_BLOCKS + rd]);
-      const T cI = rI.x, zI = rI.y, cJ = rJ.x, zJ = rJ.y;
-      const T ett = et.x, etb = et.y, ebt = diag ? et.y : eb.x, ebb = eb.y;
-      const T ftt = cI * ett - zI * ebt, fbt = zI * ett + cI * ebt;  // rows of seat I
-      const T ftb = cI * etb - zI * ebb, fbb = zI * etb + cI * ebb;
-      SB[nxt + wtt] = cJ * ftt - zJ * ftb;                            // columns of seat J
-      SB[nxt + wtb] = zJ * ftt + cJ * ftb;
-      SB[nxt + wbt] = cJ * fbt - zJ * fbb;
-      SB[nxt + wbb] = zJ * fbt + cJ * fbb;
-    }
-    Pair2<T> mine = {T(0), T(0)};
-    if (!rwave) {
-      // one LDS read per lane, scalar broadcasts later: lane k (k < SEATS) holds the rotation of seat k
-      mine = rcs[SEATS * wave + (lane & (SEATS - 1))];
+    const int par = st & 1, cur = par * BUF, nxt = BUF - cur;
+    const bool more = st + 1 < inner_steps;  // after the last step only R leaves the kernel
+    if (rwave) {
+      if (lane < JB && more) {
+        // ---- the next pivot, evaluated from the current S and the current rotations ---------------
+        // element (kr, kc) of J_I^T B J_J for the block at pair slot r, in the order the block lanes use
+        auto element = [&](int r, bool isdiag, Pair2<T> rI, Pair2<T> rJ, bool kr, bool kc) {
+          const Pair2<T> et = *reinterpret_cast<const Pair2<T>*>(&SB[cur + r]);
+          const Pair2<T> eb = *reinterpret_cast<const Pair2<T>*>(&SB[cur + 2 * N_BLOCKS + r]);
+          const T ebt = isdiag ? et.y : eb.x;
+          const T uI0 = kr ? rI.y : rI.x, uI1 = kr ? rI.x : -rI.y;
+          const T uJ0 = kc ? rJ.y : rJ.x, uJ1 = kc ? rJ.x : -rJ.y;
+          const T f0 = uI0 * et.x + uI1 * ebt, f1 = uI0 * et.y + uI1 * eb.y;
+          return uJ0 * f0 + uJ1 * f1;
+        };
+        const Pair2<T> rX = rcs[par][Sx], rY = rcs[par][Sy];
+        const T axx = element(rdx, true, rX, rX, kx, kx), ayy = element(rdy, true, rY, rY, ky, ky);
+        const T axy = element(rdxy, false, swp ? rY : rX, swp ? rX : rY, swp ? ky : kx, swp ? kx : ky);
+        SB[nxt + rd] = axx;                      // the seat's new diagonal ((top,bottom) comes from a block lane)
+        SB[nxt + 2 * N_BLOCKS + rd + 1] = ayy;
+        SB[nxt + wtb] = T(0);                    // the element annihilated in this step, at its new place
+        store_rotation(par ^ 1, axx, axy, ayy);
+      }
+    } else {
+      // ---- S <- J^T S J ---------------------------------------------------------------------------
+      if (act && more) {
+        const Pair2<T> rI = rcs[par][sI], rJ = rcs[par][sJ];
+        const Pair2<T> et = *reinterpret_cast<const Pair2<T>*>(&SB[cur + rd]);
+        const Pair2<T> eb = *reinterpret_cast<const Pair2<T>*>(&SB[cur + 2 * N_BLOCKS + rd]);
+        const T cI = rI.x, zI = rI.y, cJ = rJ.x, zJ = rJ.y;
+        const T ftt = cI * et.x - zI * eb.x, fbt = zI * et.x + cI * eb.x;  // rows of seat I
+        const T ftb = cI * et.y - zI * eb.y, fbb = zI * et.y + cI * eb.y;
+        SB[nxt + wtt] = cJ * ftt - zJ * ftb;                                // columns of seat J
+        SB[nxt + wtb] = zJ * ftt + cJ * ftb;
+        SB[nxt + wbt] = cJ * fbt - zJ * fbb;
+        SB[nxt + wbb] = zJ * fbt + cJ * fbb;
+      }
+      // ---- R <- R J on this wavefront's seats -----------------------------------------------------
+      // one LDS read per lane, then scalar broadcasts: lane k (k < SEATS) holds the rotation of seat k
+      const Pair2<T> mine = rcs[par][SEATS * wave + (lane & (SEATS - 1))];
       if (st > 0) {  // columns handed over by the neighbours during the previous step
         if (CROSS) {
-          rbot[SEATS - 1] = xbot[(wave + 1) % SOLVE_WAVES][lane];
+          rbot[SEATS - 1] = xch[par ^ 1][0][(wave + 1) % SOLVE_WAVES][lane];
         } else {
-          if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
-          if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+          if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xch[par ^ 1][0][wave + 1][lane];
+          if (wave > 0) rbot[0] = xch[par ^ 1][XCOPIES - 1][wave - 1][lane];
         }
       }
-    }
-    __syncthreads();  // S is up to date; the rotation table and the hand-over buffers have been read
-    if (rwave) {
-      if (lane < JB && st + 1 < inner_steps) make_rotations(nxt / BUF);
-    } else {
-      // ---- R <- R J on this wavefront's seats -----------------------------------------------------
 #pragma unroll
       for (int k = 0; k < SEATS; k++) {
         const T c = lane_value(mine.x, k), z = lane_value(mine.y, k);
@@ -337,7 +387,7 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
         const T out_bot = rbot[0];
 #pragma unroll
         for (int k = 0; k < SEATS - 1; k++) rbot[k] = rbot[k + 1];
-        xbot[wave][lane] = out_bot;  // becomes the last bottom of the wavefront before
+        xch[par][0][wave][lane] = out_bot;  // becomes the last bottom of the wavefront before
       } else {  // tops move towards seat 1, bottoms away from seat 0
         const T out_top = rtop[0], out_bot = rbot[SEATS - 1], top1 = rtop[1];
         if (wave == 0) {
@@ -351,19 +401,20 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
 #pragma unroll
         for (int k = SEATS - 1; k > 0; k--) rbot[k] = rbot[k - 1];
         if (wave == 0) rbot[0] = top1;                                    // bottom_0 <- top_1
-        if (wave > 0) xtop[wave][lane] = out_top;                         // becomes the last top of wave-1
-        if (wave < SOLVE_WAVES - 1) xbot[wave][lane] = out_bot;           // becomes the first bottom of wave+1
+        if (wave > 0) xch[par][0][wave][lane] = out_top;                  // becomes the last top of wave-1
+        if (wave < SOLVE_WAVES - 1) xch[par][XCOPIES - 1][wave][lane] = out_bot;  // becomes the first bottom of wave+1
       }
     }
-    __syncthreads();  // next rotations and the handed-over columns are visible
+    __syncthreads();  // the other S buffer, the next rotations and the handed-over columns are complete
   }
   if (!rwave) {
     if (inner_steps > 0) {
+      const int par = (inner_steps - 1) & 1;
       if (CROSS) {
-        rbot[SEATS - 1] = xbot[(wave + 1) % SOLVE_WAVES][lane];
+        rbot[SEATS - 1] = xch[par][0][(wave + 1) % SOLVE_WAVES][lane];
       } else {
-        if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xtop[wave + 1][lane];
-        if (wave > 0) rbot[0] = xbot[wave - 1][lane];
+        if (wave < SOLVE_WAVES - 1) rtop[SEATS - 1] = xch[par][0][wave + 1][lane];
+        if (wave > 0) rbot[0] = xch[par][XCOPIES - 1][wave - 1][lane];
       }
     }
     // after a whole sweep (63 or 32 steps) the seats are back in their step-0 order; stage R through
