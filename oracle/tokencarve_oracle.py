@@ -32,6 +32,23 @@ Readings taken where the paper is silent (each mirrored by the HIP path):
     averaging acts on the rows handed in as X; output rows in ascending
     original position.
 
+Beyond the compression path (Section 3.2 and the Conclusion):
+  * Information quantity = matrix rank of the attention output of the visual
+    tokens (Section 3.2.2): the number of singular values above rtol * sigma_max.
+    The paper names no tolerance: the default is max(rows, cols) * 2^-23, the
+    usual numerical-rank threshold for float32 data; callers may pass their own.
+    The curve "rank versus kept tokens" is normalised with Eq. 3-3 (minmax()).
+    The paper evaluates it on the last layer's Z after running the compressed
+    sequence through the model; with no model here it is evaluated on the rows
+    of the given Z that survive (kept_idx), which is the same quantity at the
+    layer where compression happens.
+  * Sequence after compression: [system | kept visual | prompt], every token
+    keeps its original position id (Conclusion: rotary encodings are recomputed
+    from the original position ids).  Rotary tables follow the standard
+    definition theta_i = base^(-2i/d_h), angle = position * theta_i.
+  * KV cache share (CUDA Time Test table): layers in front of the compression
+    point keep the full sequence, the others the shortened one.
+
 PARITY UNPINNED: when two singular values coincide, U is not unique inside
 that subspace and Eq. 3-6 depends on the basis chosen; there only the
 invariants (sum_i (u_xi sigma_i)^2 = ||Z_x||^2, bounds on C) are pinned.
@@ -241,3 +258,66 @@ def gram_precision_floor(O, gram_dtype=np.float32):
     lam, U = np.linalg.eigh(G)
     C = (np.abs(U) * np.sqrt(np.maximum(lam, 0.0))).sum(axis=1)
     return float(np.max(np.abs(C - C_ref) / C_ref))
+
+
+# ----------------------------------------------------------------------------
+# Information quantity (Section 3.2.2, "Attention Output Matrix Rank")
+# ----------------------------------------------------------------------------
+def info_rank(O, rows=None, rtol=None):
+    """Numerical rank of the rows `rows` (all if None) of O [N, D]; returns (rank, sigma descending)."""
+    A = np.asarray(O, dtype=np.float64)
+    if rows is not None:
+        A = A[np.asarray(rows, dtype=np.int64)]
+    if A.shape[0] == 0:
+        return 0, np.zeros(0)
+    sigma = np.linalg.svd(A, compute_uv=False)
+    if rtol is None:
+        rtol = max(A.shape) * 2.0 ** -23
+    if sigma[0] <= 0.0:
+        return 0, sigma
+    return int(np.count_nonzero(sigma > rtol * sigma[0])), sigma
+
+
+def visual_token_information(ranks):
+    """The rank curve of Section 3.2.2, normalised with Eq. 3-3."""
+    return minmax(np.asarray(ranks, dtype=np.float64))
+
+
+# ----------------------------------------------------------------------------
+# Sequence after compression (Fig. 2; Conclusion on position ids)
+# ----------------------------------------------------------------------------
+def assemble_sequence(H, X_out, kept_idx, n_sys, n_vis):
+    """H [L, D] hidden states of the full sequence, X_out [k_f, D] compressed visual rows.
+
+    Returns (H_new [L - n_vis + k_f, D], pos_ids): system rows, compressed visual rows, prompt
+    rows, each with the position it had in the full sequence.
+    """
+    H = np.asarray(H, dtype=np.float64)
+    kept_idx = np.asarray(kept_idx, dtype=np.int64)
+    L = H.shape[0]
+    H_new = np.concatenate([H[:n_sys], np.asarray(X_out, dtype=np.float64), H[n_sys + n_vis:]], axis=0)
+    pos = np.concatenate([np.arange(n_sys), n_sys + kept_idx, np.arange(n_sys + n_vis, L)])
+    return H_new, pos.astype(np.int64)
+
+
+def rope_tables(pos_ids, head_dim, base=10000.0):
+    """cos and sin [len(pos_ids), head_dim/2] of the rotary embedding R(theta) of Eq. 3-1."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    theta = base ** (-2.0 * i / head_dim)
+    ang = np.asarray(pos_ids, dtype=np.float64)[:, None] * theta[None, :]
+    return np.cos(ang), np.sin(ang)
+
+
+def apply_rope(x, cos, sin):
+    """Rotate x [n, head_dim] pairwise (x_i, x_{i+d/2}), the LLaMA layout."""
+    x = np.asarray(x, dtype=np.float64)
+    h = x.shape[1] // 2
+    a, b = x[:, :h], x[:, h:]
+    return np.concatenate([a * cos - b * sin, a * sin + b * cos], axis=1)
+
+
+def kv_cache_fraction(n_text, n_vis, n_kept, n_layers, n_layers_before):
+    """KV-cache size relative to the uncompressed run (CUDA Time Test table)."""
+    full = n_text + n_vis
+    short = n_text + n_kept
+    return (n_layers_before * full + (n_layers - n_layers_before) * short) / (n_layers * full)

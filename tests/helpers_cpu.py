@@ -71,3 +71,23 @@ def best_subset_by_sum(E, k):
         if tot > best:
             best, best_set = tot, comb
     return set(best_set)
+
+
+def rank_by_elimination(A, tol=1e-9):
+    """Rank of a small matrix by Gaussian elimination with full pivoting (independent of any SVD)."""
+    M = np.array(A, dtype=np.float64)
+    scale = np.abs(M).max() if M.size else 0.0
+    if scale == 0.0:
+        return 0
+    rank = 0
+    rows, cols = M.shape
+    for _ in range(min(rows, cols)):
+        sub = np.abs(M[rank:, rank:])
+        i, j = np.unravel_index(np.argmax(sub), sub.shape)
+        if sub[i, j] <= tol * scale:
+            break
+        M[[rank, rank + i]] = M[[rank + i, rank]]
+        M[:, [rank, rank + j]] = M[:, [rank + j, rank]]
+        M[rank + 1:, rank:] -= np.outer(M[rank + 1:, rank] / M[rank, rank], M[rank, rank:])
+        rank += 1
+    return rank
