@@ -175,6 +175,60 @@ TC_API int tc_profile_compress(const tc_params* p, const void* Q, const void* K,
                                float* jacobi_update_ms_by_sweep, int32_t max_sweeps_out);
 
 /*
+ * Information quantity of a set of visual tokens (Section 3.2.2, "matrix rank as a proxy metric"; the
+ * appendix "Attention Output Matrix Rank"): for every image the numerical rank of the attention
+ * output rows O[b, rows[b, :], :],
+ *     rank[b] = #{ i : sigma_i > rtol * sigma_max },
+ * sigma = singular values of the n_rows x D matrix (D = n_heads * head_dim), obtained as the square
+ * roots of the eigenvalues of its Gram matrix with the eigensolver of tc_ipgs_score (p->eig_dtype,
+ * jacobi_* as there; TC_EIG_F64 recommended).
+ *   O      [B, n_vis, D]  device, p->dtype, as written by tc_attn_output
+ *   rows   [B, n_rows]    device int32, distinct visual indices in [0, n_vis) (e.g. kept_idx of
+ *                         tc_merge); NULL = all n_vis rows (n_rows is then ignored).  An index out of
+ *                         range is clamped, not reported.
+ *   rtol   threshold relative to sigma_max; 0 = max(n_rows, D) * 2^-23 (numerical rank of float32
+ *          data).  Values in (0, 1e-7) are rejected with TC_ERR_PARAM: the Gram route cannot resolve
+ *          singular values that far below the largest one.
+ *   rank   [B] device int32, written
+ *   sigma  [B, n_rows] device float, optional: the singular values, descending
+ *   info   [B] device int32, optional: sweeps used, negative if not converged
+ *   ws     workspace of tc_workspace_bytes(p) bytes (its contents are destroyed)
+ * n_rows = 0 gives rank 0.  Errors as for tc_ipgs_score; 0 <= n_rows <= n_vis else TC_ERR_SHAPE.
+ */
+TC_API int tc_info_rank(const tc_params* p, const void* O, const int32_t* rows, int32_t n_rows, float rtol,
+                        int32_t* rank, float* sigma, int32_t* info, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The sequence handed to the next layer after compression (Fig. 2, lower panel; Conclusion: kept
+ * tokens keep their original position ids and the rotary encodings are recomputed from them):
+ *     H_new[b] = [ H[b, 0 : vis_start] | X_out[b] | H[b, vis_start + n_vis : seq_len] ]
+ *     pos_ids[b] = [ 0 .. vis_start-1 | vis_start + kept_idx[b, :] | vis_start + n_vis .. seq_len-1 ]
+ * with L' = seq_len - n_vis + k_final rows, and optionally the rotary tables of Eq. 3-1's R(theta),
+ *     rope_cos[b, j, i] = cos(pos_ids[b, j] * rope_base^(-2 i / head_dim)),  i < head_dim / 2
+ * (rope_sin alike), evaluated in float64 and rounded once.
+ *   H        [B, seq_len, hidden_dim]  device, p->dtype: hidden states of the full sequence
+ *   X_out    [B, k_final, hidden_dim]  device, p->dtype: compressed visual rows (tc_merge / tc_compress)
+ *   kept_idx [B, k_final]              device int32, ascending (tc_merge / tc_compress)
+ *   H_new    [B, L', hidden_dim]       device, written; must not overlap H or X_out
+ *   pos_ids  [B, L']                   device int32, written
+ *   rope_cos, rope_sin [B, L', head_dim/2] device float, both given or both NULL; rope_base > 1
+ *                                      (10000 for LLaMA) is only read when they are given
+ * Needs no workspace.  Text rows are copied bit for bit.
+ */
+TC_API int tc_assemble_sequence(const tc_params* p, const void* H, const void* X_out, const int32_t* kept_idx,
+                                void* H_new, int32_t* pos_ids, float rope_base, float* rope_cos, float* rope_sin,
+                                void* stream);
+
+/*
+ * Host arithmetic, no GPU work: size of the KV cache relative to the uncompressed run when the
+ * n_layers_before layers in front of the compression point hold the full sequence (n_text + n_vis
+ * tokens) and the remaining layers n_text + n_kept tokens (the "KV Cache (%)" row of the paper's
+ * latency table).  Returns -1 for arguments out of range.
+ */
+TC_API double tc_kv_cache_fraction(int32_t n_text, int32_t n_vis, int32_t n_kept, int32_t n_layers,
+                                   int32_t n_layers_before);
+
+/*
  * Measurement aid: sustained rates of this GPU, for reading roofline fractions against what the part
  * actually delivers.  Runs register-only loops of independent matrix-core products (fp64 16x16x4,
  * fp32 16x16x4, bf16 32x32x16) and a streaming copy of 128 MiB inside `ws` (ws_bytes >= 256 MiB,

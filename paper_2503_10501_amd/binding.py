@@ -18,7 +18,8 @@ TC_NORM_NONE, TC_NORM_MINMAX = 0, 1
 TC_EIG_F64, TC_EIG_F32 = 0, 1
 
 SYMBOLS = ("tc_workspace_bytes", "tc_status_string", "tc_attn_output", "tc_ipgs_score", "tc_select_topk",
-           "tc_merge", "tc_compress", "tc_profile_compress", "tc_probe_rates")
+           "tc_merge", "tc_compress", "tc_profile_compress", "tc_probe_rates", "tc_info_rank",
+           "tc_assemble_sequence", "tc_kv_cache_fraction")
 PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_update_u", "jacobi_sweep_end",
               "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average")
 
@@ -83,8 +84,12 @@ def load_library():
     lib.tc_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_profile_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, ctypes.c_int32]
     lib.tc_probe_rates.argtypes = [vp, sz, vp, vp]
+    lib.tc_info_rank.argtypes = [pp, vp, vp, ctypes.c_int32, ctypes.c_float, vp, vp, vp, vp, sz, vp]
+    lib.tc_assemble_sequence.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp]
+    lib.tc_kv_cache_fraction.argtypes = [ctypes.c_int32] * 5
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ctypes.c_int
+    lib.tc_kv_cache_fraction.restype = ctypes.c_double
     _lib = lib
     return lib
 
@@ -183,3 +188,24 @@ def tc_probe_rates(stream=None):
     _check(load_library().tc_probe_rates(_ptr(ws), ws.numel(), _stream(stream), rates))
     return {"mfma_f64_tflops": float(rates[0]), "mfma_f32_tflops": float(rates[1]),
             "mfma_bf16_tflops": float(rates[2]), "copy_gbps": float(rates[3])}
+
+
+def tc_info_rank(p, O, rank, ws, rows=None, rtol=0.0, sigma=None, info=None, stream=None):
+    n_rows = int(rows.shape[1]) if rows is not None else int(p.n_vis)
+    if rows is not None and rows.numel() == 0:   # an empty tensor has no address; NULL would mean "all rows"
+        rows = torch.zeros(4, dtype=torch.int32, device="cuda")
+    _check(load_library().tc_info_rank(ctypes.byref(p), _ptr(O), _ptr(rows, torch.int32), n_rows, float(rtol),
+                                       _ptr(rank, torch.int32), _ptr(sigma, torch.float32), _ptr(info, torch.int32),
+                                       _ptr(ws), ws.numel(), _stream(stream)))
+
+
+def tc_assemble_sequence(p, H, X_out, kept_idx, H_new, pos_ids, rope_base=10000.0, rope_cos=None, rope_sin=None,
+                         stream=None):
+    _check(load_library().tc_assemble_sequence(ctypes.byref(p), _ptr(H), _ptr(X_out), _ptr(kept_idx, torch.int32),
+                                               _ptr(H_new), _ptr(pos_ids, torch.int32), float(rope_base),
+                                               _ptr(rope_cos, torch.float32), _ptr(rope_sin, torch.float32),
+                                               _stream(stream)))
+
+
+def tc_kv_cache_fraction(n_text, n_vis, n_kept, n_layers, n_layers_before):
+    return float(load_library().tc_kv_cache_fraction(n_text, n_vis, n_kept, n_layers, n_layers_before))

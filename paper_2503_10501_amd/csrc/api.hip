@@ -60,16 +60,6 @@ int make_plan(const tc_params* p, Plan* pl) {
   return TC_OK;
 }
 
-template <typename T>
-static T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
-
-static int check_ws(const Plan& pl, const void* ws, size_t ws_bytes) {
-  if (!ws) return TC_ERR_NULL;
-  if (misaligned(ws)) return TC_ERR_ALIGN;
-  if (ws_bytes < pl.total) return TC_ERR_WORKSPACE;
-  return TC_OK;
-}
-
 static int ipgs_chain(const Plan& pl, const tc_params* p, const void* O, const float* S, float* score, float* ics,
                       float* sigma, int32_t* info, void* ws, hipStream_t st) {
   void* G = at<char>(ws, pl.off_G);

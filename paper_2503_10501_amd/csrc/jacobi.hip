@@ -711,7 +711,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
       else
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JB)));
       TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg)));
-      TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg)));
+      if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg)));
     }
     TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<nimg, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, img0, nimg)));
   }
@@ -720,7 +720,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
 template <typename T>
 static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, EigState* state, hipStream_t st) {
   const int Np = pl.Np;
-  TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));
+  if (U) TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));  // U == nullptr: eigenvalues only
   TC_TIMED(PK_JINIT, 1, st, (jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np)));
   int groups = pl.groups > 0 ? pl.groups : (pl.B >= 16 ? 4 : (pl.B >= 4 ? 2 : 1));
   if (groups > pl.B) groups = pl.B;

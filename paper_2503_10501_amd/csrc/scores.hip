@@ -119,6 +119,19 @@ static int run_scores(const Plan& pl, const T* G, const float* U, const EigState
   return check_launch();
 }
 
+// Singular values only (no eigenvectors): sqrt of the eigenvalues into sig_ws, optional sorted copy and sweep count.
+int launch_sigma(const Plan& pl, int eig_dtype, const void* G, const EigState* state, double* sig_ws, float* sigma_out,
+                 int32_t* info_out, hipStream_t st) {
+  int n2 = 1;
+  while (n2 < pl.Np) n2 <<= 1;
+  const size_t shm = sigma_out ? n2 * sizeof(float) : 0;
+  if (eig_dtype == TC_EIG_F64)
+    sigma_kernel<double><<<pl.B, 256, shm, st>>>((const double*)G, state, sig_ws, sigma_out, info_out, pl.N, pl.Np);
+  else
+    sigma_kernel<float><<<pl.B, 256, shm, st>>>((const float*)G, state, sig_ws, sigma_out, info_out, pl.N, pl.Np);
+  return check_launch();
+}
+
 int launch_scores(const Plan& pl, int eig_dtype, const void* G, const void* U, const EigState* state, const float* S,
                   float lambda, int norm_mode, float sv_rtol, void* sig_ws, float* C_ws, float* E, float* C_out,
                   float* sigma_out, int32_t* info_out, hipStream_t st) {

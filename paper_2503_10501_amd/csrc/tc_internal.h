@@ -48,15 +48,27 @@ int make_plan(const tc_params* p, Plan* plan);  // validates p; returns tc_statu
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+template <typename T>
+inline T* at(void* ws, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(ws) + off); }
+
+inline int check_ws(const Plan& pl, const void* ws, size_t ws_bytes) {
+  if (!ws) return TC_ERR_NULL;
+  if (misaligned(ws)) return TC_ERR_ALIGN;
+  if (ws_bytes < pl.total) return TC_ERR_WORKSPACE;
+  return TC_OK;
+}
+
 // ---- stage launchers (each returns a tc_status; all work is enqueued on `st`) ----------
 int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const void* K, const void* V, void* O,
                      float* S, float* Spart, hipStream_t st);
 int launch_gram(const Plan& pl, int dtype, int eig_dtype, const void* O, void* G, hipStream_t st);
-int launch_jacobi(const Plan& pl, int eig_dtype, void* G, void* U, void* R, double* offpart, EigState* state,
-                  hipStream_t st);
+int launch_jacobi(const Plan& pl, int eig_dtype, void* G, void* U /* nullptr: eigenvalues only */, void* R,
+                  double* offpart, EigState* state, hipStream_t st);
 int launch_scores(const Plan& pl, int eig_dtype, const void* G, const void* U, const EigState* state,
                   const float* S, float lambda, int norm_mode, float sv_rtol, void* sig_ws, float* C_ws, float* E,
                   float* C_out, float* sigma_out, int32_t* info_out, hipStream_t st);
+int launch_sigma(const Plan& pl, int eig_dtype, const void* G, const EigState* state, double* sig_ws, float* sigma_out,
+                 int32_t* info_out, hipStream_t st);
 int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st);
 int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, const int32_t* order, void* X_out,
                  int32_t* kept_idx, int32_t* merge_dst, float* rnorm, float* sim, int32_t* mlist, hipStream_t st);

@@ -91,6 +91,37 @@ def test_null_alignment_and_workspace_errors():
     assert lib.tc_select_topk(ctypes.byref(p), None, None, None, 0, None) == 0
 
 
+def test_rank_and_sequence_entry_points_check_their_arguments_on_the_host():
+    tc = _binding()
+    from workloads import CONFIGS
+    p = tc.params_for(CONFIGS["tiny"])
+    lib = tc.load_library()
+    need = tc.tc_workspace_bytes(p)
+    fake = 4096
+    c = ctypes.byref(p)
+    assert lib.tc_info_rank(c, None, None, 0, 0.0, fake, None, None, fake, need, None) == -1
+    assert lib.tc_info_rank(c, fake, None, 0, 0.0, None, None, None, fake, need, None) == -1
+    assert lib.tc_info_rank(c, fake, fake, p.n_vis + 1, 0.0, fake, None, None, fake, need, None) == -2
+    assert lib.tc_info_rank(c, fake, fake, -1, 0.0, fake, None, None, fake, need, None) == -2
+    assert lib.tc_info_rank(c, fake, None, 0, 1e-9, fake, None, None, fake, need, None) == -4   # below what the Gram route resolves
+    assert lib.tc_info_rank(c, fake, None, 0, 1.0, fake, None, None, fake, need, None) == -4
+    assert lib.tc_info_rank(c, fake, None, 0, -0.5, fake, None, None, fake, need, None) == -4
+    assert lib.tc_info_rank(c, fake, None, 0, 0.0, fake, None, None, fake, 16, None) == -5
+    assert lib.tc_info_rank(c, fake, None, 0, 0.0, fake + 8, None, None, fake, need, None) == -6
+    assert lib.tc_assemble_sequence(c, fake, fake, fake, None, fake, 10000.0, None, None, None) == -1
+    assert lib.tc_assemble_sequence(c, fake, fake, fake, fake, fake, 10000.0, fake, None, None) == -1   # cos without sin
+    assert lib.tc_assemble_sequence(c, fake, fake, fake, fake, fake, 1.0, fake, fake, None) == -4       # base must exceed 1
+    assert lib.tc_assemble_sequence(c, fake, fake, fake, fake, fake + 2, 10000.0, None, None, None) == -6
+    # host arithmetic: the paper's KV-cache column for 192 / 128 / 64 kept tokens at about 80 text tokens
+    assert abs(100 * tc.tc_kv_cache_fraction(80, 576, 192, 32, 2) - 45.1) < 0.15
+    assert abs(100 * tc.tc_kv_cache_fraction(80, 576, 128, 32, 2) - 36.0) < 0.15
+    assert abs(100 * tc.tc_kv_cache_fraction(80, 576, 64, 32, 2) - 26.9) < 0.15
+    assert tc.tc_kv_cache_fraction(80, 576, 600, 32, 2) == -1.0
+    p.batch = 0
+    assert lib.tc_info_rank(c, None, None, 0, 0.0, None, None, None, None, 0, None) == 0
+    assert lib.tc_assemble_sequence(c, None, None, None, None, None, 0.0, None, None, None) == 0
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     from paper_2503_10501_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
