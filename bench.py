@@ -165,6 +165,40 @@ def main():
         "kernel_ms_total": round(total_kernel_ms, 3),
     }
 
+    # the entry points beyond the compression path, timed with events on the launch stream
+    def timed(fn, reps=5):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    O_all = torch.empty(B, N, w.n_heads * w.head_dim, dtype=sd, device="cuda")
+    tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, O=O_all, info=info)
+    rank = torch.empty(B, dtype=torch.int32, device="cuda")
+    ms_rank_all = timed(lambda: tc.tc_info_rank(p, O_all, rank, ws, rtol=0.02))
+    ms_rank_kept = timed(lambda: tc.tc_info_rank(p, O_all, rank, ws, rows=kept, rtol=0.02))
+    L = w.n_sys + w.n_vis + w.n_prompt
+    Ln = L - N + w.k_final
+    Hfull = dev(batch["X"])
+    H_new = torch.empty(B, Ln, w.hidden, dtype=sd, device="cuda")
+    pos = torch.empty(B, Ln, dtype=torch.int32, device="cuda")
+    rc_t = torch.empty(B, Ln, w.head_dim // 2, dtype=torch.float32, device="cuda")
+    rs_t = torch.empty_like(rc_t)
+    ms_asm = timed(lambda: tc.tc_assemble_sequence(p, Hfull, X_out, kept, H_new, pos, 10000.0, rc_t, rs_t), reps=20)
+    asm_bytes = 2 * B * Ln * w.hidden * Hfull.element_size() + 2 * rc_t.numel() * 4 + pos.numel() * 4
+    out["next_rows"] = {
+        "info_rank_all_rows_ms": round(ms_rank_all, 3), "info_rank_kept_rows_ms": round(ms_rank_kept, 3),
+        "assemble_sequence_ms": round(ms_asm, 4),
+        "assemble_sequence_roofline": {"bound": "hbm", "achieved": round(asm_bytes / (ms_asm * 1e-3) / 1e9, 1),
+                                       "peak": 8000.0, "unit": "GB/s",
+                                       "frac": round(asm_bytes / (ms_asm * 1e-3) / 1e9 / 8000.0, 4)},
+        "kv_cache_share": round(tc.tc_kv_cache_fraction(w.n_sys + w.n_prompt, N, w.k_final, 32, 2), 4),
+    }
+
     if not args.no_cpu_baseline:
         from oracle import tokencarve_oracle as orc
         try:
