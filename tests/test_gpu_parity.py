@@ -103,6 +103,35 @@ def test_llava7b_batch64_with_the_256_to_192_counts():
                           oracle_images=[0, 7])
 
 
+def test_token_counts_and_selection_strategies_of_the_ablation_table():
+    """One LLaVA-1.5-7B-shaped image at the visual-token counts of the paper's selection-strategy
+    table (333 ... 64 kept tokens, merge proportion 1/2) with the attention score alone (lambda = 1),
+    the information contribution score alone (lambda = 0) and their combination."""
+    tc, gu, parity, CONFIGS, _ = _mods()
+    from oracle import tokencarve_oracle as orc
+    from workloads import make_batch
+    w = CONFIGS["llava7b_b1"]
+    batch = make_batch(w, [0])
+    p0 = tc.params_for(w, batch=1)
+    O, S = gu.attn_output(p0, batch["Q"], batch["K"], batch["V"])
+    Oh, Sh = gu.host(O).astype(np.float64)[0], gu.host(S).astype(np.float64)[0]
+    C = orc.ics(Oh)[0]
+    Xv = np.ascontiguousarray(batch["X"][:, w.n_sys:w.n_sys + w.n_vis])
+    Xd = gu.dev(Xv, p0)
+    for kf in (333, 288, 192, 144, 128, 72, 64):
+        kp = (3 * kf + 1) // 2
+        for lam in (0.0, 1.0, 0.5):
+            p = tc.params_for(w, batch=1, k_prune=kp, k_final=kf, lam=lam)
+            E, Cg, sig, info = gu.ipgs_score(p, O, S)
+            Eo = orc.combined_score(C, Sh, lam, p.norm_mode)
+            assert np.abs(gu.host(E)[0] - Eo).max() <= 1e-4 * np.abs(Eo).max()
+            order = gu.select_topk(p, E)
+            parity.check_topk(p, [0], E, order, {0: Eo}, {})
+            X_out, kept, dst = gu.merge(p, Xd, O, order)
+            parity.check_merge(p, w, [0], Xv, O, order, X_out, kept, dst, {})
+            assert kept.shape[1] == kf and int((gu.host(dst)[0] >= 0).sum()) == kp
+
+
 def test_hires_2880_tokens_sampled():
     tc, gu, parity, CONFIGS, _ = _mods()
     rep = parity.run_all_stages(CONFIGS["hires_b8"], oracle_images=[3])
