@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path-only", action="store_true",
+                    help="skip the timings of the entry points beyond the compression path (keeps kernel traces clean)")
     ap.add_argument("--cpu-sample", type=int, default=12, help="images timed through the CPU oracle")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -165,7 +167,33 @@ def main():
         "kernel_ms_total": round(total_kernel_ms, 3),
     }
 
-    # the entry points beyond the compression path, timed with events on the launch stream
+    if not args.path_only:
+        next_rows(args, tc, torch, w, p, batch, dev, sd, Q, K, V, X, X_out, kept, dst, info, ws, out)
+
+    if not args.no_cpu_baseline:
+        from oracle import tokencarve_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        n = min(args.cpu_sample, B)
+        t0 = time.perf_counter()
+        for i in range(n):
+            orc.compress(batch["Q"][i], batch["K"][i], batch["V"][i], batch["X"][i, w.n_sys:w.n_sys + w.n_vis],
+                         w.n_sys, w.n_vis, w.k_prune, w.k_final, lam=w.lam, causal=bool(w.causal), dtype=w.dtype)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n / cpu_s, 3), "unit": "images/s", "cores": int(cores),
+                               "kind": "oracle",
+                               "sample": "first %d images of the same batch, float64 numpy oracle, one image at a "
+                                         "time with BLAS/LAPACK threads" % n}
+    print(json.dumps(out))
+
+
+def next_rows(args, tc, torch, w, p, batch, dev, sd, Q, K, V, X, X_out, kept, dst, info, ws, out):
+    """The entry points beyond the compression path, timed with events on the launch stream."""
+    B, N = w.batch, w.n_vis
+
     def timed(fn, reps=5):
         fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -198,25 +226,6 @@ def main():
                                        "frac": round(asm_bytes / (ms_asm * 1e-3) / 1e9 / 8000.0, 4)},
         "kv_cache_share": round(tc.tc_kv_cache_fraction(w.n_sys + w.n_prompt, N, w.k_final, 32, 2), 4),
     }
-
-    if not args.no_cpu_baseline:
-        from oracle import tokencarve_oracle as orc
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        n = min(args.cpu_sample, B)
-        t0 = time.perf_counter()
-        for i in range(n):
-            orc.compress(batch["Q"][i], batch["K"][i], batch["V"][i], batch["X"][i, w.n_sys:w.n_sys + w.n_vis],
-                         w.n_sys, w.n_vis, w.k_prune, w.k_final, lam=w.lam, causal=bool(w.causal), dtype=w.dtype)
-        cpu_s = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(n / cpu_s, 3), "unit": "images/s", "cores": int(cores),
-                               "kind": "oracle",
-                               "sample": "first %d images of the same batch, float64 numpy oracle, one image at a "
-                                         "time with BLAS/LAPACK threads" % n}
-    print(json.dumps(out))
 
 
 if __name__ == "__main__":
