@@ -232,8 +232,9 @@ TC_API double tc_kv_cache_fraction(int32_t n_text, int32_t n_vis, int32_t n_kept
  * Measurement aid: sustained rates of this GPU, for reading roofline fractions against what the part
  * actually delivers.  Runs register-only loops of independent matrix-core products (fp64 16x16x4,
  * fp32 16x16x4, bf16 32x32x16) and a streaming copy of 128 MiB inside `ws` (ws_bytes >= 256 MiB,
- * contents destroyed), waits for them, and writes to the HOST array rates[4]:
- * TFLOP/s fp64, TFLOP/s fp32, TFLOP/s bf16, GB/s copied (read + written).  Blocks the calling thread.
+ * contents destroyed), waits for them, and writes to the HOST array rates[5]:
+ * TFLOP/s fp64 (16x16x4), TFLOP/s fp32, TFLOP/s bf16, GB/s copied (read + written), TFLOP/s fp64 with
+ * the 4x4x4 four-block product.  Blocks the calling thread.
  */
 TC_API int tc_probe_rates(void* ws, size_t ws_bytes, void* stream, float* rates);
 

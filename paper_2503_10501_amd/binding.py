@@ -184,10 +184,11 @@ def tc_profile_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, info, ws, max
 def tc_probe_rates(stream=None):
     """Sustained {fp64, fp32, bf16} matrix-core TFLOP/s and streaming-copy GB/s of the current GPU."""
     ws = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
-    rates = (ctypes.c_float * 4)()
+    rates = (ctypes.c_float * 5)()
     _check(load_library().tc_probe_rates(_ptr(ws), ws.numel(), _stream(stream), rates))
     return {"mfma_f64_tflops": float(rates[0]), "mfma_f32_tflops": float(rates[1]),
-            "mfma_bf16_tflops": float(rates[2]), "copy_gbps": float(rates[3])}
+            "mfma_bf16_tflops": float(rates[2]), "copy_gbps": float(rates[3]),
+            "mfma_f64_4x4x4_tflops": float(rates[4])}
 
 
 def tc_info_rank(p, O, rank, ws, rows=None, rtol=0.0, sigma=None, info=None, stream=None):

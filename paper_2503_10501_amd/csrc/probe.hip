@@ -10,12 +10,14 @@ typedef __attribute__((ext_vector_type(4))) float f4;
 typedef __attribute__((ext_vector_type(16))) float f16v;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf8;
 
-// MODE 0: v_mfma_f64_16x16x4 (2048 flop), 1: v_mfma_f32_16x16x4 (2048 flop), 2: v_mfma_f32_32x32x16_bf16 (32768 flop)
+// MODE 0: v_mfma_f64_16x16x4 (2048 flop), 1: v_mfma_f32_16x16x4 (2048 flop), 2: v_mfma_f32_32x32x16_bf16 (32768 flop),
+// 3: v_mfma_f64_4x4x4, four blocks (512 flop)
 template <int MODE>
 __global__ __launch_bounds__(256) void mfma_loop(float* __restrict__ out, int n) {
   const int tid = threadIdx.x;
   const double a = tid * 1e-3, b = tid * 2e-3;
   d4 c[4];
+  double s4[4] = {0.0, 0.0, 0.0, 0.0};
   f4 e[4];
   f16v g[4];
   bf8 ha, hb;
@@ -34,12 +36,13 @@ __global__ __launch_bounds__(256) void mfma_loop(float* __restrict__ out, int n)
       if (MODE == 0) c[i] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c[i], 0, 0, 0);
       if (MODE == 1) e[i] = __builtin_amdgcn_mfma_f32_16x16x4f32((float)a, (float)b, e[i], 0, 0, 0);
       if (MODE == 2) g[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ha, hb, g[i], 0, 0, 0);
+      if (MODE == 3) s4[i] = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, s4[i], 0, 0, 0);
     }
   }
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
-    s += (float)c[i][0] + e[i][0] + g[i][0];
+    s += (float)c[i][0] + e[i][0] + g[i][0] + (float)s4[i];
   }
   out[(size_t)blockIdx.x * 256 + tid] = s;
 }
@@ -83,7 +86,8 @@ extern "C" int tc_probe_rates(void* ws, size_t ws_bytes, void* stream, float* ra
   const float t0 = time_mfma<0>(buf, blocks, iters, st);
   const float t1 = time_mfma<1>(buf, blocks, iters, st);
   const float t2 = time_mfma<2>(buf, blocks, iters, st);
-  if (t0 <= 0.f || t1 <= 0.f || t2 <= 0.f) return TC_ERR_HIP;
+  const float t3 = time_mfma<3>(buf, blocks, iters, st);
+  if (t0 <= 0.f || t1 <= 0.f || t2 <= 0.f || t3 <= 0.f) return TC_ERR_HIP;
   rates[0] = (float)(mfmas * 2048.0 / (t0 * 1e-3) / 1e12);
   rates[1] = (float)(mfmas * 2048.0 / (t1 * 1e-3) / 1e12);
   rates[2] = (float)(mfmas * 32768.0 / (t2 * 1e-3) / 1e12);
@@ -104,5 +108,6 @@ extern "C" int tc_probe_rates(void* ws, size_t ws_bytes, void* stream, float* ra
   (void)hipEventDestroy(e1);
   if (best <= 0.f) return TC_ERR_HIP;
   rates[3] = (float)(2.0 * half / (best * 1e-3) / 1e9);  // GB/s, bytes read + bytes written
+  rates[4] = (float)(mfmas * 512.0 / (t3 * 1e-3) / 1e12);
   return check_launch();
 }
