@@ -586,28 +586,40 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
   }
 }
 
-// Eigenvector update in float32: a 64-row slab of the columns of pair J, U_J <- U_J R_J.
+// Eigenvector update in float32: U_J <- U_J R_J on the columns of pair J, 64-row slabs.
 // U only feeds Eq. 3-6, where an absolute error of 1e-6 per entry is far below the tolerance, so it
 // is stored and multiplied in float32 whatever the type of G; R is rounded to float32 on load.
+// A workgroup keeps its fragments of R_J in registers and walks over U_CHUNK consecutive slabs,
+// fetching the next slab into registers while the matrix cores work on the current one.
+constexpr int U_CHUNK = 3;
+
 template <typename T>
 __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
                                                        int img0, int nimg) {
-  const int P = nblk / 2;
+  const int P = nblk / 2, nslab = Np / JT, nchunk = (nslab + U_CHUNK - 1) / U_CHUNK;
   int img, tile;
-  if (!group_on_xcd(blockIdx.x, (Np / JT) * P, nimg, &img, &tile)) return;
+  if (!group_on_xcd(blockIdx.x, nchunk * P, nimg, &img, &tile)) return;
   const int b = img0 + img;
   if (state[b].done) return;
   __shared__ float X[JT][SLD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
-  const int J = tile % P, slab = tile / P;
+  const int J = tile % P, chunk = tile / P;
+  const int slab0 = chunk * U_CHUNK, slab1 = min(nslab, slab0 + U_CHUNK);
   float* M = U + (size_t)b * Np * Np;
   int colbase[2];
   round_robin_pair(nblk, step, J, &colbase[0], &colbase[1]);
   colbase[0] *= JB; colbase[1] *= JB;
-  const int row0 = slab * JT;
   const T* RJ = R + ((size_t)b * P + J) * JT * JT;
+  const int c = (lane & 15) + 16 * wave;
+  const int gc = colbase[c >> 5] + (c & 31);
+  float xpre[16];
+  auto fetch = [&](int slab) {
+#pragma unroll
+    for (int it = 0; it < 16; it++) xpre[it] = M[(size_t)(slab * JT + (lane >> 4) + 4 * it) * Np + gc];
+  };
+  fetch(slab0);
   float rf[16][2];
 #pragma unroll
   for (int ks = 0; ks < 16; ks++) {
@@ -615,40 +627,38 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
     rf[ks][0] = (float)RJ[k * JT + wc * 32 + (lane & 15)];
     rf[ks][1] = (float)RJ[k * JT + wc * 32 + 16 + (lane & 15)];
   }
-  {
-    const int c = (lane & 15) + 16 * wave;
-    const int gc = colbase[c >> 5] + (c & 31);
+  for (int slab = slab0; slab < slab1; slab++) {
 #pragma unroll
-    for (int it = 0; it < 16; it++) {
-      const int r = (lane >> 4) + 4 * it;
-      X[r][c] = M[(size_t)(row0 + r) * Np + gc];
+    for (int it = 0; it < 16; it++) X[(lane >> 4) + 4 * it][c] = xpre[it];
+    __syncthreads();
+    if (slab + 1 < slab1) fetch(slab + 1);
+    f4 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+      for (int j = 0; j < 2; j++) acc[i][j] = f4{0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < 16; ks++) {
+      const int k = ks + 16 * (lane >> 4);
+      const float a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
+      acc[0][0] = MM<float>::mma(a0, rf[ks][0], acc[0][0]);
+      acc[0][1] = MM<float>::mma(a0, rf[ks][1], acc[0][1]);
+      acc[1][0] = MM<float>::mma(a1, rf[ks][0], acc[1][0]);
+      acc[1][1] = MM<float>::mma(a1, rf[ks][1], acc[1][1]);
     }
+    const int row0 = slab * JT;
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const int r = wr * 32 + mt * 16 + MM<float>::row(j, lane);
+          const int cc = wc * 32 + nt * 16 + (lane & 15);
+          M[(size_t)(row0 + r) * Np + colbase[cc >> 5] + (cc & 31)] = acc[mt][nt][j];
+        }
+    __syncthreads();  // every wave has finished reading X
   }
-  __syncthreads();
-  f4 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; i++)
-#pragma unroll
-    for (int j = 0; j < 2; j++) acc[i][j] = f4{0, 0, 0, 0};
-#pragma unroll
-  for (int ks = 0; ks < 16; ks++) {
-    const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
-    const float a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
-    acc[0][0] = MM<float>::mma(a0, rf[ks][0], acc[0][0]);
-    acc[0][1] = MM<float>::mma(a0, rf[ks][1], acc[0][1]);
-    acc[1][0] = MM<float>::mma(a1, rf[ks][0], acc[1][0]);
-    acc[1][1] = MM<float>::mma(a1, rf[ks][1], acc[1][1]);
-  }
-#pragma unroll
-  for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-    for (int nt = 0; nt < 2; nt++)
-#pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const int r = wr * 32 + mt * 16 + MM<float>::row(j, lane);
-        const int c = wc * 32 + nt * 16 + (lane & 15);
-        M[(size_t)(row0 + r) * Np + colbase[c >> 5] + (c & 31)] = acc[mt][nt][j];
-      }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -699,7 +709,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
   const dim3 gs(P, nimg);
-  const int gg = grid_for_groups((P * (P + 1) / 2 + G_CHUNK - 1) / G_CHUNK, nimg), gu = grid_for_groups((Np / JT) * P, nimg);
+  const int gg = grid_for_groups((P * (P + 1) / 2 + G_CHUNK - 1) / G_CHUNK, nimg), gu = grid_for_groups(((Np / JT + U_CHUNK - 1) / U_CHUNK) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
       // After the first sweep the diagonal blocks are nearly diagonal: most visits only rotate index
