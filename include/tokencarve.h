@@ -59,7 +59,7 @@ typedef enum {
   TC_ERR_HIP = -7        /* a HIP launch failed (hipGetLastError was not hipSuccess) */
 } tc_status;
 
-typedef enum { TC_F32 = 0, TC_BF16 = 1 } tc_dtype;          /* storage of Q,K,V,O,X,X_out */
+typedef enum { TC_F32 = 0, TC_BF16 = 1, TC_F16 = 2 } tc_dtype;  /* storage of Q,K,V,O,X,X_out (TC_F16: IEEE half) */
 typedef enum { TC_NORM_NONE = 0, TC_NORM_MINMAX = 1 } tc_norm;
 /* arithmetic of the Gram matrix and of the eigenvalue iteration (the eigenvectors are accumulated in
    float32 either way); TC_EIG_F32 is only accurate enough for well-conditioned spectra */

@@ -63,10 +63,12 @@ NORM_MINMAX = 1
 # storage rounding (stage boundary: Z is stored in the workload's dtype)
 # ----------------------------------------------------------------------------
 def to_storage(a, dtype):
-    """Round float64 values to the nearest bf16 / float32 value (ties to even); returns float64."""
+    """Round float64 values to the nearest bf16 / IEEE half / float32 value (ties to even); returns float64."""
     a = np.asarray(a, dtype=np.float64)
     if dtype == "f32":
         return a.astype(np.float32).astype(np.float64)
+    if dtype == "f16":
+        return a.astype(np.float16).astype(np.float64)
     if dtype != "bf16":
         raise ValueError(dtype)
     # bf16 has 8 significand bits: round x to a multiple of 2^(e-7), e = floor(log2|x|).

@@ -13,7 +13,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtokencarve.so")
 
-TC_F32, TC_BF16 = 0, 1
+TC_F32, TC_BF16, TC_F16 = 0, 1, 2
+_DTYPES = {"f32": TC_F32, "bf16": TC_BF16, "f16": TC_F16}
 TC_NORM_NONE, TC_NORM_MINMAX = 0, 1
 TC_EIG_F64, TC_EIG_F32 = 0, 1
 
@@ -54,7 +55,7 @@ def params_for(w, batch=None, **overrides):
     """tc_params for a workloads.Workload."""
     kw = dict(batch=w.batch if batch is None else batch, seq_len=w.seq_len, vis_start=w.n_sys, n_vis=w.n_vis,
               n_heads=w.n_heads, head_dim=w.head_dim, hidden_dim=w.hidden,
-              dtype=TC_BF16 if w.dtype == "bf16" else TC_F32, k_prune=w.k_prune, k_final=w.k_final, lam=w.lam,
+              dtype=_DTYPES[w.dtype], k_prune=w.k_prune, k_final=w.k_final, lam=w.lam,
               causal=w.causal)
     kw.update(overrides)
     return make_params(**kw)
@@ -114,7 +115,7 @@ def _check(rc):
 
 
 def storage_dtype(p):
-    return torch.bfloat16 if p.dtype == TC_BF16 else torch.float32
+    return {TC_F32: torch.float32, TC_BF16: torch.bfloat16, TC_F16: torch.float16}[p.dtype]
 
 
 def tc_status_string(status):

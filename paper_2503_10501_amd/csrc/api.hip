@@ -8,7 +8,7 @@ namespace tc {
 
 int make_plan(const tc_params* p, Plan* pl) {
   if (!p) return TC_ERR_NULL;
-  if (p->dtype != TC_F32 && p->dtype != TC_BF16) return TC_ERR_DTYPE;
+  if (p->dtype != TC_F32 && p->dtype != TC_BF16 && p->dtype != TC_F16) return TC_ERR_DTYPE;
   if (p->eig_dtype != TC_EIG_F64 && p->eig_dtype != TC_EIG_F32) return TC_ERR_DTYPE;
   if (p->batch < 0 || p->seq_len < 1 || p->vis_start < 0 || p->n_vis < 1 || p->n_vis > MAX_NVIS ||
       (int64_t)p->vis_start + p->n_vis > p->seq_len || p->n_heads < 1 || p->n_heads > 1024 ||
@@ -30,7 +30,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.nA = nA; q.nB = nB;
   q.Np = round_up(q.N, JT); q.nblk = q.Np / JB; q.P = q.nblk / 2; q.steps = q.nblk - 1;
   q.q_tile = 128; q.n_qtiles = (q.N + q.q_tile - 1) / q.q_tile;
-  q.esize = p->dtype == TC_BF16 ? 2 : 4;
+  q.esize = p->dtype == TC_F32 ? 4 : 2;
   q.tsize = p->eig_dtype == TC_EIG_F64 ? 8 : 4;
   q.groups = p->stream_groups;
   q.max_sweeps = p->jacobi_max_sweeps > 0 ? p->jacobi_max_sweeps : 30;

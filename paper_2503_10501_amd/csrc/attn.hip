@@ -1,7 +1,7 @@
 // Attention output of the visual query rows (Eq. 3-1, 3-2 and the slice of Section 3.2.2) and the
 // attention score of every visual token (Eq. 3-7).
 //
-// bf16 path: one workgroup = one (image, head, 128-query tile); each wavefront owns 32 queries.
+// 16-bit storage (bf16 or half): one workgroup = one (image, head, 128-query tile); each wavefront owns 32 queries.
 // Scores are formed transposed, S^T = K Q^T, so that a lane owns one query (softmax statistics stay
 // in the lane) and the probabilities feed O^T = V^T P^T straight from the accumulator registers.
 // Two passes over the keys: pass 1 finds the row maximum and normaliser, pass 2 recomputes the
@@ -13,7 +13,23 @@
 namespace tc {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf8;
+typedef __attribute__((ext_vector_type(8))) _Float16 h8;
 typedef __attribute__((ext_vector_type(16))) float f16v;
+
+// The 16-bit element type of the matrix-core operands: bf16 (F16 = false) or IEEE half.
+template <bool F16> struct Elem16;
+template <> struct Elem16<false> {
+  typedef __bf16 elem;
+  typedef bf8 vec8;
+  __device__ static inline f16v mma(vec8 a, vec8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+  __device__ static inline uint16_t bits(float f) { return float_to_bf16_bits(f); }
+};
+template <> struct Elem16<true> {
+  typedef _Float16 elem;
+  typedef h8 vec8;
+  __device__ static inline f16v mma(vec8 a, vec8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
+  __device__ static inline uint16_t bits(float f) { return float_to_f16_bits(f); }
+};
 
 constexpr int AQ = 128;  // queries per workgroup
 constexpr int AK = 64;   // keys per LDS tile
@@ -74,8 +90,9 @@ __device__ inline void store_v_tile_transposed(uint16_t* Vt, const uint4* regs) 
 
 // S^T sub-tile: 32 keys (rows) x 32 queries (columns); accumulator element r of a lane is
 // key 8*(r/4) + 4*(lane/32) + r%4, query lane%32.
-template <int DH>
-__device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const bf8* qf, int lane) {
+template <int DH, bool F16>
+__device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const typename Elem16<F16>::vec8* qf, int lane) {
+  typedef typename Elem16<F16>::vec8 vec8;
   constexpr int KLD = AttnSmem<DH>::KLD;
   f16v acc;
 #pragma unroll
@@ -83,18 +100,20 @@ __device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const bf8* qf,
   const uint16_t* row = Ks + (sub * 32 + (lane & 31)) * KLD + 8 * (lane >> 5);
 #pragma unroll
   for (int ks = 0; ks < DH / 16; ks++) {
-    const bf8 a = *reinterpret_cast<const bf8*>(row + 16 * ks);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], acc, 0, 0, 0);
+    const vec8 a = *reinterpret_cast<const vec8*>(row + 16 * ks);
+    acc = Elem16<F16>::mma(a, qf[ks], acc);
   }
   return acc;
 }
 
-template <int DH>
+template <int DH, bool F16>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                         const uint16_t* __restrict__ V, uint16_t* __restrict__ O,
                                                         float* __restrict__ Spart, int L, int Ls, int N, int H,
                                                         int causal, float scale_log2e, int n_qtiles, int B) {
   typedef AttnSmem<DH> SM;
+  typedef typename Elem16<F16>::vec8 vec8;
+  typedef typename Elem16<F16>::elem elem;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SM::MAIN];
   __shared__ float cs[4][AK];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
@@ -116,10 +135,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   const int kend = causal ? min(L, Ls + q_last + 1) : L;
   const int n_tiles = (kend + AK - 1) / AK;
 
-  bf8 qf[DH / 16];
+  vec8 qf[DH / 16];
 #pragma unroll
   for (int ks = 0; ks < DH / 16; ks++)
-    qf[ks] = *reinterpret_cast<const bf8*>(Qh + (size_t)p * DH + 16 * ks + 8 * half);
+    qf[ks] = *reinterpret_cast<const vec8*>(Qh + (size_t)p * DH + 16 * ks + 8 * half);
 
   // ---------------- pass 1: row maximum and normaliser (log2 domain) ----------------
   float m_run = -INFINITY, l_run = 0.f;
@@ -132,7 +151,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
     __syncthreads();
 #pragma unroll
     for (int sub = 0; sub < 2; sub++) {
-      const f16v acc = score_subtile<DH>(Ks, sub, qf, lane);
+      const f16v acc = score_subtile<DH, F16>(Ks, sub, qf, lane);
       float s2[16], mx = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; r++) {
@@ -179,7 +198,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
     for (int sub = 0; sub < 2; sub++) {
       float pr[16];
       {
-        const f16v acc = score_subtile<DH>(Ks, sub, qf, lane);
+        const f16v acc = score_subtile<DH, F16>(Ks, sub, qf, lane);
 #pragma unroll
         for (int r = 0; r < 16; r++) {
           const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
@@ -190,24 +209,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
       // sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
 #pragma unroll
       for (int u = 0; u < 2; u++) {
-        // probabilities enter the matrix cores as a bf16 head plus a bf16 remainder (16 significant
-        // bits), so O is accurate to its own final rounding
-        bf8 pb, pl;
+        // probabilities enter the matrix cores as a 16-bit head plus a 16-bit remainder (16 or more
+        // significant bits), so O is accurate to its own final rounding
+        vec8 pb, pl;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
           const float pv = pr[8 * u + i];
-          pb[i] = (__bf16)pv;
-          pl[i] = (__bf16)(pv - (float)pb[i]);
+          pb[i] = (elem)pv;
+          pl[i] = (elem)(pv - (float)pb[i]);
         }
 #pragma unroll
         for (int mt = 0; mt < DH / 32; mt++) {
           const uint16_t* vrow = Vt + (32 * mt + (lane & 31)) * SM::VLD + sub * 32 + 16 * u + 4 * half;
           const uint2 lo = *reinterpret_cast<const uint2*>(vrow);
           const uint2 hi = *reinterpret_cast<const uint2*>(vrow + 8);
-          union { uint4 u4; bf8 v; } va;
+          union { uint4 u4; vec8 v; } va;
           va.u4 = uint4{lo.x, lo.y, hi.x, hi.y};
-          oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb, oacc[mt], 0, 0, 0);
-          oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pl, oacc[mt], 0, 0, 0);
+          oacc[mt] = Elem16<F16>::mma(va.v, pb, oacc[mt]);
+          oacc[mt] = Elem16<F16>::mma(va.v, pl, oacc[mt]);
         }
       }
       // column sums over this wavefront's 32 queries: recursive halving across the 32 lanes of each
@@ -245,7 +264,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       const int d = 32 * mt + 8 * (r >> 2) + 4 * half + (r & 3);
-      Os[(lane & 31) * SM::KLD + d] = float_to_bf16_bits(oacc[mt][r]);
+      Os[(lane & 31) * SM::KLD + d] = Elem16<F16>::bits(oacc[mt][r]);
     }
   __syncthreads();
   constexpr int CH = DH / 8;
@@ -351,17 +370,19 @@ __global__ __launch_bounds__(256) void attn_f32_cols(const float* __restrict__ Q
 
 int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const void* K, const void* V, void* O,
                      float* S, float* Spart, hipStream_t st) {
-  if (dtype == TC_BF16) {
+  if (dtype == TC_BF16 || dtype == TC_F16) {
     const dim3 grid(grid_for_groups(pl.n_qtiles, pl.B * pl.H));
     const float sl2 = pl.scale * 1.4426950408889634f;
-    if (pl.dh == 128)
-      TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<128><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
-                                                  (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
-                                                  pl.n_qtiles, pl.B)));
-    else
-      TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<64><<<grid, 256, 0, st>>>((const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V,
-                                                 (uint16_t*)O, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2,
-                                                 pl.n_qtiles, pl.B)));
+    const uint16_t *q = (const uint16_t*)Q, *k = (const uint16_t*)K, *v = (const uint16_t*)V;
+    uint16_t* o = (uint16_t*)O;
+#define TC_ATTN16(DH_, F16_) \
+  TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<DH_, F16_><<<grid, 256, 0, st>>>(q, k, v, o, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2, pl.n_qtiles, pl.B)))
+    if (pl.dh == 128) {
+      if (dtype == TC_F16) TC_ATTN16(128, true); else TC_ATTN16(128, false);
+    } else {
+      if (dtype == TC_F16) TC_ATTN16(64, true); else TC_ATTN16(64, false);
+    }
+#undef TC_ATTN16
     if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.H, pl.n_qtiles)));
   } else {
     const dim3 grid(pl.N, pl.H, pl.B);

@@ -25,6 +25,18 @@ __device__ inline void load8<uint16_t>(const uint16_t* src, double* dst) {
   }
 }
 template <>
+__device__ inline void load8<f16_t>(const f16_t* src, double* dst) {
+  uint4 v = *reinterpret_cast<const uint4*>(src);
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    float lo, hi;
+    unpack2<f16_t>(w[i], &lo, &hi);
+    dst[2 * i] = (double)lo;
+    dst[2 * i + 1] = (double)hi;
+  }
+}
+template <>
 __device__ inline void load8<float>(const float* src, double* dst) {
   float4 a = *reinterpret_cast<const float4*>(src);
   float4 b = *reinterpret_cast<const float4*>(src + 4);
@@ -110,6 +122,11 @@ int launch_gram(const Plan& pl, int dtype, int eig_dtype, const void* O, void* G
       TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, double><<<grid, block, 0, st>>>((const uint16_t*)O, (double*)G, pl.N, pl.D, pl.Np, pl.B)));
     else
       TC_TIMED(PK_GRAM, 0, st, (gram_kernel<uint16_t, float><<<grid, block, 0, st>>>((const uint16_t*)O, (float*)G, pl.N, pl.D, pl.Np, pl.B)));
+  } else if (dtype == TC_F16) {
+    if (eig_dtype == TC_EIG_F64)
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<f16_t, double><<<grid, block, 0, st>>>((const f16_t*)O, (double*)G, pl.N, pl.D, pl.Np, pl.B)));
+    else
+      TC_TIMED(PK_GRAM, 0, st, (gram_kernel<f16_t, float><<<grid, block, 0, st>>>((const f16_t*)O, (float*)G, pl.N, pl.D, pl.Np, pl.B)));
   } else {
     if (eig_dtype == TC_EIG_F64)
       TC_TIMED(PK_GRAM, 0, st, (gram_kernel<float, double><<<grid, block, 0, st>>>((const float*)O, (double*)G, pl.N, pl.D, pl.Np, pl.B)));

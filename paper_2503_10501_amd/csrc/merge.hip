@@ -6,6 +6,7 @@
 namespace tc {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf8;
+typedef __attribute__((ext_vector_type(8))) _Float16 h8;
 typedef __attribute__((ext_vector_type(16))) float f16v;
 
 // ---- 1 / ||metric row||_2 for the k_prune surviving rows, in score order -----------------------
@@ -23,7 +24,8 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const TIn* __restrict__ me
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+        float lo, hi;
+        unpack2<TIn>(w[i], &lo, &hi);
         ss += lo * lo;
         ss += hi * hi;
       }
@@ -38,10 +40,11 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const TIn* __restrict__ me
   if (lane == 0) rnorm[(size_t)b * kp + r] = 1.0f / fmaxf(sqrtf(ss), 1e-30f);
 }
 
-// ---- Sim[b][j][i] = <z_Bj, z_Ai> / (|z_Bj| |z_Ai|), bf16 rows on the bf16 matrix cores -----------
+// ---- Sim[b][j][i] = <z_Bj, z_Ai> / (|z_Bj| |z_Ai|), 16-bit rows (bf16 or half) on the matrix cores ---
 constexpr int SK = 64;       // K chunk
 constexpr int SP = SK + 8;   // padded LDS row (bf16 elements)
 
+template <bool F16>
 __global__ __launch_bounds__(256) void sim_bf16_kernel(const uint16_t* __restrict__ metric,
                                                        const int32_t* __restrict__ order,
                                                        const float* __restrict__ rnorm, float* __restrict__ sim, int N,
@@ -73,9 +76,15 @@ __global__ __launch_bounds__(256) void sim_bf16_kernel(const uint16_t* __restric
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < SK; kk += 16) {
-      const bf8 fa = *reinterpret_cast<const bf8*>(&Bj[wr * 32 + (lane & 31)][kk + 8 * (lane >> 5)]);
-      const bf8 fb = *reinterpret_cast<const bf8*>(&Ai[wc * 32 + (lane & 31)][kk + 8 * (lane >> 5)]);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+      if constexpr (F16) {
+        const h8 fa = *reinterpret_cast<const h8*>(&Bj[wr * 32 + (lane & 31)][kk + 8 * (lane >> 5)]);
+        const h8 fb = *reinterpret_cast<const h8*>(&Ai[wc * 32 + (lane & 31)][kk + 8 * (lane >> 5)]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc, 0, 0, 0);
+      } else {
+        const bf8 fa = *reinterpret_cast<const bf8*>(&Bj[wr * 32 + (lane & 31)][kk + 8 * (lane >> 5)]);
+        const bf8 fb = *reinterpret_cast<const bf8*>(&Ai[wc * 32 + (lane & 31)][kk + 8 * (lane >> 5)]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc, 0, 0, 0);
+      }
     }
   }
   const int i = ti * 64 + wc * 32 + (lane & 31);
@@ -239,7 +248,8 @@ __global__ __launch_bounds__(256) void average_kernel(const TIn* __restrict__ X,
       if constexpr (sizeof(TIn) == 2) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-          const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+          float lo, hi;
+          unpack2<TIn>(w[i], &lo, &hi);
           acc[2 * i] = first ? lo : acc[2 * i] + lo;
           acc[2 * i + 1] = first ? hi : acc[2 * i + 1] + hi;
         }
@@ -253,10 +263,7 @@ __global__ __launch_bounds__(256) void average_kernel(const TIn* __restrict__ X,
     uint32_t w[4];
     if constexpr (sizeof(TIn) == 2) {
 #pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const uint32_t lo = float_to_bf16_bits(acc[2 * i] / fc), hi = float_to_bf16_bits(acc[2 * i + 1] / fc);
-        w[i] = lo | (hi << 16);
-      }
+      for (int i = 0; i < 4; i++) w[i] = pack2<TIn>(acc[2 * i] / fc, acc[2 * i + 1] / fc);
     } else {
 #pragma unroll
       for (int i = 0; i < 4; i++) w[i] = __float_as_uint(acc[i] / fc);
@@ -269,11 +276,15 @@ int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, c
                  int32_t* kept_idx, int32_t* merge_dst, float* rnorm, float* sim, int32_t* mlist, hipStream_t st) {
   const dim3 gn((pl.kp + 3) / 4, pl.B);
   if (pl.nA > 0) {
-    if (dtype == TC_BF16) {
-      TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
+    if (dtype == TC_BF16 || dtype == TC_F16) {
       const dim3 gsim(((pl.nB + 63) / 64) * ((pl.nA + 63) / 64), pl.B);
-      TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA,
-                                            pl.nB)));
+      if (dtype == TC_F16) {
+        TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<f16_t><<<gn, 256, 0, st>>>((const f16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
+        TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<true><<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
+      } else {
+        TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
+        TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<false><<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
+      }
     } else {
       TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<float><<<gn, 256, 0, st>>>((const float*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
       const dim3 gsim(((pl.nB + 15) / 16) * ((pl.nA + 15) / 16), pl.B);
@@ -283,7 +294,9 @@ int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, c
   const size_t lds = ((size_t)pl.N + 2 * (size_t)pl.nB + 512) * 4;
   TC_TIMED(PK_ASSIGN, 0, st, (assign_kernel<<<pl.B, 256, lds, st>>>(sim, order, kept_idx, merge_dst, mlist, pl.N, pl.kp, pl.kf, pl.nA, pl.nB)));
   const dim3 ga(pl.kf, pl.B);
-  if (dtype == TC_BF16)
+  if (dtype == TC_F16)
+    TC_TIMED(PK_AVERAGE, 0, st, (average_kernel<f16_t><<<ga, 256, 0, st>>>((const f16_t*)X, kept_idx, mlist, (f16_t*)X_out, pl.N, pl.hidden, pl.kf, pl.m)));
+  else if (dtype == TC_BF16)
     TC_TIMED(PK_AVERAGE, 0, st, (average_kernel<uint16_t><<<ga, 256, 0, st>>>((const uint16_t*)X, kept_idx, mlist, (uint16_t*)X_out, pl.N, pl.hidden,
                                                 pl.kf, pl.m)));
   else

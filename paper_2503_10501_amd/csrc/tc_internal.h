@@ -101,6 +101,29 @@ __device__ inline uint16_t float_to_bf16_bits(float f) {  // round to nearest ev
   return uint16_t(u >> 16);
 }
 
+// IEEE half precision storage (TC_F16): conversions by the hardware, round to nearest even.
+struct f16_t { uint16_t bits; };  // tag type for templates; bf16 storage uses plain uint16_t
+__device__ inline float f16_bits_to_float(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+__device__ inline uint16_t float_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+
+// The two 16-bit elements packed in a 32-bit word, and the way back (T = uint16_t: bf16, f16_t: half).
+template <typename T> __device__ inline void unpack2(uint32_t w, float* lo, float* hi);
+template <> __device__ inline void unpack2<uint16_t>(uint32_t w, float* lo, float* hi) {
+  *lo = __uint_as_float(w << 16);
+  *hi = __uint_as_float(w & 0xffff0000u);
+}
+template <> __device__ inline void unpack2<f16_t>(uint32_t w, float* lo, float* hi) {
+  *lo = f16_bits_to_float((uint16_t)(w & 0xffffu));
+  *hi = f16_bits_to_float((uint16_t)(w >> 16));
+}
+template <typename T> __device__ inline uint32_t pack2(float lo, float hi);
+template <> __device__ inline uint32_t pack2<uint16_t>(float lo, float hi) {
+  return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+}
+template <> __device__ inline uint32_t pack2<f16_t>(float lo, float hi) {
+  return (uint32_t)float_to_f16_bits(lo) | ((uint32_t)float_to_f16_bits(hi) << 16);
+}
+
 // Round-robin tournament on n (even) players: pair `i` (0 <= i < n/2) of round `s` (0 <= s < n-1).
 __host__ __device__ inline void round_robin_pair(int n, int s, int i, int* a, int* b) {
   const int m = n - 1;

@@ -16,7 +16,7 @@ def host(t):
 
 
 def storage_name(p):
-    return "bf16" if p.dtype == tc.TC_BF16 else "f32"
+    return {tc.TC_F32: "f32", tc.TC_BF16: "bf16", tc.TC_F16: "f16"}[p.dtype]
 
 
 def attn_output(p, Q, K, V):

@@ -24,6 +24,8 @@ from tests import gpu_utils as gu
 def ulp_bound(ref, dtype, rms):
     if dtype == "bf16":
         return 2.0 ** -7 * np.abs(ref) + 1e-5 * rms
+    if dtype == "f16":
+        return 2.0 ** -10 * np.abs(ref) + 1e-5 * rms
     return 2.0 ** -22 * np.abs(ref) + 1e-5 * rms   # float32 storage: sums are accumulated in float32
 
 

@@ -22,6 +22,8 @@ SMALL = {
     "bf16_ragged": (11, 2, 200, 36, 4, 4, 128, "bf16", 50, 33, 16, "powerlaw", 0.05, "proj"),
     "bf16_dh64_odd": (12, 2, 100, 5, 3, 3, 64, "bf16", 31, 20, 8, "powerlaw", 0.05, "proj"),
     "bf16_iid": (13, 1, 130, 7, 0, 2, 128, "bf16", 64, 32, 8, "linspace", 0.01, "iid"),
+    "f16_ragged": (16, 2, 150, 9, 2, 3, 128, "f16", 40, 27, 12, "powerlaw", 0.05, "proj"),
+    "f16_dh64": (17, 1, 90, 4, 0, 2, 64, "f16", 30, 30, 8, "linspace", 0.01, "iid"),
     "f32_ragged": (14, 1, 70, 3, 2, 2, 64, "f32", 20, 14, 8, "linspace", 0.01, "iid"),
     "f32_dh128": (15, 1, 40, 0, 0, 1, 128, "f32", 40, 20, 4, "linspace", 0.01, "iid"),
 }
@@ -87,6 +89,14 @@ def test_llava7b_batch1_full_size():
     tc, gu, parity, CONFIGS, _ = _mods()
     rep = parity.run_all_stages(CONFIGS["llava7b_b1"])
     print("llava7b_b1", rep)
+    assert max(rep["C_rel"]) < 1e-4
+
+
+def test_llava7b_shape_with_half_precision_storage():
+    # the precision the paper's own runs used (V100): IEEE half storage, same shapes and counts
+    tc, gu, parity, CONFIGS, _ = _mods()
+    rep = parity.run_all_stages(CONFIGS["llava7b_b1"].with_(dtype="f16"))
+    print("llava7b_b1 f16", rep)
     assert max(rep["C_rel"]) < 1e-4
 
 

@@ -96,3 +96,22 @@ def test_storage_rounding_matches_torch():
     ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
     np.testing.assert_array_equal(mine, ref)
     np.testing.assert_array_equal(orc.to_storage(x, "f32"), x.astype(np.float32).astype(np.float64))
+
+
+def test_half_precision_storage_rounding_closed_forms():
+    """IEEE half: 11 significant bits, ties to even, largest finite value 65504, subnormals down to 2^-24."""
+    x = np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -10, -(2.0 + 2.0 ** -10), 65504.0, 65519.9,
+                  2.0 ** -24, 0.6 * 2.0 ** -24, 2.0 ** -14 * (1 + 2.0 ** -10), 0.1])
+    got = orc.to_storage(x, "f16")
+    expect = np.array([1.0, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -10, -2.0, 65504.0, 65504.0,
+                       2.0 ** -24, 2.0 ** -24, 2.0 ** -14 * (1 + 2.0 ** -10), 0.0999755859375])
+    np.testing.assert_array_equal(got, expect)
+    from workloads.generate import round_to_storage
+    rng = np.random.default_rng(3)
+    y = rng.standard_normal(1000) * 10.0 ** rng.integers(-6, 4, 1000)
+    np.testing.assert_array_equal(round_to_storage(y, "f16").astype(np.float64), orc.to_storage(y, "f16"))
+    # idempotent, monotone, within half a unit in the last place
+    r = orc.to_storage(y, "f16")
+    np.testing.assert_array_equal(orc.to_storage(r, "f16"), r)
+    big = np.abs(y) >= 2.0 ** -14
+    assert np.all(np.abs(r - y)[big] <= 2.0 ** -11 * np.abs(y)[big])

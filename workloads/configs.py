@@ -18,7 +18,7 @@ class Workload:
     n_prompt: int         # L_p  (tokens after the image)
     n_heads: int          # H
     head_dim: int         # d_h
-    dtype: str            # "f32" | "bf16": storage type of Q,K,V,O,X
+    dtype: str            # "f32" | "bf16" | "f16": storage type of Q,K,V,O,X
     k_prune: int          # L_vc (1 + rho)
     k_final: int          # L_vc
     rank: int             # planted rank of the hidden states

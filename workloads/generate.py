@@ -18,11 +18,14 @@ def round_to_storage(a, dtype):
     """Round a float array to the storage type and return it as float32.
 
     "f32": plain cast.  "bf16": round-to-nearest-even on the upper 16 bits of
-    the float32 pattern (a storage-format conversion, not part of the method).
+    the float32 pattern.  "f16": IEEE half, round-to-nearest-even (storage-format
+    conversions, not part of the method).
     """
     a32 = np.ascontiguousarray(a, dtype=np.float32)
     if dtype == "f32":
         return a32
+    if dtype == "f16":
+        return np.asarray(a, dtype=np.float64).astype(np.float16).astype(np.float32)
     if dtype != "bf16":
         raise ValueError(dtype)
     u = a32.view(np.uint32)
