@@ -589,15 +589,15 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
 // Eigenvector update in float32: U_J <- U_J R_J on the columns of pair J, 64-row slabs.
 // U only feeds Eq. 3-6, where an absolute error of 1e-6 per entry is far below the tolerance, so it
 // is stored and multiplied in float32 whatever the type of G; R is rounded to float32 on load.
-// A workgroup keeps its fragments of R_J in registers and walks over U_CHUNK consecutive slabs,
-// fetching the next slab into registers while the matrix cores work on the current one.
-constexpr int U_CHUNK = 3;
+// A workgroup keeps its fragments of R_J in registers and walks over `uchunk` consecutive slabs,
+// fetching the next slab into registers while the matrix cores work on the current one (3 slabs
+// when the launch has enough workgroups to fill the chip that way, else one slab per workgroup).
 
 template <typename T>
 __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
-                                                       int img0, int nimg) {
-  const int P = nblk / 2, nslab = Np / JT, nchunk = (nslab + U_CHUNK - 1) / U_CHUNK;
+                                                       int img0, int nimg, int uchunk) {
+  const int P = nblk / 2, nslab = Np / JT, nchunk = (nslab + uchunk - 1) / uchunk;
   int img, tile;
   if (!group_on_xcd(blockIdx.x, nchunk * P, nimg, &img, &tile)) return;
   const int b = img0 + img;
@@ -606,7 +606,7 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   const int J = tile % P, chunk = tile / P;
-  const int slab0 = chunk * U_CHUNK, slab1 = min(nslab, slab0 + U_CHUNK);
+  const int slab0 = chunk * uchunk, slab1 = min(nslab, slab0 + uchunk);
   float* M = U + (size_t)b * Np * Np;
   int colbase[2];
   round_robin_pair(nblk, step, J, &colbase[0], &colbase[1]);
@@ -709,7 +709,8 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
   const dim3 gs(P, nimg);
-  const int gg = grid_for_groups((P * (P + 1) / 2 + G_CHUNK - 1) / G_CHUNK, nimg), gu = grid_for_groups(((Np / JT + U_CHUNK - 1) / U_CHUNK) * P, nimg);
+  const int gg = grid_for_groups((P * (P + 1) / 2 + G_CHUNK - 1) / G_CHUNK, nimg), uchunk = (Np / JT) * P * nimg >= 512 ? 3 : 1,
+            gu = grid_for_groups(((Np / JT + uchunk - 1) / uchunk) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
       // After the first sweep the diagonal blocks are nearly diagonal: most visits only rotate index
@@ -721,7 +722,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
       else
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JB)));
       TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg)));
-      if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg)));
+      if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg, uchunk)));
     }
     TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<nimg, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, img0, nimg)));
   }
