@@ -127,3 +127,74 @@ def test_kv_cache_share_reproduces_the_papers_table():
     # a plausible mistake (compressing the first layers too) misses the table by many points
     assert abs(100.0 * orc.kv_cache_fraction(80, 576, 64, 32, 0) - table[64]) > 4.0
     assert orc.kv_cache_fraction(80, 576, 576, 32, 2) == 1.0
+
+
+# ---------------------------------------------------------------------------------------------
+# planted mistakes: each plausible wrong version of these functions must fail at least one pin
+# ---------------------------------------------------------------------------------------------
+def _pins():
+    return [test_rank_of_an_exactly_low_rank_matrix, test_rank_matches_gaussian_elimination_on_small_matrices,
+            test_rank_threshold_separates_planted_signal_from_noise, test_rank_of_kept_rows_and_invariances,
+            test_rank_curve_is_monotone_and_normalised, test_assembled_sequence_keeps_text_rows_and_original_positions,
+            test_rotary_tables_closed_forms_and_relative_position_property, test_kv_cache_share_reproduces_the_papers_table]
+
+
+def _caught(monkeypatch, name, mutant):
+    monkeypatch.setattr(orc, name, mutant)
+    failed = 0
+    for pin in _pins():
+        try:
+            pin()
+        except AssertionError:
+            failed += 1
+    return failed
+
+
+def test_planted_mistakes_in_rank_sequence_and_cache_functions_are_caught(monkeypatch):
+    real_rank, real_asm, real_rope, real_kv = orc.info_rank, orc.assemble_sequence, orc.rope_tables, orc.kv_cache_fraction
+
+    def rank_absolute_threshold(O, rows=None, rtol=None):            # threshold not relative to sigma_max
+        r, s = real_rank(O, rows, rtol)
+        t = rtol if rtol is not None else 1e-7
+        return int((s > t).sum()), s
+
+    def rank_ignores_rows(O, rows=None, rtol=None):                  # always the whole matrix
+        return real_rank(O, None, rtol)
+
+    def rank_counts_squared(O, rows=None, rtol=None):                # eigenvalues of the Gram matrix compared instead of sigma
+        r, s = real_rank(O, rows, rtol)
+        t = rtol if rtol is not None else 1e-7
+        return (int((s ** 2 > t * s[0] ** 2).sum()) if s.size and s[0] > 0 else 0), s
+
+    def asm_compacted_positions(H, X_out, kept_idx, n_sys, n_vis):   # positions renumbered 0..L'-1
+        Hn, pos = real_asm(H, X_out, kept_idx, n_sys, n_vis)
+        return Hn, np.arange(len(pos))
+
+    def asm_prompt_before_visual(H, X_out, kept_idx, n_sys, n_vis):
+        Hn, pos = real_asm(H, X_out, kept_idx, n_sys, n_vis)
+        k = len(kept_idx)
+        return np.concatenate([Hn[:n_sys], Hn[n_sys + k:], Hn[n_sys:n_sys + k]]), pos
+
+    def rope_wrong_exponent(pos_ids, head_dim, base=10000.0):        # theta_i = base^(-i/d) instead of base^(-2i/d)
+        i = np.arange(head_dim // 2, dtype=np.float64)
+        ang = np.asarray(pos_ids, dtype=np.float64)[:, None] * (base ** (-i / head_dim))[None, :]
+        return np.cos(ang), np.sin(ang)
+
+    def rope_swapped(pos_ids, head_dim, base=10000.0):
+        c, s = real_rope(pos_ids, head_dim, base)
+        return s, c
+
+    def kv_all_layers_short(n_text, n_vis, n_kept, n_layers, n_layers_before):
+        return real_kv(n_text, n_vis, n_kept, n_layers, 0)
+
+    def kv_visual_only(n_text, n_vis, n_kept, n_layers, n_layers_before):   # text tokens forgotten
+        return real_kv(0, n_vis, n_kept, n_layers, n_layers_before)
+
+    for name, mutant in [("info_rank", rank_absolute_threshold), ("info_rank", rank_ignores_rows),
+                         ("info_rank", rank_counts_squared), ("assemble_sequence", asm_compacted_positions),
+                         ("assemble_sequence", asm_prompt_before_visual), ("rope_tables", rope_wrong_exponent),
+                         ("rope_tables", rope_swapped), ("kv_cache_fraction", kv_all_layers_short),
+                         ("kv_cache_fraction", kv_visual_only)]:
+        assert _caught(monkeypatch, name, mutant) >= 1, "mutant %s survives every pin" % mutant.__name__
+        monkeypatch.undo()
+    assert _caught(monkeypatch, "info_rank", real_rank) == 0         # and the real functions pass them all
