@@ -6,8 +6,9 @@
 // in LDS (jacobi_solve), giving an orthogonal 64x64 matrix R.  Then every 64x64 tile of G that the
 // step's pairs (I,J) span is replaced by R_I^T G_IJ R_J and the eigenvector columns by U_J R_J
 // (jacobi_update), both as small matrix products on the matrix cores.  nblk-1 steps make a sweep;
-// sweeps repeat until the off-diagonal mass measured during a sweep is below the tolerance, per
-// image, with the iteration count fixed on the host and converged images skipped on the device.
+// sweeps repeat until the off-diagonal mass of G, measured after every sweep, is below the
+// tolerance, per image, with the iteration count fixed on the host and converged images skipped on
+// the device.
 // After the Gram kernel has filled G in full, only its blocks on and above the block diagonal are
 // maintained.
 // On exit diag(G) holds the eigenvalues sigma_i^2 and U the left singular vectors of O
@@ -173,7 +174,8 @@ constexpr int SOLVE_THREADS = 64 * (SOLVE_WAVES + 1);   // plus the rotation wav
 // Declared bound of the kernel.  With a bound of 9 wavefronts the compiler derives "at most 7
 // wavefronts per SIMD" from the wave slots and pads the register allocation to 65 (72 allocated),
 // after which only two workgroups fit a compute unit; a bound of 10 leaves the allocation alone and
-// three fit as long as the kernel needs no more than 64 registers.
+// three fit as long as the kernel needs no more than 64 registers (which waves_per_eu(8) on the
+// kernel makes the register allocator's budget).
 constexpr int SOLVE_BOUND = 64 * (SOLVE_WAVES + 2);
 constexpr int SEATS = JB / SOLVE_WAVES;                 // seats per wavefront
 constexpr int N_BLOCKS = JB * (JB + 1) / 2;             // stored blocks, diagonal ones included
@@ -220,8 +222,7 @@ __device__ inline int slot_of(int a, int b) {
 }
 
 template <typename T, bool CROSS>
-__global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
-                                                            double* __restrict__ offpart,
+__global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 8))) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
                                                             const EigState* __restrict__ state, int Np, int nblk,
                                                             int step, int img0, int inner_steps) {
   const int b = img0 + blockIdx.y, pair = blockIdx.x, P = nblk / 2;
@@ -232,7 +233,6 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
   __shared__ __attribute__((aligned(16))) T SB[(2 * BUF > STAGE ? 2 * BUF : STAGE)];
   __shared__ T xch[2][XCOPIES][SOLVE_WAVES][JT];  // columns of R handed to the neighbouring wavefront: [parity][top/bottom]
   __shared__ Pair2<T> rcs[2][JB];                  // (c, z) of every seat, [parity]
-  __shared__ double red[SOLVE_WAVES + 1];
   int p, q;
   round_robin_pair(nblk, step, pair, &p, &q);
   const T* Gb = G + (size_t)b * Np * Np;
@@ -251,9 +251,6 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
     if (r >= JB && c < JB) { const int t = r; r = c; c = t; }
     const int gr = (r < JB ? p * JB + r : q * JB + r - JB), gc = (c < JB ? p * JB + c : q * JB + c - JB);
     return Gb[(size_t)gr * Np + gc];
-  };
-  auto weight = [&](int r, int c) {  // share of v^2 in the off-diagonal mass of this visit
-    return ((r < JB) == (c < JB)) ? 2.0 / (double)(nblk - 1) : 2.0;  // inside G_pp, G_qq: seen nblk-1 times per sweep
   };
   // the off-diagonal block of S this lane owns (wavefronts 0..7): row I of the strict upper triangle holds JB-1-I blocks
   const bool act = !rwave && tid < N_OFFDIAG;
@@ -280,7 +277,6 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
   const int rdx = 2 * block_id(Sx, Sx), rdy = 2 * block_id(Sy, Sy);
   const int rdxy = 2 * (swp ? block_id(Sy, Sx) : block_id(Sx, Sy));
 
-  double off = 0.0;
   T d_tt = T(0), d_tb = T(0), d_bb = T(0);
   if (act) {
     const int iTI = top0(sI), iBI = bot0(sI), iTJ = top0(sJ), iBJ = bot0(sJ);
@@ -288,19 +284,14 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
     if (done) return;  // uniform over the workgroup
     *reinterpret_cast<Pair2<T>*>(&SB[rd]) = Pair2<T>{ett, etb};
     *reinterpret_cast<Pair2<T>*>(&SB[2 * N_BLOCKS + rd]) = Pair2<T>{ebt, ebb};
-    off = weight(iTI, iTJ) * (double)ett * (double)ett + weight(iTI, iBJ) * (double)etb * (double)etb +
-          weight(iBI, iTJ) * (double)ebt * (double)ebt + weight(iBI, iBJ) * (double)ebb * (double)ebb;
   } else if (rwave && lane < JB) {  // the diagonal block of the seat
     d_tt = gload(rt, rt); d_tb = gload(rt, rb); d_bb = gload(rb, rb);
     if (done) return;
     *reinterpret_cast<Pair2<T>*>(&SB[rd]) = Pair2<T>{d_tt, d_tb};
     SB[2 * N_BLOCKS + rd + 1] = d_bb;
-    off = weight(rt, rb) * (double)d_tb * (double)d_tb;
   } else if (done) {
     return;
   }
-  off = wave_sum(off);
-  if (lane == 0) red[wave] = off;
   T rtop[SEATS], rbot[SEATS];  // columns of R in seat order (wavefronts 0..7), R = I at the start
 #pragma unroll
   for (int k = 0; k < SEATS; k++) {
@@ -320,11 +311,6 @@ __global__ __launch_bounds__(SOLVE_BOUND) void jacobi_solve(const T* __restrict_
   };
   if (rwave && lane < JB && inner_steps > 0) store_rotation(0, d_tt, d_tb, d_bb);  // rotations of step 0
   __syncthreads();
-  if (tid == 0) {
-    double tot = 0.0;
-    for (int w = 0; w < SOLVE_WAVES + 1; w++) tot += red[w];
-    offpart[((size_t)b * (nblk - 1) + step) * P + pair] = tot;
-  }
 
   for (int st = 0; st < inner_steps; st++) {  // a whole sweep brings the seats back to their starting order
     const int par = st & 1, cur = par * BUF, nxt = BUF - cur;
@@ -662,15 +648,40 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
 }
 
 // ---------------------------------------------------------------------------------------
+// Off-diagonal mass of G after a sweep, from the blocks that are maintained: block row i of image b
+// gives  sum_{c != r, same block} G_rc^2 + 2 sum_{blocks j > i} G_rc^2  (the blocks below the block
+// diagonal mirror those above).  One workgroup per (block row, image); every thread adds its
+// elements in a fixed order and the partial sums are combined in a fixed order, so the stopping
+// decision is reproducible.
+template <typename T>
+__global__ __launch_bounds__(256) void jacobi_offnorm(const T* __restrict__ G, const EigState* __restrict__ state,
+                                                      double* __restrict__ offpart, int Np, int nblk, int img0) {
+  const int i = blockIdx.x, b = img0 + blockIdx.y, tid = threadIdx.x;
+  if (state[b].done) return;
+  __shared__ double red[4];
+  const T* Gb = G + (size_t)b * Np * Np;
+  const int c0 = i * JB, width = Np - c0;
+  double s = 0.0;
+  for (int e = tid; e < JB * width; e += 256) {
+    const int r = e / width, c = e % width;  // consecutive threads read consecutive columns of one row
+    const double v = (double)Gb[(size_t)(c0 + r) * Np + c0 + c];
+    s += (c >= JB ? 2.0 : (c == r ? 0.0 : 1.0)) * v * v;
+  }
+  s = wave_sum(s);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) offpart[(size_t)b * nblk + i] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// One wavefront per image: add the block-row partials, count the sweep, decide.
 __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* __restrict__ state, int count,
-                                 double tol, int img0, int nimg) {
-  const int b = img0 + blockIdx.x, lane = threadIdx.x;  // one wavefront per image
-  (void)nimg;
+                                 double tol, int img0) {
+  const int b = img0 + blockIdx.x, lane = threadIdx.x;
   if (state[b].done) return;
   const double* op = offpart + (size_t)b * count;
   double s = 0.0;
   for (int i = lane; i < count; i += 64) s += op[i];
-  s = wave_sum(s);  // fixed association: the decision is reproducible
+  s = wave_sum(s);
   if (lane == 0) {
     state[b].sweeps += 1;
     if (s <= tol * tol * state[b].norm2) state[b].done = 1;
@@ -718,13 +729,14 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
       // keeps the entries inside the diagonal blocks converging (cross-only sweeps stall).
       // (float32 solver: always full sweeps; its rounding noise inside the diagonal blocks needs them)
       if (sweep == 0 || step % FULL_EVERY == 0 || sizeof(T) == 4)
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JT - 1)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JT - 1)));
       else
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, offpart, state, Np, nblk, step, img0, JB)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JB)));
       TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg)));
       if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg, uchunk)));
     }
-    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<nimg, 64, 0, st>>>(offpart, state, P * pl.steps, pl.tol, img0, nimg)));
+    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_offnorm<T><<<dim3(nblk, nimg), 256, 0, st>>>(G, state, offpart, Np, nblk, img0)));
+    TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_sweep_end<<<nimg, 64, 0, st>>>(offpart, state, nblk, pl.tol, img0)));
   }
 }
 
