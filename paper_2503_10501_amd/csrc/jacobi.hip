@@ -424,7 +424,7 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
 // columns of pair J is gathered (a quadrant whose block lies below the diagonal is read from its
 // mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and is scattered back to
 // the stored blocks.  The mirror tile (J,I) is never formed.
-constexpr int FULL_EVERY = 6;  // after the first sweep, one solve in FULL_EVERY is a full 63-step sweep
+constexpr int FULL_EVERY = 6;  // one solve in FULL_EVERY is a full 63-step sweep of its subproblem
 constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup
 
 // Tile index t (row-major over the upper triangle of pair pairs, row I holds P - I tiles) -> (I, J).
@@ -724,11 +724,12 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
             gu = grid_for_groups(((Np / JT + uchunk - 1) / uchunk) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
-      // After the first sweep the diagonal blocks are nearly diagonal: most visits only rotate index
-      // pairs across the two blocks (32 steps instead of 63); a full sweep every FULL_EVERY-th step
-      // keeps the entries inside the diagonal blocks converging (cross-only sweeps stall).
+      // Step 0 of a sweep visits every block, and its full 63-step solve leaves the diagonal blocks
+      // nearly diagonal: most later visits only rotate index pairs across the two blocks (32 steps
+      // instead of 63); a full solve every FULL_EVERY-th step keeps the entries inside the diagonal
+      // blocks converging (cross-only sweeps stall).
       // (float32 solver: always full sweeps; its rounding noise inside the diagonal blocks needs them)
-      if (sweep == 0 || step % FULL_EVERY == 0 || sizeof(T) == 4)
+      if (step % FULL_EVERY == 0 || sizeof(T) == 4)
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JT - 1)));
       else
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JB)));
