@@ -31,6 +31,15 @@ template <> struct Elem16<true> {
   __device__ static inline uint16_t bits(float f) { return float_to_f16_bits(f); }
 };
 
+typedef __attribute__((ext_vector_type(2))) unsigned int u2v;
+
+// v of the lane that a data-parallel permutation control pairs this lane with (0x140: 15-L within a
+// row of 16 lanes, 0x141: 7-L within 8, 0x4E: L^2, 0xB1: L^1).  All lanes of the wavefront must be active.
+template <int CTRL>
+__device__ inline float lane_perm(float v) {
+  return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), CTRL, 0xf, 0xf, false));
+}
+
 constexpr int AQ = 128;  // queries per workgroup
 constexpr int AK = 64;   // keys per LDS tile
 
@@ -76,14 +85,17 @@ template <int DH>
 __device__ inline void store_v_tile_transposed(uint16_t* Vt, const uint4* regs) {
   constexpr int ITER = DH / 32, VLD = AttnSmem<DH>::VLD;
   const int key = threadIdx.x & 63;
+  // Within a row the keys are stored with bits 2 and 3 swapped: the eight keys that one lane feeds
+  // to a matrix-core product (16u + 4*half + {0..3} and those plus 8) are then 16 contiguous bytes.
+  const int pos = (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1);
 #pragma unroll
   for (int it = 0; it < ITER; it++) {
     const int ch = (threadIdx.x >> 6) + 4 * it;
     const uint32_t w[4] = {regs[it].x, regs[it].y, regs[it].z, regs[it].w};
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-      Vt[(ch * 8 + 2 * i) * VLD + key] = (uint16_t)(w[i] & 0xffffu);
-      Vt[(ch * 8 + 2 * i + 1) * VLD + key] = (uint16_t)(w[i] >> 16);
+      Vt[(ch * 8 + 2 * i) * VLD + pos] = (uint16_t)(w[i] & 0xffffu);
+      Vt[(ch * 8 + 2 * i + 1) * VLD + pos] = (uint16_t)(w[i] >> 16);
     }
   }
 }
@@ -141,14 +153,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
     qf[ks] = *reinterpret_cast<const vec8*>(Qh + (size_t)p * DH + 16 * ks + 8 * half);
 
   // ---------------- pass 1: row maximum and normaliser (log2 domain) ----------------
+  // (both passes fetch the next key tile into registers while the matrix cores work on this one)
   float m_run = -INFINITY, l_run = 0.f;
+  uint4 kr[AK * (DH / 8) / 256], vr[DH / 32];
+  load_k_tile<DH>(Kh, 0, L, kr);
   for (int t = 0; t < n_tiles; t++) {
     const int k0 = t * AK;
-    uint4 kr[AK * (DH / 8) / 256];
-    load_k_tile<DH>(Kh, k0, L, kr);
     __syncthreads();
     store_k_tile<DH>(Ks, kr);
     __syncthreads();
+    load_k_tile<DH>(Kh, t + 1 < n_tiles ? k0 + AK : 0, L, kr);  // after the last tile: tile 0 for pass 2
 #pragma unroll
     for (int sub = 0; sub < 2; sub++) {
       const f16v acc = score_subtile<DH, F16>(Ks, sub, qf, lane);
@@ -184,15 +198,17 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
 #pragma unroll
     for (int i = 0; i < 16; i++) oacc[mt][i] = 0.f;
   float* sp_row = Spart + (((size_t)b * H + h) * n_qtiles + qt) * N;
+  load_v_tile<DH>(Vh, 0, L, vr);
   for (int t = 0; t < n_tiles; t++) {
     const int k0 = t * AK;
-    uint4 kr[AK * (DH / 8) / 256], vr[DH / 32];
-    load_k_tile<DH>(Kh, k0, L, kr);
-    load_v_tile<DH>(Vh, k0, L, vr);
     __syncthreads();
     store_k_tile<DH>(Ks, kr);
     store_v_tile_transposed<DH>(Vt, vr);
     __syncthreads();
+    if (t + 1 < n_tiles) {
+      load_k_tile<DH>(Kh, k0 + AK, L, kr);
+      load_v_tile<DH>(Vh, k0 + AK, L, vr);
+    }
     // one 32-key sub-tile at a time keeps the live register set small (two wavefronts per SIMD)
 #pragma unroll
     for (int sub = 0; sub < 2; sub++) {
@@ -220,28 +236,37 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
         }
 #pragma unroll
         for (int mt = 0; mt < DH / 32; mt++) {
-          const uint16_t* vrow = Vt + (32 * mt + (lane & 31)) * SM::VLD + sub * 32 + 16 * u + 4 * half;
-          const uint2 lo = *reinterpret_cast<const uint2*>(vrow);
-          const uint2 hi = *reinterpret_cast<const uint2*>(vrow + 8);
-          union { uint4 u4; vec8 v; } va;
-          va.u4 = uint4{lo.x, lo.y, hi.x, hi.y};
+          union { uint4 u4; vec8 v; } va;  // V^T row 32 mt + lane%32, the lane's eight keys (stored side by side)
+          va.u4 = *reinterpret_cast<const uint4*>(Vt + (32 * mt + (lane & 31)) * SM::VLD + sub * 32 + 16 * u + 8 * half);
           oacc[mt] = Elem16<F16>::mma(va.v, pb, oacc[mt]);
           oacc[mt] = Elem16<F16>::mma(va.v, pl, oacc[mt]);
         }
       }
-      // column sums over this wavefront's 32 queries: recursive halving across the 32 lanes of each
-      // half (16 values -> 1 value per lane pair), then the two lanes of a pair are added
+      // column sums over this wavefront's 32 queries (the 32 lanes of each half): recursive halving,
+      // 16 values -> 1 value per lane pair.  First the two 16-lane rows of a half trade eight values
+      // with the row-swap instruction (after it, one register holds a value's two row parts in the even
+      // row and the other the partner value's in the odd row), then lanes L and 15-L, L and 7-L,
+      // L and L^2 trade through data-parallel lane permutations, and the two lanes of a pair are added.
 #pragma unroll
-      for (int o = 16, n = 16; o >= 2; o >>= 1, n >>= 1) {
-        const bool up = (lane & o) != 0;
-#pragma unroll
-        for (int i = 0; i < n / 2; i++) {
-          const float send = up ? pr[i] : pr[i + n / 2];
-          const float keep = up ? pr[i + n / 2] : pr[i];
-          pr[i] = keep + __shfl_xor(send, o, 64);
-        }
+      for (int i = 0; i < 8; i++) {
+        const u2v sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(pr[i]), __float_as_uint(pr[i + 8]), false, false);
+        pr[i] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
       }
-      pr[0] += __shfl_xor(pr[0], 1, 64);
+      {
+        const bool up = (lane & 8) != 0;
+#pragma unroll
+        for (int i = 0; i < 4; i++) pr[i] = (up ? pr[i + 4] : pr[i]) + lane_perm<0x140>(up ? pr[i] : pr[i + 4]);  // L <-> 15-L
+      }
+      {
+        const bool up = (lane & 4) != 0;
+#pragma unroll
+        for (int i = 0; i < 2; i++) pr[i] = (up ? pr[i + 2] : pr[i]) + lane_perm<0x141>(up ? pr[i] : pr[i + 2]);  // L <-> 7-L
+      }
+      {
+        const bool up = (lane & 2) != 0;
+        pr[0] = (up ? pr[1] : pr[0]) + lane_perm<0x4E>(up ? pr[0] : pr[1]);  // L <-> L^2
+      }
+      pr[0] += lane_perm<0xB1>(pr[0]);  // L <-> L^1
       if ((lane & 1) == 0) {
         const int r = (lane >> 1) & 15;  // accumulator element whose column sum this lane pair holds
         cs[wave][sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = pr[0];
