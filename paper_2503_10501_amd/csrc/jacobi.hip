@@ -30,6 +30,7 @@ typedef __attribute__((ext_vector_type(4))) float f4;
 template <typename T> struct MM;
 template <> struct MM<double> {
   typedef d4 acc_t;
+  typedef __attribute__((ext_vector_type(2))) double pair_t;
   __device__ static inline acc_t mma(double a, double b, acc_t c) {
     return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
   }
@@ -37,6 +38,7 @@ template <> struct MM<double> {
 };
 template <> struct MM<float> {
   typedef f4 acc_t;
+  typedef __attribute__((ext_vector_type(2))) float pair_t;
   __device__ static inline acc_t mma(float a, float b, acc_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
   }
@@ -438,79 +440,93 @@ __device__ inline void decode_tile(int t, int P, int* I, int* J) {
 // A workgroup walks over G_CHUNK consecutive tiles and software-pipelines them: while the matrix
 // cores work on tile k, the gather of tile k+1 and the right factor of tile k are already in flight
 // in registers, so only the first tile of a chunk waits for memory.
+//
+// Wavefront w owns quadrant (wr, wc) = (w / 2, w % 2) of the tile: it gathers it, and it holds that
+// quadrant of both products in its accumulators, as 2 x 2 matrix-core tiles of 16 x 16.  The 16 tile
+// columns n of column tile nt are the quadrant's columns 2 n + nt, so the two column tiles of a lane
+// are neighbours in memory: right factor, tile rows in LDS, W and the stored Y all move as 16-byte
+// pairs.  The left factor stays in registers while consecutive tiles share it; the right factor
+// goes through LDS (fetched once per workgroup, and the register file has no room for both factors,
+// the next tile and the accumulators: a spilled register costs a full wait on the memory counter in
+// the middle of the tile).  Product ks contracts over k = 4 ks + lane / 16.
+constexpr int GLDP = JT + 2;  // row pitch of the tile in LDS: even (pairs stay 16-byte aligned), conflict-free reads
+
 template <typename T>
 __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
                                                        int img0, int nimg) {
   typedef typename MM<T>::acc_t acc_t;
+  typedef typename MM<T>::pair_t T2;  // two neighbouring elements, moved as one 16-byte (8-byte) access
   const int P = nblk / 2, ntiles = P * (P + 1) / 2, nchunks = (ntiles + G_CHUNK - 1) / G_CHUNK;
   int img, chunk;
   if (!group_on_xcd(blockIdx.x, nchunks, nimg, &img, &chunk)) return;
   const int b = img0 + img;
   if (state[b].done) return;
-  __shared__ T X[JT][SLD];
+  __shared__ __attribute__((aligned(16))) T X[JT][GLDP];   // the tile, then W
+  __shared__ __attribute__((aligned(16))) T RJs[JT][GLDP]; // the right factor R_J
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 1, wc = wave & 1;
+  const int wr = wave >> 1, wc = wave & 1, l15 = lane & 15, q4 = lane >> 4;
   T* M = G + (size_t)b * Np * Np;
   const T* Rimg = R + (size_t)b * P * JT * JT;
   const int t0 = chunk * G_CHUNK, t1 = min(ntiles, t0 + G_CHUNK);
-  // This thread moves, for it = 0..15, the element (r, c) = (lane/16 + 4 it, lane%16 + 16 wave) of a
-  // tile if its block is stored, else the element of the mirror block that sits at the same place of
-  // the stored block; 16 consecutive lanes always touch 16 consecutive columns in memory.
-  const int c = (lane & 15) + 16 * wave, cq = c >> 5, ci = c & 31;
-  auto gather = [&](int I, int J, T* x) {
+  // Gather of quadrant (wr, wc): for it = 0..7 the column pair 2 l15, 2 l15 + 1 of row q4 + 4 it of
+  // the stored block -- the quadrant's own block, or its mirror block when that lies below the
+  // block diagonal (then the pair is transposed on the way into LDS).
+  auto gather = [&](int I, int J, T2* x) {
     int rowblk[2], colblk[2];
     round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
     round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
+    const int br = rowblk[wr], bc = colblk[wc];
+    const T* src = (br <= bc ? M + (size_t)(br * JB) * Np + bc * JB : M + (size_t)(bc * JB) * Np + br * JB) + 2 * l15;
 #pragma unroll
-    for (int it = 0; it < 16; it++) {
-      const int r = (lane >> 4) + 4 * it, rq = r >> 5, ri = r & 31;
-      const int br = rowblk[rq], bc = colblk[cq];
-      x[it] = br <= bc ? M[(size_t)(br * JB + ri) * Np + bc * JB + ci] : M[(size_t)(bc * JB + ri) * Np + br * JB + ci];
-    }
+    for (int it = 0; it < 8; it++) x[it] = *reinterpret_cast<const T2*>(src + (size_t)(q4 + 4 * it) * Np);
   };
   auto load_left = [&](int I, T (*f)[2]) {  // R_I^T as A fragments: A[i][k] = R_I[k][i], rows wr*32 .. +32
-    const T* RI = Rimg + (size_t)I * JT * JT;
+    const T* RI = Rimg + (size_t)I * JT * JT + wr * 32 + l15;
 #pragma unroll
     for (int ks = 0; ks < 16; ks++) {
-      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
-      f[ks][0] = RI[k * JT + wr * 32 + (lane & 15)];
-      f[ks][1] = RI[k * JT + wr * 32 + 16 + (lane & 15)];
+      f[ks][0] = RI[(4 * ks + q4) * JT];
+      f[ks][1] = RI[(4 * ks + q4) * JT + 16];
     }
   };
-  auto load_right = [&](int J, T (*f)[2]) {  // R_J[:, wc*32 .. +32) as B fragments
-    const T* RJ = Rimg + (size_t)J * JT * JT;
+  // R_J on its way to LDS: thread moves, for it = 0..7, the column pair 2 (tid % 32) of row tid / 32 + 8 it
+  auto fetch_right = [&](int J, T2* x) {
+    const T* RJ = Rimg + (size_t)J * JT * JT + (tid >> 5) * JT + 2 * (tid & 31);
 #pragma unroll
-    for (int ks = 0; ks < 16; ks++) {
-      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
-      f[ks][0] = RJ[k * JT + wc * 32 + (lane & 15)];
-      f[ks][1] = RJ[k * JT + wc * 32 + 16 + (lane & 15)];
-    }
+    for (int it = 0; it < 8; it++) x[it] = *reinterpret_cast<const T2*>(RJ + 8 * it * JT);
   };
   int I, J;
   decode_tile(t0, P, &I, &J);
-  T left[16][2], right[16][2], xpre[16];
+  T left[16][2];
+  T2 xpre[8], rpre[8];
   load_left(I, left);
   gather(I, J, xpre);
+  fetch_right(J, rpre);
   for (int t = t0; t < t1; t++) {
     int rowblk[2], colblk[2];
     round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
     round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
-    // tile into LDS (a quadrant read from its mirror block is transposed here)
+    // quadrant into LDS
+    if (rowblk[wr] <= colblk[wc]) {
 #pragma unroll
-    for (int it = 0; it < 16; it++) {
-      const int r = (lane >> 4) + 4 * it, rq = r >> 5, ri = r & 31;
-      if (rowblk[rq] <= colblk[cq]) X[r][c] = xpre[it];
-      else X[rq * JB + ci][cq * JB + ri] = xpre[it];
+      for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&X[wr * JB + q4 + 4 * it][wc * JB + 2 * l15]) = xpre[it];
+    } else {
+#pragma unroll
+      for (int it = 0; it < 8; it++) {
+        X[wr * JB + 2 * l15][wc * JB + q4 + 4 * it] = xpre[it].x;
+        X[wr * JB + 2 * l15 + 1][wc * JB + q4 + 4 * it] = xpre[it].y;
+      }
     }
+#pragma unroll
+    for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&RJs[(tid >> 5) + 8 * it][2 * (tid & 31)]) = rpre[it];
     __syncthreads();
-    // memory traffic for later: right factor of this tile, gather of the next one
-    load_right(J, right);
+    // memory traffic for later: the next tile and its right factor
     int In = I, Jn = J;
     const bool more = t + 1 < t1;
     if (more) {
       decode_tile(t + 1, P, &In, &Jn);
       gather(In, Jn, xpre);
+      fetch_right(Jn, rpre);
     }
     acc_t acc[2][2];
 #pragma unroll
@@ -520,22 +536,19 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
     // W = R_I^T X
 #pragma unroll
     for (int ks = 0; ks < 16; ks++) {
-      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
-      const T b0 = X[k][wc * 32 + (lane & 15)], b1 = X[k][wc * 32 + 16 + (lane & 15)];
-      acc[0][0] = MM<T>::mma(left[ks][0], b0, acc[0][0]);
-      acc[0][1] = MM<T>::mma(left[ks][0], b1, acc[0][1]);
-      acc[1][0] = MM<T>::mma(left[ks][1], b0, acc[1][0]);
-      acc[1][1] = MM<T>::mma(left[ks][1], b1, acc[1][1]);
+      const T2 bb = *reinterpret_cast<const T2*>(&X[4 * ks + q4][wc * 32 + 2 * l15]);
+      acc[0][0] = MM<T>::mma(left[ks][0], bb.x, acc[0][0]);
+      acc[0][1] = MM<T>::mma(left[ks][0], bb.y, acc[0][1]);
+      acc[1][0] = MM<T>::mma(left[ks][1], bb.x, acc[1][0]);
+      acc[1][1] = MM<T>::mma(left[ks][1], bb.y, acc[1][1]);
     }
     if (more && In != I) load_left(In, left);  // next tile starts a new row of tiles
     __syncthreads();  // every wave has finished reading X
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-      for (int nt = 0; nt < 2; nt++)
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-          X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + nt * 16 + (lane & 15)] = acc[mt][nt][j];
+      for (int j = 0; j < 4; j++)
+        *reinterpret_cast<T2*>(&X[wr * 32 + mt * 16 + MM<T>::row(j, lane)][wc * 32 + 2 * l15]) = T2{acc[mt][0][j], acc[mt][1][j]};
     __syncthreads();
     // Y = W R_J
 #pragma unroll
@@ -544,28 +557,34 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
       for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < 16; ks++) {
-      const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
-      const T a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
-      acc[0][0] = MM<T>::mma(a0, right[ks][0], acc[0][0]);
-      acc[0][1] = MM<T>::mma(a0, right[ks][1], acc[0][1]);
-      acc[1][0] = MM<T>::mma(a1, right[ks][0], acc[1][0]);
-      acc[1][1] = MM<T>::mma(a1, right[ks][1], acc[1][1]);
+      const T a0 = X[wr * 32 + l15][4 * ks + q4], a1 = X[wr * 32 + 16 + l15][4 * ks + q4];
+      const T2 bb = *reinterpret_cast<const T2*>(&RJs[4 * ks + q4][wc * 32 + 2 * l15]);
+      acc[0][0] = MM<T>::mma(a0, bb.x, acc[0][0]);
+      acc[0][1] = MM<T>::mma(a0, bb.y, acc[0][1]);
+      acc[1][0] = MM<T>::mma(a1, bb.x, acc[1][0]);
+      acc[1][1] = MM<T>::mma(a1, bb.y, acc[1][1]);
     }
-    // Each wavefront holds one quadrant of Y (rows of block rowblk[wr], columns of block colblk[wc])
-    // in its accumulators and stores it straight from registers: as it is when the block is stored,
-    // else transposed into the mirror block (32-byte pieces that the L2 merges into full lines).
+    // The quadrant of Y goes from the accumulators to its block (rows of block rowblk[wr], columns
+    // of block colblk[wc]): as 16-byte column pairs when the block is stored, else transposed into
+    // the mirror block (32-byte pieces that the L2 merges into full lines).
     const int br = rowblk[wr], bc = colblk[wc];
     if (!(I == J && wr == 1 && wc == 0)) {  // (1,0) of a diagonal tile mirrors its quadrant (0,1)
+      if (br <= bc) {
+        T* dst = M + (size_t)(br * JB) * Np + bc * JB + 2 * l15;
 #pragma unroll
-      for (int mt = 0; mt < 2; mt++)
+        for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-        for (int nt = 0; nt < 2; nt++)
+          for (int j = 0; j < 4; j++)
+            *reinterpret_cast<T2*>(dst + (size_t)(mt * 16 + MM<T>::row(j, lane)) * Np) = T2{acc[mt][0][j], acc[mt][1][j]};
+      } else {
+        T* dst = M + (size_t)(bc * JB + 2 * l15) * Np + br * JB;
 #pragma unroll
-          for (int j = 0; j < 4; j++) {
-            const int r = mt * 16 + MM<T>::row(j, lane), cc = nt * 16 + (lane & 15);  // inside the quadrant
-            if (br <= bc) M[(size_t)(br * JB + r) * Np + bc * JB + cc] = acc[mt][nt][j];
-            else M[(size_t)(bc * JB + cc) * Np + br * JB + r] = acc[mt][nt][j];
-          }
+        for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+          for (int nt = 0; nt < 2; nt++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) dst[(size_t)nt * Np + mt * 16 + MM<T>::row(j, lane)] = acc[mt][nt][j];
+      }
     }
     __syncthreads();  // W fully consumed before the next tile overwrites it
     I = In; J = Jn;
