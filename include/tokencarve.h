@@ -84,7 +84,7 @@ typedef struct {
   int32_t jacobi_max_sweeps; /* 0 => 30                                                         */
   float jacobi_tol;     /* an image stops after the first sweep that leaves off(G)/||G||_F < tol
                            (off = Frobenius norm of the off-diagonal part);
-                           0 => 1e-9 (3e-6 for TC_EIG_F32)                                      */
+                           0 => 2e-9 (3e-6 for TC_EIG_F32)                                      */
   int32_t eig_dtype;    /* tc_eig_dtype                                                         */
   int32_t stream_groups; /* eigensolver: 0 = cut the batch into up to 4 groups that run on helper
                             streams and overlap; 1 = everything on `stream`; 2..4 = that many groups */

@@ -34,7 +34,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.tsize = p->eig_dtype == TC_EIG_F64 ? 8 : 4;
   q.groups = p->stream_groups;
   q.max_sweeps = p->jacobi_max_sweeps > 0 ? p->jacobi_max_sweeps : 30;
-  q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 1e-9 : 3e-6);
+  q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 2e-9 : 3e-6);
   q.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)q.dh);
 
   size_t off = 0;

@@ -24,9 +24,10 @@ typedef __attribute__((ext_vector_type(4))) float f4;
 
 // 16x16x4 matrix-core product for both element types.  A: lane holds A[lane%16][lane/16];
 // B: lane holds B[lane/16][lane%16]; accumulator element j of a lane is C[row(j)][lane%16].
-// Which four of the 64 contraction indices one product covers is free as long as A and B agree; the
-// update kernels give product ks the indices ks, ks+16, ks+32, ks+48 so that the four LDS rows a
-// wavefront reads at once fall into different banks with the 65-element row pitch.
+// Which four of the 64 contraction indices one product covers is free as long as A and B agree: the
+// eigenvector update gives product ks the indices ks, ks+16, ks+32, ks+48 (the four LDS rows a
+// wavefront reads at once fall into different banks with its 65-element row pitch), the tile update
+// of G the indices 4 ks .. 4 ks + 3 (conflict-free with its 66-element pitch).
 template <typename T> struct MM;
 template <> struct MM<double> {
   typedef d4 acc_t;
@@ -534,13 +535,18 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
 #pragma unroll
       for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
     // W = R_I^T X
+    {  // the operand of product ks + 1 is read from LDS while product ks runs
+      T2 bb = *reinterpret_cast<const T2*>(&X[q4][wc * 32 + 2 * l15]);
 #pragma unroll
-    for (int ks = 0; ks < 16; ks++) {
-      const T2 bb = *reinterpret_cast<const T2*>(&X[4 * ks + q4][wc * 32 + 2 * l15]);
-      acc[0][0] = MM<T>::mma(left[ks][0], bb.x, acc[0][0]);
-      acc[0][1] = MM<T>::mma(left[ks][0], bb.y, acc[0][1]);
-      acc[1][0] = MM<T>::mma(left[ks][1], bb.x, acc[1][0]);
-      acc[1][1] = MM<T>::mma(left[ks][1], bb.y, acc[1][1]);
+      for (int ks = 0; ks < 16; ks++) {
+        const T2 cb = bb;
+        if (ks + 1 < 16) bb = *reinterpret_cast<const T2*>(&X[4 * (ks + 1) + q4][wc * 32 + 2 * l15]);
+        __builtin_amdgcn_sched_barrier(0);  // keep the read ahead of the products (the scheduler would sink it)
+        acc[0][0] = MM<T>::mma(left[ks][0], cb.x, acc[0][0]);
+        acc[0][1] = MM<T>::mma(left[ks][0], cb.y, acc[0][1]);
+        acc[1][0] = MM<T>::mma(left[ks][1], cb.x, acc[1][0]);
+        acc[1][1] = MM<T>::mma(left[ks][1], cb.y, acc[1][1]);
+      }
     }
     if (more && In != I) load_left(In, left);  // next tile starts a new row of tiles
     __syncthreads();  // every wave has finished reading X
@@ -555,14 +561,24 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
     for (int i = 0; i < 2; i++)
 #pragma unroll
       for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
+    {  // operands of product ks + 1 are read from LDS while product ks runs
+      T a0 = X[wr * 32 + l15][q4], a1 = X[wr * 32 + 16 + l15][q4];
+      T2 bb = *reinterpret_cast<const T2*>(&RJs[q4][wc * 32 + 2 * l15]);
 #pragma unroll
-    for (int ks = 0; ks < 16; ks++) {
-      const T a0 = X[wr * 32 + l15][4 * ks + q4], a1 = X[wr * 32 + 16 + l15][4 * ks + q4];
-      const T2 bb = *reinterpret_cast<const T2*>(&RJs[4 * ks + q4][wc * 32 + 2 * l15]);
-      acc[0][0] = MM<T>::mma(a0, bb.x, acc[0][0]);
-      acc[0][1] = MM<T>::mma(a0, bb.y, acc[0][1]);
-      acc[1][0] = MM<T>::mma(a1, bb.x, acc[1][0]);
-      acc[1][1] = MM<T>::mma(a1, bb.y, acc[1][1]);
+      for (int ks = 0; ks < 16; ks++) {
+        const T c0 = a0, c1 = a1;
+        const T2 cb = bb;
+        if (ks + 1 < 16) {
+          a0 = X[wr * 32 + l15][4 * (ks + 1) + q4];
+          a1 = X[wr * 32 + 16 + l15][4 * (ks + 1) + q4];
+          bb = *reinterpret_cast<const T2*>(&RJs[4 * (ks + 1) + q4][wc * 32 + 2 * l15]);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the products (the scheduler would sink them)
+        acc[0][0] = MM<T>::mma(c0, cb.x, acc[0][0]);
+        acc[0][1] = MM<T>::mma(c0, cb.y, acc[0][1]);
+        acc[1][0] = MM<T>::mma(c1, cb.x, acc[1][0]);
+        acc[1][1] = MM<T>::mma(c1, cb.y, acc[1][1]);
+      }
     }
     // The quadrant of Y goes from the accumulators to its block (rows of block rowblk[wr], columns
     // of block colblk[wc]): as 16-byte column pairs when the block is stored, else transposed into
