@@ -503,11 +503,16 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
   load_left(I, left);
   gather(I, J, xpre);
   fetch_right(J, rpre);
-  for (int t = t0; t < t1; t++) {
+  // The prefetched quadrant and right factor go from registers into LDS (a quadrant read from its
+  // mirror block is transposed here).  Done for the first tile before the loop and for every later
+  // tile at the end of the previous iteration, behind that tile's stores: on that path the compiler
+  // can count the eight stores issued after the prefetch loads and leave them in flight (the memory
+  // counter is in order; a wait placed at the top of the loop would have to assume the path from the
+  // prologue, with nothing behind the loads, and so wait for the stores to be acknowledged).
+  auto stage = [&](int I, int J) {
     int rowblk[2], colblk[2];
     round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
     round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
-    // quadrant into LDS
     if (rowblk[wr] <= colblk[wc]) {
 #pragma unroll
       for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&X[wr * JB + q4 + 4 * it][wc * JB + 2 * l15]) = xpre[it];
@@ -520,7 +525,13 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
     }
 #pragma unroll
     for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&RJs[(tid >> 5) + 8 * it][2 * (tid & 31)]) = rpre[it];
-    __syncthreads();
+  };
+  stage(I, J);
+  for (int t = t0; t < t1; t++) {
+    int rowblk[2], colblk[2];
+    round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
+    round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
+    __syncthreads();  // tile and right factor complete in LDS
     // memory traffic for later: the next tile and its right factor
     int In = I, Jn = J;
     const bool more = t + 1 < t1;
@@ -580,29 +591,37 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
         acc[1][1] = MM<T>::mma(c1, cb.y, acc[1][1]);
       }
     }
+    __syncthreads();  // W and R_J fully consumed
     // The quadrant of Y goes from the accumulators to its block (rows of block rowblk[wr], columns
-    // of block colblk[wc]): as 16-byte column pairs when the block is stored, else transposed into
-    // the mirror block (32-byte pieces that the L2 merges into full lines).
+    // of block colblk[wc]) as 16-byte column pairs.  A quadrant whose block is only stored as its
+    // mirror is first transposed inside the wavefront's own quarter of X (nobody else touches that
+    // quarter before the next barrier, and the LDS serves one wavefront's accesses in order).  The
+    // lower quadrant of a diagonal tile mirrors its quadrant (0,1); it is written to its own block
+    // below the block diagonal, which nobody reads.  This way every wavefront issues exactly eight
+    // stores per tile on every path: the wait for the prefetched next tile at the top of the loop
+    // can then leave them in flight (the memory counter is in order and the compiler has to assume
+    // the path with the fewest stores behind the loads).
     const int br = rowblk[wr], bc = colblk[wc];
-    if (!(I == J && wr == 1 && wc == 0)) {  // (1,0) of a diagonal tile mirrors its quadrant (0,1)
-      if (br <= bc) {
-        T* dst = M + (size_t)(br * JB) * Np + bc * JB + 2 * l15;
+    if (br <= bc || I == J) {
+      T* dst = M + (size_t)(br * JB) * Np + bc * JB + 2 * l15;
 #pragma unroll
-        for (int mt = 0; mt < 2; mt++)
+      for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-          for (int j = 0; j < 4; j++)
-            *reinterpret_cast<T2*>(dst + (size_t)(mt * 16 + MM<T>::row(j, lane)) * Np) = T2{acc[mt][0][j], acc[mt][1][j]};
-      } else {
-        T* dst = M + (size_t)(bc * JB + 2 * l15) * Np + br * JB;
+        for (int j = 0; j < 4; j++)
+          *reinterpret_cast<T2*>(dst + (size_t)(mt * 16 + MM<T>::row(j, lane)) * Np) = T2{acc[mt][0][j], acc[mt][1][j]};
+    } else {
 #pragma unroll
-        for (int mt = 0; mt < 2; mt++)
+      for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-          for (int nt = 0; nt < 2; nt++)
+        for (int nt = 0; nt < 2; nt++)
 #pragma unroll
-            for (int j = 0; j < 4; j++) dst[(size_t)nt * Np + mt * 16 + MM<T>::row(j, lane)] = acc[mt][nt][j];
-      }
+          for (int j = 0; j < 4; j++) X[wr * 32 + 2 * l15 + nt][wc * 32 + mt * 16 + MM<T>::row(j, lane)] = acc[mt][nt][j];
+      T* dst = M + (size_t)(bc * JB) * Np + br * JB + 2 * l15;
+#pragma unroll
+      for (int it = 0; it < 8; it++)
+        *reinterpret_cast<T2*>(dst + (size_t)(q4 + 4 * it) * Np) = *reinterpret_cast<const T2*>(&X[wr * 32 + q4 + 4 * it][wc * 32 + 2 * l15]);
     }
-    __syncthreads();  // W fully consumed before the next tile overwrites it
+    if (more) stage(In, Jn);
     I = In; J = Jn;
   }
 }
