@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void jacobi_init_u(float* __restrict__ U, int 
   const size_t n2 = (size_t)Np * Np;
   float* Ub = U + (size_t)blockIdx.y * n2;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += (size_t)gridDim.x * blockDim.x)
-    Ub[i] = (i / Np == i % Np) ? 1.f : 0.f;
+    Ub[i] = ((i / JB) % Np == (i / ((size_t)JB * Np)) * JB + i % JB) ? 1.f : 0.f;  // row == column in the block-column layout
 }
 
 template <typename T>
@@ -632,71 +632,70 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
 // A workgroup keeps its fragments of R_J in registers and walks over `uchunk` consecutive slabs,
 // fetching the next slab into registers while the matrix cores work on the current one (3 slabs
 // when the launch has enough workgroups to fill the chip that way, else one slab per workgroup).
+// Wavefront w owns rows 16 w .. 16 w + 15 of the slab and all 64 columns, as four matrix-core column
+// tiles whose 16 columns n are the slab's columns 4 n + nt: a lane's four results of a row are
+// neighbours in memory, and the slab moves in and out as 16-byte accesses (128-byte row pieces).
+constexpr int ULD = JT + 4;  // LDS pitch of the slab: 16-byte aligned rows, conflict-free operand reads
 
 template <typename T>
 __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
                                                        int img0, int nimg, int uchunk) {
+  typedef typename MM<T>::pair_t T2;
   const int P = nblk / 2, nslab = Np / JT, nchunk = (nslab + uchunk - 1) / uchunk;
   int img, tile;
   if (!group_on_xcd(blockIdx.x, nchunk * P, nimg, &img, &tile)) return;
   const int b = img0 + img;
   if (state[b].done) return;
-  __shared__ float X[JT][SLD];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 1, wc = wave & 1;
+  __shared__ __attribute__((aligned(16))) float X[JT][ULD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l15 = lane & 15, q4 = lane >> 4;
   const int J = tile % P, chunk = tile / P;
   const int slab0 = chunk * uchunk, slab1 = min(nslab, slab0 + uchunk);
   float* M = U + (size_t)b * Np * Np;
-  int colbase[2];
-  round_robin_pair(nblk, step, J, &colbase[0], &colbase[1]);
-  colbase[0] *= JB; colbase[1] *= JB;
+  int colblk[2];
+  round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
   const T* RJ = R + ((size_t)b * P + J) * JT * JT;
-  const int c = (lane & 15) + 16 * wave;
-  const int gc = colbase[c >> 5] + (c & 31);
-  float xpre[16];
+  // moving the slab: thread handles columns 4 (tid % 16) .. + 3 of rows tid / 16 + 16 it; U is
+  // stored by block columns (u_index), so a row of a block column is JB floats from the next
+  const int mrow = tid >> 4, mcol = 4 * (tid & 15);
+  const float* src = M + (size_t)colblk[mcol >> 5] * Np * JB + (mcol & 31);
+  f4 xpre[4];
   auto fetch = [&](int slab) {
 #pragma unroll
-    for (int it = 0; it < 16; it++) xpre[it] = M[(size_t)(slab * JT + (lane >> 4) + 4 * it) * Np + gc];
+    for (int it = 0; it < 4; it++) xpre[it] = *reinterpret_cast<const f4*>(src + (size_t)(slab * JT + mrow + 16 * it) * JB);
   };
   fetch(slab0);
-  float rf[16][2];
+  float rf[16][4];  // B fragments: product ks contracts over k = 4 ks + q4; column tile nt holds columns 4 n + nt
 #pragma unroll
   for (int ks = 0; ks < 16; ks++) {
-    const int k = ks + 16 * (lane >> 4);  // k-slot q of product ks is k = ks + 16 q: LDS rows 16 apart, no bank conflicts
-    rf[ks][0] = (float)RJ[k * JT + wc * 32 + (lane & 15)];
-    rf[ks][1] = (float)RJ[k * JT + wc * 32 + 16 + (lane & 15)];
+    const T* rp = RJ + (4 * ks + q4) * JT + 4 * l15;
+    const T2 v0 = *reinterpret_cast<const T2*>(rp), v1 = *reinterpret_cast<const T2*>(rp + 2);
+    rf[ks][0] = (float)v0.x; rf[ks][1] = (float)v0.y; rf[ks][2] = (float)v1.x; rf[ks][3] = (float)v1.y;
   }
+  float* dst = M + (size_t)colblk[(4 * l15) >> 5] * Np * JB + ((4 * l15) & 31);  // the lane's four columns of a result row
   for (int slab = slab0; slab < slab1; slab++) {
 #pragma unroll
-    for (int it = 0; it < 16; it++) X[(lane >> 4) + 4 * it][c] = xpre[it];
+    for (int it = 0; it < 4; it++) *reinterpret_cast<f4*>(&X[mrow + 16 * it][mcol]) = xpre[it];
     __syncthreads();
     if (slab + 1 < slab1) fetch(slab + 1);
-    f4 acc[2][2];
+    f4 acc[4];
 #pragma unroll
-    for (int i = 0; i < 2; i++)
+    for (int i = 0; i < 4; i++) acc[i] = f4{0, 0, 0, 0};
+    {  // the operand of product ks + 1 is read from LDS while product ks runs
+      float a = X[wave * 16 + l15][q4];
 #pragma unroll
-      for (int j = 0; j < 2; j++) acc[i][j] = f4{0, 0, 0, 0};
+      for (int ks = 0; ks < 16; ks++) {
+        const float ca = a;
+        if (ks + 1 < 16) a = X[wave * 16 + l15][4 * (ks + 1) + q4];
+        __builtin_amdgcn_sched_barrier(0);  // keep the read ahead of the products (the scheduler would sink it)
 #pragma unroll
-    for (int ks = 0; ks < 16; ks++) {
-      const int k = ks + 16 * (lane >> 4);
-      const float a0 = X[wr * 32 + (lane & 15)][k], a1 = X[wr * 32 + 16 + (lane & 15)][k];
-      acc[0][0] = MM<float>::mma(a0, rf[ks][0], acc[0][0]);
-      acc[0][1] = MM<float>::mma(a0, rf[ks][1], acc[0][1]);
-      acc[1][0] = MM<float>::mma(a1, rf[ks][0], acc[1][0]);
-      acc[1][1] = MM<float>::mma(a1, rf[ks][1], acc[1][1]);
+        for (int nt = 0; nt < 4; nt++) acc[nt] = MM<float>::mma(ca, rf[ks][nt], acc[nt]);
+      }
     }
-    const int row0 = slab * JT;
 #pragma unroll
-    for (int mt = 0; mt < 2; mt++)
-#pragma unroll
-      for (int nt = 0; nt < 2; nt++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          const int r = wr * 32 + mt * 16 + MM<float>::row(j, lane);
-          const int cc = wc * 32 + nt * 16 + (lane & 15);
-          M[(size_t)(row0 + r) * Np + colbase[cc >> 5] + (cc & 31)] = acc[mt][nt][j];
-        }
+    for (int j = 0; j < 4; j++)
+      *reinterpret_cast<f4*>(dst + (size_t)(slab * JT + wave * 16 + MM<float>::row(j, lane)) * JB) =
+          f4{acc[0][j], acc[1][j], acc[2][j], acc[3][j]};
     __syncthreads();  // every wave has finished reading X
   }
 }

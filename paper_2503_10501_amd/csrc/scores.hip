@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void sigma_kernel(const T* __restrict__ G, con
   for (int i = tid; i < N; i += 256) sigma_out[(size_t)b * N + i] = key[i];
 }
 
-// C(x) = sum_i |U[x][i]| sigma_i, one wavefront per token, float64 accumulation.
+// C(x) = sum_i |U[x][i]| sigma_i (Eq. 3-6), one wavefront per token, float64 accumulation.
 __global__ __launch_bounds__(256) void ics_kernel(const float* __restrict__ U, const double* __restrict__ sig,
                                                   float sv_rtol, float* __restrict__ C, float* __restrict__ C_out,
                                                   int N, int Np) {
@@ -59,11 +59,11 @@ __global__ __launch_bounds__(256) void ics_kernel(const float* __restrict__ U, c
   }
   const int x = blockIdx.x * 4 + wave;
   if (x >= N) return;
-  const float* Ux = U + ((size_t)b * Np + x) * Np;
+  const float* Ub = U + (size_t)b * Np * Np;  // stored by block columns
   double acc = 0.0;
   for (int i = lane; i < Np; i += 64) {
     const double s = sb[i];
-    if (s > thr) acc += fabs((double)Ux[i]) * s;
+    if (s > thr) acc += fabs((double)Ub[u_index(x, i, Np)]) * s;
   }
   acc = wave_sum(acc);
   if (lane == 0) {

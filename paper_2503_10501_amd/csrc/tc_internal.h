@@ -15,6 +15,13 @@ constexpr int JT = 2 * JB;  // a block pair spans a 64 x 64 tile
 constexpr int MAX_NVIS = 4096;
 
 __host__ __device__ inline int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// The eigenvector matrix U of an image (Np x Np, float32) is stored by block columns: the JB columns
+// of block column c / JB are kept together, row after row, so that the two block columns a step's
+// pair rotates are two contiguous streams (a 64-row slab of one is 8 KB in a row).
+__host__ __device__ inline size_t u_index(int r, int c, int Np) {
+  return ((size_t)(c / JB) * Np + r) * JB + (c % JB);
+}
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 // Per-image eigensolver state kept in the workspace.
