@@ -665,13 +665,25 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
     for (int it = 0; it < 4; it++) xpre[it] = *reinterpret_cast<const f4*>(src + (size_t)(slab * JT + mrow + 16 * it) * JB);
   };
   fetch(slab0);
+  // R_J, rounded to float32, goes through the slab buffer once per workgroup (every wavefront needs
+  // all of it): thread handles columns 4 (tid % 16) .. + 3 of rows tid / 16 + 16 it
+#pragma unroll
+  for (int it = 0; it < 4; it++) {
+    const T* rp = RJ + (mrow + 16 * it) * JT + mcol;
+    const T2 v0 = *reinterpret_cast<const T2*>(rp), v1 = *reinterpret_cast<const T2*>(rp + 2);
+    *reinterpret_cast<f4*>(&X[mrow + 16 * it][mcol]) = f4{(float)v0.x, (float)v0.y, (float)v1.x, (float)v1.y};
+  }
+  __syncthreads();
   float rf[16][4];  // B fragments: product ks contracts over k = 4 ks + q4; column tile nt holds columns 4 n + nt
 #pragma unroll
   for (int ks = 0; ks < 16; ks++) {
-    const T* rp = RJ + (4 * ks + q4) * JT + 4 * l15;
-    const T2 v0 = *reinterpret_cast<const T2*>(rp), v1 = *reinterpret_cast<const T2*>(rp + 2);
-    rf[ks][0] = (float)v0.x; rf[ks][1] = (float)v0.y; rf[ks][2] = (float)v1.x; rf[ks][3] = (float)v1.y;
+    const f4 v = *reinterpret_cast<const f4*>(&X[4 * ks + q4][4 * l15]);
+    rf[ks][0] = v[0]; rf[ks][1] = v[1]; rf[ks][2] = v[2]; rf[ks][3] = v[3];
   }
+  // The fragments are only used inside the slab loop, and the optimiser would sink these reads to
+  // the loop's entry, behind the barrier below, where other wavefronts already overwrite the buffer.
+  asm volatile("" ::: "memory");
+  __syncthreads();  // the buffer is free for the first slab
   float* dst = M + (size_t)colblk[(4 * l15) >> 5] * Np * JB + ((4 * l15) & 31);  // the lane's four columns of a result row
   for (int slab = slab0; slab < slab1; slab++) {
 #pragma unroll

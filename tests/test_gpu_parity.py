@@ -224,6 +224,41 @@ def test_results_are_bit_reproducible():
         assert torch.equal(r1[k], r2[k]), k
 
 
+@pytest.mark.parametrize("name", ["tiny", "bf16_ragged", "llava7b_b1"])
+def test_results_do_not_depend_on_what_the_workspace_held_before(name):
+    # every byte the kernels read from the workspace must have been written by the same call: a read of
+    # stale scratch (or of LDS another wavefront has already reused) shows up as a run-to-run difference
+    tc, gu, _, CONFIGS, _ = _mods()
+    from workloads import make_batch
+    w = CONFIGS[name] if name in CONFIGS else _small(name)
+    b = make_batch(w)
+    p = tc.params_for(w)
+    sd = tc.storage_dtype(p)
+    Q, K, V = (gu.dev(b[k], p) for k in ("Q", "K", "V"))
+    X = gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)
+    B, N = p.batch, p.n_vis
+    runs = []
+    for fill in ("zeros", "ones", "random", "random"):
+        ws = tc.new_workspace(p)
+        if fill == "zeros":
+            ws.zero_()
+        elif fill == "ones":
+            ws.fill_(255)
+        else:
+            ws.copy_(torch.randint(0, 256, ws.shape, dtype=torch.uint8, device="cuda"))
+        out = {"X_out": torch.empty(B, p.k_final, p.hidden_dim, dtype=sd, device="cuda"),
+               "kept": torch.empty(B, p.k_final, dtype=torch.int32, device="cuda"),
+               "dst": torch.empty(B, N, dtype=torch.int32, device="cuda"),
+               "E": torch.empty(B, N, dtype=torch.float32, device="cuda"),
+               "info": torch.empty(B, dtype=torch.int32, device="cuda")}
+        tc.tc_compress(p, Q, K, V, X, out["X_out"], out["kept"], out["dst"], ws, score=out["E"], info=out["info"])
+        torch.cuda.synchronize()
+        runs.append(out)
+    for r in runs[1:]:
+        for k in r:
+            assert torch.equal(runs[0][k], r[k]), k
+
+
 def test_inputs_are_not_modified_and_binding_rejects_bad_tensors():
     tc, gu, _, _, _ = _mods()
     from workloads import make_batch
