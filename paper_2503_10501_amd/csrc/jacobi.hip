@@ -465,18 +465,27 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
   if (state[b].done) return;
   __shared__ __attribute__((aligned(16))) T X[JT][GLDP];   // the tile, then W
   __shared__ __attribute__((aligned(16))) T RJs[JT][GLDP]; // the right factor R_J
+  __shared__ int2 pairs[MAX_NVIS / JT];                     // the two blocks of every pair of this step
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1, l15 = lane & 15, q4 = lane >> 4;
   T* M = G + (size_t)b * Np * Np;
   const T* Rimg = R + (size_t)b * P * JT * JT;
   const int t0 = chunk * G_CHUNK, t1 = min(ntiles, t0 + G_CHUNK);
+  if (tid < P) {
+    int x, y;
+    round_robin_pair(nblk, step, tid, &x, &y);
+    pairs[tid] = int2{x, y};
+  }
+  __syncthreads();
+  auto blocks_of = [&](int pr, int* blk) {  // uniform over the workgroup
+    const int2 v = pairs[pr];
+    blk[0] = __builtin_amdgcn_readfirstlane(v.x);
+    blk[1] = __builtin_amdgcn_readfirstlane(v.y);
+  };
   // Gather of quadrant (wr, wc): for it = 0..7 the column pair 2 l15, 2 l15 + 1 of row q4 + 4 it of
   // the stored block -- the quadrant's own block, or its mirror block when that lies below the
   // block diagonal (then the pair is transposed on the way into LDS).
-  auto gather = [&](int I, int J, T2* x) {
-    int rowblk[2], colblk[2];
-    round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
-    round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
+  auto gather = [&](const int* rowblk, const int* colblk, T2* x) {
     const int br = rowblk[wr], bc = colblk[wc];
     const T* src = (br <= bc ? M + (size_t)(br * JB) * Np + bc * JB : M + (size_t)(bc * JB) * Np + br * JB) + 2 * l15;
 #pragma unroll
@@ -496,12 +505,14 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
 #pragma unroll
     for (int it = 0; it < 8; it++) x[it] = *reinterpret_cast<const T2*>(RJ + 8 * it * JT);
   };
-  int I, J;
+  int I, J, rowblk[2], colblk[2];
   decode_tile(t0, P, &I, &J);
+  blocks_of(I, rowblk);
+  blocks_of(J, colblk);
   T left[16][2];
   T2 xpre[8], rpre[8];
   load_left(I, left);
-  gather(I, J, xpre);
+  gather(rowblk, colblk, xpre);
   fetch_right(J, rpre);
   // The prefetched quadrant and right factor go from registers into LDS (a quadrant read from its
   // mirror block is transposed here).  Done for the first tile before the loop and for every later
@@ -509,10 +520,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
   // can count the eight stores issued after the prefetch loads and leave them in flight (the memory
   // counter is in order; a wait placed at the top of the loop would have to assume the path from the
   // prologue, with nothing behind the loads, and so wait for the stores to be acknowledged).
-  auto stage = [&](int I, int J) {
-    int rowblk[2], colblk[2];
-    round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
-    round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
+  auto stage = [&](const int* rowblk, const int* colblk) {
     if (rowblk[wr] <= colblk[wc]) {
 #pragma unroll
       for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&X[wr * JB + q4 + 4 * it][wc * JB + 2 * l15]) = xpre[it];
@@ -526,18 +534,20 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
 #pragma unroll
     for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&RJs[(tid >> 5) + 8 * it][2 * (tid & 31)]) = rpre[it];
   };
-  stage(I, J);
+  stage(rowblk, colblk);
   for (int t = t0; t < t1; t++) {
-    int rowblk[2], colblk[2];
-    round_robin_pair(nblk, step, I, &rowblk[0], &rowblk[1]);
-    round_robin_pair(nblk, step, J, &colblk[0], &colblk[1]);
     __syncthreads();  // tile and right factor complete in LDS
-    // memory traffic for later: the next tile and its right factor
-    int In = I, Jn = J;
+    // memory traffic for later: the next tile (the next of its row, or the first of the next row) and its right factor
+    int In = I, Jn = J + 1, rowblk_n[2] = {rowblk[0], rowblk[1]}, colblk_n[2];
     const bool more = t + 1 < t1;
     if (more) {
-      decode_tile(t + 1, P, &In, &Jn);
-      gather(In, Jn, xpre);
+      if (Jn == P) {
+        In = I + 1;
+        Jn = In;
+        blocks_of(In, rowblk_n);
+      }
+      blocks_of(Jn, colblk_n);
+      gather(rowblk_n, colblk_n, xpre);
       fetch_right(Jn, rpre);
     }
     acc_t acc[2][2];
@@ -621,8 +631,12 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
       for (int it = 0; it < 8; it++)
         *reinterpret_cast<T2*>(dst + (size_t)(q4 + 4 * it) * Np) = *reinterpret_cast<const T2*>(&X[wr * 32 + q4 + 4 * it][wc * 32 + 2 * l15]);
     }
-    if (more) stage(In, Jn);
-    I = In; J = Jn;
+    if (more) {
+      stage(rowblk_n, colblk_n);
+      I = In; J = Jn;
+      rowblk[0] = rowblk_n[0]; rowblk[1] = rowblk_n[1];
+      colblk[0] = colblk_n[0]; colblk[1] = colblk_n[1];
+    }
   }
 }
 
