@@ -428,7 +428,7 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
 // mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and is scattered back to
 // the stored blocks.  The mirror tile (J,I) is never formed.
 constexpr int FULL_EVERY = 6;  // one solve in FULL_EVERY is a full 63-step sweep of its subproblem
-constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup
+constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup (1 when the launch would not fill the chip)
 
 // Tile index t (row-major over the upper triangle of pair pairs, row I holds P - I tiles) -> (I, J).
 __device__ inline void decode_tile(int t, int P, int* I, int* J) {
@@ -455,10 +455,10 @@ constexpr int GLDP = JT + 2;  // row pitch of the tile in LDS: even (pairs stay 
 template <typename T>
 __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, const T* __restrict__ R,
                                                        const EigState* __restrict__ state, int Np, int nblk, int step,
-                                                       int img0, int nimg) {
+                                                       int img0, int nimg, int gchunk) {
   typedef typename MM<T>::acc_t acc_t;
   typedef typename MM<T>::pair_t T2;  // two neighbouring elements, moved as one 16-byte (8-byte) access
-  const int P = nblk / 2, ntiles = P * (P + 1) / 2, nchunks = (ntiles + G_CHUNK - 1) / G_CHUNK;
+  const int P = nblk / 2, ntiles = P * (P + 1) / 2, nchunks = (ntiles + gchunk - 1) / gchunk;
   int img, chunk;
   if (!group_on_xcd(blockIdx.x, nchunks, nimg, &img, &chunk)) return;
   const int b = img0 + img;
@@ -470,7 +470,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
   const int wr = wave >> 1, wc = wave & 1, l15 = lane & 15, q4 = lane >> 4;
   T* M = G + (size_t)b * Np * Np;
   const T* Rimg = R + (size_t)b * P * JT * JT;
-  const int t0 = chunk * G_CHUNK, t1 = min(ntiles, t0 + G_CHUNK);
+  const int t0 = chunk * gchunk, t1 = min(ntiles, t0 + gchunk);
   if (tid < P) {
     int x, y;
     round_robin_pair(nblk, step, tid, &x, &y);
@@ -799,7 +799,8 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
   const dim3 gs(P, nimg);
-  const int gg = grid_for_groups((P * (P + 1) / 2 + G_CHUNK - 1) / G_CHUNK, nimg), uchunk = (Np / JT) * P * nimg >= 512 ? 3 : 1,
+  const int ntiles = P * (P + 1) / 2, gchunk = ntiles * nimg >= 1024 ? G_CHUNK : 1;  // launches that would not fill the chip otherwise: one tile per workgroup
+  const int gg = grid_for_groups((ntiles + gchunk - 1) / gchunk, nimg), uchunk = (Np / JT) * P * nimg >= 512 ? 3 : 1,
             gu = grid_for_groups(((Np / JT + uchunk - 1) / uchunk) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
@@ -812,7 +813,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JT - 1)));
       else
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JB)));
-      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg)));
+      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, gchunk)));
       if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg, uchunk)));
     }
     TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_offnorm<T><<<dim3(nblk, nimg), 256, 0, st>>>(G, state, offpart, Np, nblk, img0)));
