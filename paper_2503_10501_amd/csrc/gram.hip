@@ -11,45 +11,59 @@ typedef __attribute__((ext_vector_type(4))) double d4;
 constexpr int GK = 32;   // K chunk staged in LDS
 constexpr int GLD = 64;  // panel leading dimension: panel[k][row]
 
+// Eight consecutive stored elements of a row, still in the storage type (converted on the way into LDS).
+template <typename TIn> struct Raw8;
+template <> struct Raw8<uint16_t> { uint4 v; };
+template <> struct Raw8<f16_t> { uint4 v; };
+template <> struct Raw8<float> { float4 a, b; };
+
 template <typename TIn>
-__device__ inline void load8(const TIn* src, double* dst);
-
-template <>
-__device__ inline void load8<uint16_t>(const uint16_t* src, double* dst) {
-  uint4 v = *reinterpret_cast<const uint4*>(src);
-  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+__device__ inline Raw8<TIn> fetch8(const TIn* src) {
+  Raw8<TIn> r;
+  if constexpr (sizeof(TIn) == 2) {
+    r.v = *reinterpret_cast<const uint4*>(src);
+  } else {
+    r.a = *reinterpret_cast<const float4*>(src);
+    r.b = *reinterpret_cast<const float4*>(src + 4);
+  }
+  return r;
+}
+template <typename TIn>
+__device__ inline Raw8<TIn> zero8() {
+  Raw8<TIn> r;
+  if constexpr (sizeof(TIn) == 2) r.v = uint4{0, 0, 0, 0};
+  else { r.a = float4{0, 0, 0, 0}; r.b = float4{0, 0, 0, 0}; }
+  return r;
+}
+template <typename TIn>
+__device__ inline void widen8(const Raw8<TIn>& r, double* dst) {
+  if constexpr (sizeof(TIn) == 2) {
+    const uint32_t w[4] = {r.v.x, r.v.y, r.v.z, r.v.w};
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    dst[2 * i] = (double)__uint_as_float(w[i] << 16);
-    dst[2 * i + 1] = (double)__uint_as_float(w[i] & 0xffff0000u);
+    for (int i = 0; i < 4; i++) {
+      float lo, hi;
+      unpack2<TIn>(w[i], &lo, &hi);
+      dst[2 * i] = (double)lo;
+      dst[2 * i + 1] = (double)hi;
+    }
+  } else {
+    dst[0] = r.a.x; dst[1] = r.a.y; dst[2] = r.a.z; dst[3] = r.a.w;
+    dst[4] = r.b.x; dst[5] = r.b.y; dst[6] = r.b.z; dst[7] = r.b.w;
   }
 }
-template <>
-__device__ inline void load8<f16_t>(const f16_t* src, double* dst) {
-  uint4 v = *reinterpret_cast<const uint4*>(src);
-  uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    float lo, hi;
-    unpack2<f16_t>(w[i], &lo, &hi);
-    dst[2 * i] = (double)lo;
-    dst[2 * i + 1] = (double)hi;
-  }
-}
-template <>
-__device__ inline void load8<float>(const float* src, double* dst) {
-  float4 a = *reinterpret_cast<const float4*>(src);
-  float4 b = *reinterpret_cast<const float4*>(src + 4);
-  dst[0] = a.x; dst[1] = a.y; dst[2] = a.z; dst[3] = a.w;
-  dst[4] = b.x; dst[5] = b.y; dst[6] = b.z; dst[7] = b.w;
-}
 
-// One workgroup: a 64x64 tile (ti >= tj) of G for image blockIdx.y, mirrored into (tj, ti).
+// One workgroup: a 64x64 tile (ti >= tj) of G for one image, mirrored into (tj, ti).  Wavefront w
+// owns quadrant (w / 2, w % 2) as 2 x 2 matrix-core tiles whose 16 rows (columns) are the quadrant's
+// rows 2 m + mt (columns 2 n + nt): both operands of a product step are one 16-byte LDS read, and
+// the results leave as 16-byte pairs (along the row for the tile, along the column for its mirror).
+// The next 32 columns of O are fetched into registers while the matrix cores work on the current ones.
 template <typename TIn, typename TOut>
 __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TOut* __restrict__ G, int N, int D,
                                                    int Np, int B) {
-  __shared__ double As[GK][GLD];
-  __shared__ double Bs[GK][GLD];
+  typedef __attribute__((ext_vector_type(2))) double d2;
+  typedef __attribute__((ext_vector_type(2))) TOut o2;
+  __shared__ __attribute__((aligned(16))) double As[GK][GLD];
+  __shared__ __attribute__((aligned(16))) double Bs[GK][GLD];
   const int ntile = Np / 64;
   int b, t;
   if (!group_on_xcd(blockIdx.x, ntile * (ntile + 1) / 2, B, &b, &t)) return;
@@ -58,7 +72,7 @@ __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TO
   const int tj = t;
   const TIn* Ob = O + (size_t)b * N * D;
   TOut* Gb = G + (size_t)b * Np * Np;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l15 = lane & 15, q4 = lane >> 4;
   const int wr = wave >> 1, wc = wave & 1;
   const int lrow = tid & 63, kc = tid >> 6;  // loader: row within the panel, which 8-wide k chunk
   d4 acc[2][2];
@@ -68,18 +82,14 @@ __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TO
     for (int j = 0; j < 2; j++) acc[i][j] = d4{0, 0, 0, 0};
   const int rowA = ti * 64 + lrow, rowB = tj * 64 + lrow;
   const bool diag = ti == tj;
+  const TIn* srcA = Ob + (size_t)rowA * D + kc * 8;
+  const TIn* srcB = Ob + (size_t)rowB * D + kc * 8;
+  Raw8<TIn> ra = rowA < N ? fetch8<TIn>(srcA) : zero8<TIn>();
+  Raw8<TIn> rb = (!diag && rowB < N) ? fetch8<TIn>(srcB) : zero8<TIn>();
   for (int k0 = 0; k0 < D; k0 += GK) {
     double va[8], vb[8];
-    if (rowA < N) load8<TIn>(Ob + (size_t)rowA * D + k0 + kc * 8, va);
-    else
-#pragma unroll
-      for (int i = 0; i < 8; i++) va[i] = 0.0;
-    if (!diag) {
-      if (rowB < N) load8<TIn>(Ob + (size_t)rowB * D + k0 + kc * 8, vb);
-      else
-#pragma unroll
-        for (int i = 0; i < 8; i++) vb[i] = 0.0;
-    }
+    widen8<TIn>(ra, va);
+    if (!diag) widen8<TIn>(rb, vb);
     __syncthreads();  // previous chunk fully consumed
 #pragma unroll
     for (int i = 0; i < 8; i++) {
@@ -87,31 +97,38 @@ __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TO
       if (!diag) Bs[kc * 8 + i][lrow] = vb[i];
     }
     __syncthreads();
+    if (k0 + GK < D) {  // in flight during the products
+      if (rowA < N) ra = fetch8<TIn>(srcA + k0 + GK);
+      if (!diag && rowB < N) rb = fetch8<TIn>(srcB + k0 + GK);
+    }
     const double(*Bp)[GLD] = diag ? As : Bs;
 #pragma unroll
     for (int kk = 0; kk < GK; kk += 4) {
-      const int k = kk + (lane >> 4);
-      double a0 = As[k][wr * 32 + (lane & 15)], a1 = As[k][wr * 32 + 16 + (lane & 15)];
-      double b0 = Bp[k][wc * 32 + (lane & 15)], b1 = Bp[k][wc * 32 + 16 + (lane & 15)];
-      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc[1][1], 0, 0, 0);
+      const d2 a = *reinterpret_cast<const d2*>(&As[kk + q4][wr * 32 + 2 * l15]);
+      const d2 bb = *reinterpret_cast<const d2*>(&Bp[kk + q4][wc * 32 + 2 * l15]);
+      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.x, bb.x, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.x, bb.y, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.y, bb.x, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.y, bb.y, acc[1][1], 0, 0, 0);
     }
   }
-  // accumulator element j of a lane sits at row 4*j + lane/16, column lane%16 of its 16x16 tile
+  // accumulator element j of a lane sits at tile row 4*j + lane/16, tile column lane%16
 #pragma unroll
-  for (int mt = 0; mt < 2; mt++)
+  for (int j = 0; j < 4; j++) {
+    const int m = 4 * j + q4;
 #pragma unroll
-    for (int nt = 0; nt < 2; nt++)
+    for (int mt = 0; mt < 2; mt++) {
+      const int r = ti * 64 + wr * 32 + 2 * m + mt, c = tj * 64 + wc * 32 + 2 * l15;
+      *reinterpret_cast<o2*>(&Gb[(size_t)r * Np + c]) = o2{(TOut)acc[mt][0][j], (TOut)acc[mt][1][j]};
+    }
+    if (!diag) {
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const int r = ti * 64 + wr * 32 + mt * 16 + 4 * j + (lane >> 4);
-        const int c = tj * 64 + wc * 32 + nt * 16 + (lane & 15);
-        const TOut v = (TOut)acc[mt][nt][j];
-        Gb[(size_t)r * Np + c] = v;
-        if (!diag) Gb[(size_t)c * Np + r] = v;
+      for (int nt = 0; nt < 2; nt++) {
+        const int r = ti * 64 + wr * 32 + 2 * m, c = tj * 64 + wc * 32 + 2 * l15 + nt;
+        *reinterpret_cast<o2*>(&Gb[(size_t)c * Np + r]) = o2{(TOut)acc[0][nt][j], (TOut)acc[1][nt][j]};
       }
+    }
+  }
 }
 
 int launch_gram(const Plan& pl, int dtype, int eig_dtype, const void* O, void* G, hipStream_t st) {
