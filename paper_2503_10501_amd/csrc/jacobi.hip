@@ -56,23 +56,29 @@ __global__ __launch_bounds__(256) void jacobi_init_u(float* __restrict__ U, int 
     Ub[i] = ((i / JB) % Np == (i / ((size_t)JB * Np)) * JB + i % JB) ? 1.f : 0.f;  // row == column in the block-column layout
 }
 
+// ||G||_F^2 of every image, in two steps with fixed summation orders: one workgroup per 32 rows
+// writes a partial sum, then one wavefront per image adds the partials and sets up the solver state.
 template <typename T>
-__global__ __launch_bounds__(1024) void jacobi_init_state(const T* __restrict__ G, EigState* __restrict__ state,
-                                                          int Np) {
-  __shared__ double red[16];
-  const size_t n2 = (size_t)Np * Np;
-  const T* Gb = G + (size_t)blockIdx.x * n2;
+__global__ __launch_bounds__(256) void jacobi_norm_partial(const T* __restrict__ G, double* __restrict__ part, int Np,
+                                                           int nblk) {
+  __shared__ double red[4];
+  const T* rows = G + ((size_t)blockIdx.y * Np + (size_t)blockIdx.x * JB) * Np;
   double s = 0.0;
-  for (size_t i = threadIdx.x; i < n2; i += 1024) { double v = (double)Gb[i]; s += v * v; }
+  for (int i = threadIdx.x; i < JB * Np; i += 256) { const double v = (double)rows[i]; s += v * v; }
   s = wave_sum(s);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    double tot = 0.0;
-    for (int i = 0; i < 16; i++) tot += red[i];
-    state[blockIdx.x].norm2 = tot;
-    state[blockIdx.x].done = tot > 0.0 ? 0 : 1;
-    state[blockIdx.x].sweeps = 0;
+  if (threadIdx.x == 0) part[(size_t)blockIdx.y * nblk + blockIdx.x] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+__global__ void jacobi_init_state(const double* __restrict__ part, EigState* __restrict__ state, int nblk) {
+  const int b = blockIdx.x, lane = threadIdx.x;  // one wavefront per image
+  double s = 0.0;
+  for (int i = lane; i < nblk; i += 64) s += part[(size_t)b * nblk + i];
+  s = wave_sum(s);
+  if (lane == 0) {
+    state[b].norm2 = s;
+    state[b].done = s > 0.0 ? 0 : 1;
+    state[b].sweeps = 0;
   }
 }
 
@@ -825,7 +831,8 @@ template <typename T>
 static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, EigState* state, hipStream_t st) {
   const int Np = pl.Np;
   if (U) TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));  // U == nullptr: eigenvalues only
-  TC_TIMED(PK_JINIT, 1, st, (jacobi_init_state<T><<<pl.B, 1024, 0, st>>>(G, state, Np)));
+  TC_TIMED(PK_JINIT, 1, st, (jacobi_norm_partial<T><<<dim3(pl.nblk, pl.B), 256, 0, st>>>(G, offpart, Np, pl.nblk)));
+  TC_TIMED(PK_JINIT, 2, st, (jacobi_init_state<<<pl.B, 64, 0, st>>>(offpart, state, pl.nblk)));
   int groups = pl.groups > 0 ? pl.groups : (pl.B >= 16 ? 4 : (pl.B >= 4 ? 2 : 1));
   if (groups > pl.B) groups = pl.B;
   if (profiling_active()) groups = 1;  // per-kernel timing wants kernels that run alone
