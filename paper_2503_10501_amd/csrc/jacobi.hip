@@ -553,28 +553,45 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
         blocks_of(In, rowblk_n);
       }
       blocks_of(Jn, colblk_n);
-      gather(rowblk_n, colblk_n, xpre);
-      fetch_right(Jn, rpre);
     }
     acc_t acc[2][2];
 #pragma unroll
     for (int i = 0; i < 2; i++)
 #pragma unroll
       for (int j = 0; j < 2; j++) acc[i][j] = acc_t{0, 0, 0, 0};
-    // W = R_I^T X
-    {  // the operand of product ks + 1 is read from LDS while product ks runs
-      T2 bb = *reinterpret_cast<const T2*>(&X[q4][wc * 32 + 2 * l15]);
-#pragma unroll
-      for (int ks = 0; ks < 16; ks++) {
-        const T2 cb = bb;
-        if (ks + 1 < 16) bb = *reinterpret_cast<const T2*>(&X[4 * (ks + 1) + q4][wc * 32 + 2 * l15]);
-        __builtin_amdgcn_sched_barrier(0);  // keep the read ahead of the products (the scheduler would sink it)
-        acc[0][0] = MM<T>::mma(left[ks][0], cb.x, acc[0][0]);
-        acc[0][1] = MM<T>::mma(left[ks][0], cb.y, acc[0][1]);
-        acc[1][0] = MM<T>::mma(left[ks][1], cb.x, acc[1][0]);
-        acc[1][1] = MM<T>::mma(left[ks][1], cb.y, acc[1][1]);
-      }
+    // W = R_I^T X.  The operand of product ks + 1 is read from LDS while product ks runs, and the 16
+    // loads of the next tile and its right factor are issued one per product step: issued in one
+    // burst by all four wavefronts they queue up in the memory pipeline and stall the products.
+    const T* gsrc = M;
+    const T* rsrc = Rimg;
+    if (more) {
+      const int br = rowblk_n[wr], bc = colblk_n[wc];
+      gsrc = (br <= bc ? M + (size_t)(br * JB) * Np + bc * JB : M + (size_t)(bc * JB) * Np + br * JB) + 2 * l15 + (size_t)q4 * Np;
+      rsrc = Rimg + (size_t)Jn * JT * JT + (tid >> 5) * JT + 2 * (tid & 31);
     }
+    T2 bb = *reinterpret_cast<const T2*>(&X[q4][wc * 32 + 2 * l15]);
+#define TC_PRODUCT1_STEP(ks, PREFETCH)                                                                          \
+  {                                                                                                             \
+    const T2 cb = bb;                                                                                           \
+    if ((ks) + 1 < 16) bb = *reinterpret_cast<const T2*>(&X[4 * ((ks) + 1) + q4][wc * 32 + 2 * l15]);            \
+    if (PREFETCH) { /* one running address per stream: sixteen precomputed ones would spill */                   \
+      if ((ks) < 8) {                                                                                           \
+        xpre[(ks) & 7] = *reinterpret_cast<const T2*>(gsrc);                                                    \
+        gsrc += (size_t)4 * Np;                                                                                 \
+        asm volatile("" : "+v"(gsrc));                                                                          \
+      } else {                                                                                                  \
+        rpre[(ks) & 7] = *reinterpret_cast<const T2*>(rsrc + 8 * ((ks) - 8) * JT);                              \
+      }                                                                                                         \
+    }                                                                                                           \
+    __builtin_amdgcn_sched_barrier(0); /* keep the reads ahead of the products (the scheduler would sink them) */ \
+    acc[0][0] = MM<T>::mma(left[ks][0], cb.x, acc[0][0]);                                                       \
+    acc[0][1] = MM<T>::mma(left[ks][0], cb.y, acc[0][1]);                                                       \
+    acc[1][0] = MM<T>::mma(left[ks][1], cb.x, acc[1][0]);                                                       \
+    acc[1][1] = MM<T>::mma(left[ks][1], cb.y, acc[1][1]);                                                       \
+  }
+#pragma unroll
+    for (int ks = 0; ks < 16; ks++) TC_PRODUCT1_STEP(ks, more)
+#undef TC_PRODUCT1_STEP
     if (more && In != I) load_left(In, left);  // next tile starts a new row of tiles
     __syncthreads();  // every wave has finished reading X
 #pragma unroll
