@@ -148,6 +148,17 @@ def test_hires_2880_tokens_sampled():
     print("hires_b8", rep)
 
 
+def test_maximum_number_of_visual_tokens():
+    # n_vis = 4096 is the largest the library accepts (128 blocks, 127 steps per sweep); two heads of 64
+    # keep the oracle's SVD (4096 x 128) and attention small, and make the Gram matrix rank 128 with a
+    # 3968-dimensional null space
+    tc, gu, parity, _, Workload = _mods()
+    w = Workload("max_tokens", 18, 1, 4096, 2, 2, 2, 64, "bf16", 1024, 512, 8, "powerlaw", 0.05, "proj")
+    rep = parity.run_all_stages(w)
+    print("max_tokens", rep)
+    assert max(rep["C_rel"]) < 1e-4
+
+
 def test_llava13b_batch128_sampled():
     tc, gu, parity, CONFIGS, _ = _mods()
     rep = parity.run_all_stages(CONFIGS["llava13b_b128"], oracle_images=[0, 127])
