@@ -431,8 +431,8 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
 // full), which halves the traffic and keeps the working set of a step inside the last-level cache.
 // One workgroup per pair of block pairs I <= J: the 64x64 tile spanned by the rows of pair I and the
 // columns of pair J is gathered (a quadrant whose block lies below the diagonal is read from its
-// mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and is scattered back to
-// the stored blocks.  The mirror tile (J,I) is never formed.
+// mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and goes back to the
+// stored blocks.  The mirror tile (J,I) is never formed.
 constexpr int FULL_EVERY = 6;  // one solve in FULL_EVERY is a full 63-step sweep of its subproblem
 constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup (1 when the launch would not fill the chip)
 
@@ -444,9 +444,9 @@ __device__ inline void decode_tile(int t, int P, int* I, int* J) {
   *J = t + i;
 }
 
-// A workgroup walks over G_CHUNK consecutive tiles and software-pipelines them: while the matrix
-// cores work on tile k, the gather of tile k+1 and the right factor of tile k are already in flight
-// in registers, so only the first tile of a chunk waits for memory.
+// A workgroup walks over `gchunk` consecutive tiles and software-pipelines them: while the matrix
+// cores work on tile k, tile k+1 and its right factor are already in flight in registers, so only
+// the first tile of a chunk waits for memory.
 //
 // Wavefront w owns quadrant (wr, wc) = (w / 2, w % 2) of the tile: it gathers it, and it holds that
 // quadrant of both products in its accumulators, as 2 x 2 matrix-core tiles of 16 x 16.  The 16 tile
