@@ -434,7 +434,7 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
 // mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and goes back to the
 // stored blocks.  The mirror tile (J,I) is never formed.
 constexpr int FULL_EVERY = 6;  // one solve in FULL_EVERY is a full 63-step sweep of its subproblem
-constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup (1 when the launch would not fill the chip)
+constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup (2 or 1 when the launch would not fill the chip)
 
 // Tile index t (row-major over the upper triangle of pair pairs, row I holds P - I tiles) -> (I, J).
 __device__ inline void decode_tile(int t, int P, int* I, int* J) {
@@ -517,9 +517,22 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
   blocks_of(J, colblk);
   T left[16][2];
   T2 xpre[8], rpre[8];
-  load_left(I, left);
+  // The first left factor goes through the R_J buffer: fetched once per workgroup with 16-byte loads
+  // (as fragments straight from memory each wavefront would fetch its half, the workgroup all of it
+  // twice, in 8-byte pieces), while the first tile and its right factor are already on their way.
+  fetch_right(I, rpre);
   gather(rowblk, colblk, xpre);
+#pragma unroll
+  for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&RJs[(tid >> 5) + 8 * it][2 * (tid & 31)]) = rpre[it];
   fetch_right(J, rpre);
+  __syncthreads();
+#pragma unroll
+  for (int ks = 0; ks < 16; ks++) {
+    left[ks][0] = RJs[4 * ks + q4][wr * 32 + l15];
+    left[ks][1] = RJs[4 * ks + q4][wr * 32 + 16 + l15];
+  }
+  asm volatile("" ::: "memory");  // the optimiser may not sink these reads behind the barrier: the buffer is reused after it
+  __syncthreads();
   // The prefetched quadrant and right factor go from registers into LDS (a quadrant read from its
   // mirror block is transposed here).  Done for the first tile before the loop and for every later
   // tile at the end of the previous iteration, behind that tile's stores: on that path the compiler
@@ -822,7 +835,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
   const dim3 gs(P, nimg);
-  const int ntiles = P * (P + 1) / 2, gchunk = ntiles * nimg >= 1024 ? G_CHUNK : 1;  // launches that would not fill the chip otherwise: one tile per workgroup
+  const int ntiles = P * (P + 1) / 2, gchunk = ntiles * nimg >= 1024 ? G_CHUNK : (ntiles * nimg >= 512 ? 2 : 1);  // smaller launches: fewer tiles per workgroup, so that the chip is still filled
   const int gg = grid_for_groups((ntiles + gchunk - 1) / gchunk, nimg), uchunk = (Np / JT) * P * nimg >= 512 ? 3 : 1,
             gu = grid_for_groups(((Np / JT + uchunk - 1) / uchunk) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
