@@ -233,8 +233,13 @@ __device__ inline int slot_of(int a, int b) {
 template <typename T, bool CROSS>
 __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 8))) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
                                                             const EigState* __restrict__ state, int Np, int nblk,
-                                                            int step, int img0, int inner_steps) {
-  const int b = img0 + blockIdx.y, pair = blockIdx.x, P = nblk / 2;
+                                                            int step, int img0, int nimg, int inner_steps) {
+  // all pairs of an image on the XCD that runs the image's tile updates: the blocks they have just
+  // written are read from that L2, and so is R by the updates that follow
+  const int P = nblk / 2;
+  int img, pair;
+  if (!group_on_xcd(blockIdx.x, P, nimg, &img, &pair)) return;
+  const int b = img0 + img;
   const int done = state[b].done;  // tested after the loads below have been issued
   constexpr int BUF = 4 * N_BLOCKS;  // elements of one buffer: two planes of N_BLOCKS pairs
   constexpr int STAGE = JT * SLD;    // the finished R is staged here for row-contiguous stores
@@ -834,7 +839,7 @@ template <typename T>
 static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart, EigState* state, int img0, int nimg,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
-  const dim3 gs(P, nimg);
+  const int gs = grid_for_groups(P, nimg);
   const int ntiles = P * (P + 1) / 2, gchunk = ntiles * nimg >= 1024 ? G_CHUNK : (ntiles * nimg >= 512 ? 2 : 1);  // smaller launches: fewer tiles per workgroup, so that the chip is still filled
   const int gg = grid_for_groups((ntiles + gchunk - 1) / gchunk, nimg), uchunk = (Np / JT) * P * nimg >= 512 ? 3 : 1,
             gu = grid_for_groups(((Np / JT + uchunk - 1) / uchunk) * P, nimg);
@@ -846,9 +851,9 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
       // blocks converging (cross-only sweeps stall).
       // (float32 solver: always full sweeps; its rounding noise inside the diagonal blocks needs them)
       if (step % FULL_EVERY == 0 || sizeof(T) == 4)
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JT - 1)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JT - 1)));
       else
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, JB)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JB)));
       TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, gchunk)));
       if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg, uchunk)));
     }
