@@ -270,6 +270,23 @@ def test_results_do_not_depend_on_what_the_workspace_held_before(name):
             assert torch.equal(runs[0][k], r[k]), k
 
 
+def test_results_do_not_depend_on_the_number_of_stream_groups():
+    # images are independent: cutting the batch into 1..4 groups on helper streams (and the launch shapes
+    # that follow from the group size) must not change a single bit
+    tc, gu, _, _, _ = _mods()
+    from workloads import make_batch
+    w = _small("bf16_ragged").with_(batch=9)
+    b = make_batch(w)
+    runs = []
+    for groups in (1, 2, 3, 4, 0):
+        p = tc.params_for(w, stream_groups=groups)
+        args = [gu.dev(b[k], p) for k in ("Q", "K", "V")] + [gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)]
+        runs.append(gu.compress(p, *args))
+    for r in runs[1:]:
+        for k in r:
+            assert torch.equal(runs[0][k], r[k]), k
+
+
 def test_inputs_are_not_modified_and_binding_rejects_bad_tensors():
     tc, gu, _, _, _ = _mods()
     from workloads import make_batch
