@@ -107,6 +107,13 @@ def test_llava7b_batch64_in_the_benchmarked_launch_configuration():
     print("llava7b_b64", rep)
 
 
+def test_llava7b_batch64_on_one_stream():
+    # stream_groups = 1: every eigensolver launch covers the whole batch (three tiles per workgroup in the
+    # tile update, the shape bench.py's per-kernel timing and the committed profiles use)
+    tc, gu, parity, CONFIGS, _ = _mods()
+    parity.run_all_stages(CONFIGS["llava7b_b64"], oracle_images=[13, 50], stream_groups=1)
+
+
 def test_llava7b_batch64_with_the_256_to_192_counts():
     tc, gu, parity, CONFIGS, _ = _mods()
     parity.run_all_stages(CONFIGS["llava7b_b64"].with_(k_prune=256, k_final=192), images=range(8),
