@@ -25,14 +25,15 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 def jacobi_update_flops_per_image_step(n_vis):
     """Algorithmic flops of one block-Jacobi tile-update step of G for one image.
 
-    b = 32, a pair tile is 64x64.  With P pairs, symmetry leaves P(P+1)/2 tiles of G, each two
-    64x64x64 products (R_I^T G_IJ, then times R_J).  (The float32 eigenvector update is a separate
-    kernel: (Np/64) x P tiles with one product each.)
+    b = 32, a pair tile is 64x64.  With P pairs, symmetry leaves the P(P-1)/2 tiles I < J of G to
+    this kernel, each two 64x64x64 products (R_I^T G_IJ, then times R_J); the P tiles on the block
+    diagonal come back from the rotation kernel, which holds them rotated at its end.  (The float32
+    eigenvector update is a separate kernel: (Np/64) x P tiles with one product each.)
     """
     np_ = (n_vis + 63) // 64 * 64
     P = np_ // 64
     gemm = 2 * 64 ** 3
-    return P * (P + 1) // 2 * 2 * gemm
+    return P * (P - 1) // 2 * 2 * gemm
 
 
 def main():

@@ -9,8 +9,8 @@
 // sweeps repeat until the off-diagonal mass of G, measured after every sweep, is below the
 // tolerance, per image, with the iteration count fixed on the host and converged images skipped on
 // the device.
-// After the Gram kernel has filled G in full, only its blocks on and above the block diagonal are
-// maintained.
+// After the Gram kernel has filled G in full, only its upper triangle is maintained: the blocks above
+// the block diagonal by the tile update, the blocks of a pair itself by the rotation kernel.
 // On exit diag(G) holds the eigenvalues sigma_i^2 and U the left singular vectors of O
 // (Section 3.3.1: Z = U Sigma V^T  =>  Z Z^T = U Sigma^2 U^T).
 #include <mutex>
@@ -231,7 +231,7 @@ __device__ inline int slot_of(int a, int b) {
 }
 
 template <typename T, bool CROSS>
-__global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 8))) void jacobi_solve(const T* __restrict__ G, T* __restrict__ R,
+__global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 8))) void jacobi_solve(T* __restrict__ G, T* __restrict__ R,
                                                             const EigState* __restrict__ state, int Np, int nblk,
                                                             int step, int img0, int nimg, int inner_steps) {
   // all pairs of an image on the XCD that runs the image's tile updates: the blocks they have just
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
   __shared__ Pair2<T> rcs[2][JB];                  // (c, z) of every seat, [parity]
   int p, q;
   round_robin_pair(nblk, step, pair, &p, &q);
-  const T* Gb = G + (size_t)b * Np * Np;
+  T* Gb = G + (size_t)b * Np * Np;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool rwave = wave == SOLVE_WAVES;  // the rotation wavefront
@@ -260,12 +260,14 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
   auto next_top = [](int x) { return CROSS || x == 63 ? x : next63(x); };
   auto next_bot = [](int x) { return CROSS ? (x == JT - 1 ? JB : x + 1) : next63(x); };
   // Element {r,c} of the subproblem, r and c in 0..63 (first the rows and columns of block p, then
-  // of block q).  Block (q,p) is not stored: read its mirror.
-  auto gload = [&](int r, int c) {
-    if (r >= JB && c < JB) { const int t = r; r = c; c = t; }
+  // of block q), lives in memory at its place in the upper triangle: block (q,p) is not stored, and of
+  // the diagonal blocks only the upper triangle is kept up to date.
+  auto gaddr = [&](int r, int c) {
+    if (r > c) { const int t = r; r = c; c = t; }
     const int gr = (r < JB ? p * JB + r : q * JB + r - JB), gc = (c < JB ? p * JB + c : q * JB + c - JB);
-    return Gb[(size_t)gr * Np + gc];
+    return Gb + (size_t)gr * Np + gc;
   };
+  auto gload = [&](int r, int c) { return *gaddr(r, c); };
   // the off-diagonal block of S this lane owns (wavefronts 0..7): row I of the strict upper triangle holds JB-1-I blocks
   const bool act = !rwave && tid < N_OFFDIAG;
   int sI = 0, sJ = act ? tid : 0;
@@ -328,9 +330,9 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
 
   for (int st = 0; st < inner_steps; st++) {  // a whole sweep brings the seats back to their starting order
     const int par = st & 1, cur = par * BUF, nxt = BUF - cur;
-    const bool more = st + 1 < inner_steps;  // after the last step only R leaves the kernel
+    const bool more = st + 1 < inner_steps;  // after the last step no further rotations are needed
     if (rwave) {
-      if (lane < JB && more) {
+      if (lane < JB) {
         // ---- the next pivot, evaluated from the current S and the current rotations ---------------
         // element (kr, kc) of J_I^T B J_J for the block at pair slot r, in the order the block lanes use
         auto element = [&](int r, bool isdiag, Pair2<T> rI, Pair2<T> rJ, bool kr, bool kc) {
@@ -344,15 +346,21 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
         };
         const Pair2<T> rX = rcs[par][Sx], rY = rcs[par][Sy];
         const T axx = element(rdx, true, rX, rX, kx, kx), ayy = element(rdy, true, rY, rY, ky, ky);
-        const T axy = element(rdxy, false, swp ? rY : rX, swp ? rX : rY, swp ? ky : kx, swp ? kx : ky);
         SB[nxt + rd] = axx;                      // the seat's new diagonal ((top,bottom) comes from a block lane)
         SB[nxt + 2 * N_BLOCKS + rd + 1] = ayy;
-        SB[nxt + wtb] = T(0);                    // the element annihilated in this step, at its new place
-        store_rotation(par ^ 1, axx, axy, ayy);
+        // the element this step's rotation annihilates, at its new place: not an exact zero (the angle
+        // is only good to single precision), and since this S goes back to G, what is left of the
+        // element has to stay in it (dropping it would not be a similarity transformation)
+        const Pair2<T> rM = rcs[par][seat];
+        SB[nxt + wtb] = element(rd, true, rM, rM, false, true);
+        if (more) {
+          const T axy = element(rdxy, false, swp ? rY : rX, swp ? rX : rY, swp ? ky : kx, swp ? kx : ky);
+          store_rotation(par ^ 1, axx, axy, ayy);
+        }
       }
     } else {
       // ---- S <- J^T S J ---------------------------------------------------------------------------
-      if (act && more) {
+      if (act) {
         const Pair2<T> rI = rcs[par][sI], rJ = rcs[par][sJ];
         const Pair2<T> et = *reinterpret_cast<const Pair2<T>*>(&SB[cur + rd]);
         const Pair2<T> eb = *reinterpret_cast<const Pair2<T>*>(&SB[cur + 2 * N_BLOCKS + rd]);
@@ -407,6 +415,15 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
     }
     __syncthreads();  // the other S buffer, the next rotations and the handed-over columns are complete
   }
+  // The rotated subproblem itself is R^T [[G_pp G_pq][G_qp G_qq]] R: it goes back to G from here (the
+  // tile update leaves the tiles on the block diagonal alone).  After a whole sweep the seats are
+  // back in their step-0 order, so every lane finds its elements where it put them at the start.
+  const int fin = ((inner_steps - 1) & 1) ? 0 : BUF;  // the buffer the last step wrote
+  Pair2<T> s_t = Pair2<T>{T(0), T(0)}, s_b = Pair2<T>{T(0), T(0)};
+  if (act || (rwave && lane < JB)) {
+    s_t = *reinterpret_cast<const Pair2<T>*>(&SB[fin + rd]);
+    s_b = *reinterpret_cast<const Pair2<T>*>(&SB[fin + 2 * N_BLOCKS + rd]);
+  }
   if (!rwave) {
     if (inner_steps > 0) {
       const int par = (inner_steps - 1) & 1;
@@ -417,8 +434,10 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
         if (wave > 0) rbot[0] = xch[par][XCOPIES - 1][wave - 1][lane];
       }
     }
-    // after a whole sweep (63 or 32 steps) the seats are back in their step-0 order; stage R through
-    // LDS (S is no longer needed) for row-contiguous stores
+  }
+  __syncthreads();  // every lane holds its elements of S: the buffers are free
+  if (!rwave) {
+    // stage R through LDS for row-contiguous stores
 #pragma unroll
     for (int k = 0; k < SEATS; k++) {
       const int i = SEATS * wave + k;
@@ -426,27 +445,36 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
       SB[lane * SLD + bot0(i)] = rbot[k];
     }
   }
+  if (act) {
+    const int iTI = top0(sI), iBI = bot0(sI), iTJ = top0(sJ), iBJ = bot0(sJ);
+    *gaddr(iTI, iTJ) = s_t.x; *gaddr(iTI, iBJ) = s_t.y;
+    *gaddr(iBI, iTJ) = s_b.x; *gaddr(iBI, iBJ) = s_b.y;
+  } else if (rwave && lane < JB) {
+    const int it = top0(seat), ib = bot0(seat);
+    *gaddr(it, it) = s_t.x; *gaddr(it, ib) = s_t.y; *gaddr(ib, ib) = s_b.y;
+  }
   __syncthreads();
   T* Rb = R + ((size_t)b * P + pair) * JT * JT;
   for (int e = tid; e < JT * JT; e += SOLVE_THREADS) Rb[e] = SB[(e >> 6) * SLD + (e & 63)];
 }
 
 // ---------------------------------------------------------------------------------------
-// Tile update of G.  Only the 32x32 blocks (r,c) with r <= c are kept up to date (diagonal blocks in
-// full), which halves the traffic and keeps the working set of a step inside the last-level cache.
-// One workgroup per pair of block pairs I <= J: the 64x64 tile spanned by the rows of pair I and the
-// columns of pair J is gathered (a quadrant whose block lies below the diagonal is read from its
-// mirror block and transposed on the way into LDS), becomes R_I^T G_IJ R_J, and goes back to the
-// stored blocks.  The mirror tile (J,I) is never formed.
+// Tile update of G.  Only the 32x32 blocks (r,c) with r <= c are kept up to date (of the diagonal
+// blocks the upper triangle), which halves the traffic and keeps the working set of a step inside
+// the last-level cache.  The three blocks of a pair itself come back from the rotation kernel, which
+// holds R_I^T G_II R_I at its end anyway; here one workgroup takes pairs of block pairs I < J: the
+// 64x64 tile spanned by the rows of pair I and the columns of pair J is gathered (a quadrant whose
+// block lies below the diagonal is read from its mirror block and transposed on the way into LDS),
+// becomes R_I^T G_IJ R_J, and goes back to the stored blocks.  The mirror tile (J,I) is never formed.
 constexpr int FULL_EVERY = 6;  // one solve in FULL_EVERY is a full 63-step sweep of its subproblem
 constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup (2 or 1 when the launch would not fill the chip)
 
-// Tile index t (row-major over the upper triangle of pair pairs, row I holds P - I tiles) -> (I, J).
+// Tile index t (row-major over the pairs of pairs I < J, row I holds P - 1 - I tiles) -> (I, J).
 __device__ inline void decode_tile(int t, int P, int* I, int* J) {
   int i = 0;
-  while (t >= P - i) { t -= P - i; i++; }
+  while (t >= P - 1 - i) { t -= P - 1 - i; i++; }
   *I = i;
-  *J = t + i;
+  *J = t + i + 1;
 }
 
 // A workgroup walks over `gchunk` consecutive tiles and software-pipelines them: while the matrix
@@ -469,7 +497,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
                                                        int img0, int nimg, int gchunk) {
   typedef typename MM<T>::acc_t acc_t;
   typedef typename MM<T>::pair_t T2;  // two neighbouring elements, moved as one 16-byte (8-byte) access
-  const int P = nblk / 2, ntiles = P * (P + 1) / 2, nchunks = (ntiles + gchunk - 1) / gchunk;
+  const int P = nblk / 2, ntiles = P * (P - 1) / 2, nchunks = (ntiles + gchunk - 1) / gchunk;
   int img, chunk;
   if (!group_on_xcd(blockIdx.x, nchunks, nimg, &img, &chunk)) return;
   const int b = img0 + img;
@@ -567,7 +595,7 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
     if (more) {
       if (Jn == P) {
         In = I + 1;
-        Jn = In;
+        Jn = In + 1;
         blocks_of(In, rowblk_n);
       }
       blocks_of(Jn, colblk_n);
@@ -646,14 +674,12 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
     // The quadrant of Y goes from the accumulators to its block (rows of block rowblk[wr], columns
     // of block colblk[wc]) as 16-byte column pairs.  A quadrant whose block is only stored as its
     // mirror is first transposed inside the wavefront's own quarter of X (nobody else touches that
-    // quarter before the next barrier, and the LDS serves one wavefront's accesses in order).  The
-    // lower quadrant of a diagonal tile mirrors its quadrant (0,1); it is written to its own block
-    // below the block diagonal, which nobody reads.  This way every wavefront issues exactly eight
-    // stores per tile on every path: the wait for the prefetched next tile at the top of the loop
-    // can then leave them in flight (the memory counter is in order and the compiler has to assume
-    // the path with the fewest stores behind the loads).
+    // quarter before the next barrier, and the LDS serves one wavefront's accesses in order).  This
+    // way every wavefront issues exactly eight stores per tile on every path: the wait for the
+    // prefetched next tile can then leave them in flight (the memory counter is in order and the
+    // compiler has to assume the path with the fewest stores behind the loads).
     const int br = rowblk[wr], bc = colblk[wc];
-    if (br <= bc || I == J) {
+    if (br <= bc) {
       T* dst = M + (size_t)(br * JB) * Np + bc * JB + 2 * l15;
 #pragma unroll
       for (int mt = 0; mt < 2; mt++)
@@ -769,8 +795,8 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
 
 // ---------------------------------------------------------------------------------------
 // Off-diagonal mass of G after a sweep, from the blocks that are maintained: block row i of image b
-// gives  sum_{c != r, same block} G_rc^2 + 2 sum_{blocks j > i} G_rc^2  (the blocks below the block
-// diagonal mirror those above).  One workgroup per (block row, image); every thread adds its
+// gives  2 sum_{c > r} G_rc^2  over its rows (what lies below the diagonal mirrors what lies above
+// and is not kept up to date).  One workgroup per (block row, image); every thread adds its
 // elements in a fixed order and the partial sums are combined in a fixed order, so the stopping
 // decision is reproducible.
 template <typename T>
@@ -785,7 +811,7 @@ __global__ __launch_bounds__(256) void jacobi_offnorm(const T* __restrict__ G, c
   for (int e = tid; e < JB * width; e += 256) {
     const int r = e / width, c = e % width;  // consecutive threads read consecutive columns of one row
     const double v = (double)Gb[(size_t)(c0 + r) * Np + c0 + c];
-    s += (c >= JB ? 2.0 : (c == r ? 0.0 : 1.0)) * v * v;
+    s += (c > r ? 2.0 : 0.0) * v * v;  // strictly above the diagonal; the mirror half is not kept up to date
   }
   s = wave_sum(s);
   if ((tid & 63) == 0) red[tid >> 6] = s;
@@ -840,7 +866,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
                           hipStream_t st) {
   const int Np = pl.Np, nblk = pl.nblk, P = pl.P;
   const int gs = grid_for_groups(P, nimg);
-  const int ntiles = P * (P + 1) / 2, gchunk = ntiles * nimg >= 1024 ? G_CHUNK : (ntiles * nimg >= 512 ? 2 : 1);  // smaller launches: fewer tiles per workgroup, so that the chip is still filled
+  const int ntiles = P * (P - 1) / 2, gchunk = ntiles * nimg >= 1024 ? G_CHUNK : (ntiles * nimg >= 512 ? 2 : 1);  // smaller launches: fewer tiles per workgroup, so that the chip is still filled
   const int gg = grid_for_groups((ntiles + gchunk - 1) / gchunk, nimg), uchunk = (Np / JT) * P * nimg >= 512 ? 3 : 1,
             gu = grid_for_groups(((Np / JT + uchunk - 1) / uchunk) * P, nimg);
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
@@ -854,7 +880,8 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JT - 1)));
       else
         TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JB)));
-      TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, gchunk)));
+      if (ntiles > 0)  // a single pair: the rotation kernel has done it all
+        TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, gchunk)));
       if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg, uchunk)));
     }
     TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_offnorm<T><<<dim3(nblk, nimg), 256, 0, st>>>(G, state, offpart, Np, nblk, img0)));
