@@ -20,6 +20,24 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix-core peak
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_FP64_VECTOR_TFLOPS = 78.6  # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz
+PEAK_FP32_VECTOR_TFLOPS = 157.3
+FULL_EVERY = 6                   # one rotation launch in six sweeps all 64 indices of its pair (csrc/jacobi.hip)
+
+
+def jacobi_solve_flops_per_image_sweep(n_vis):
+    """Algorithmic flops of the rotation kernel for one image and sweep.
+
+    One step of a pair's 64x64 subproblem applies 32 disjoint plane rotations from both sides to the
+    symmetric S (528 2x2 blocks of its upper triangle, 4 results of 2 x 3 flops each) and from the right
+    to the accumulated R (4096 entries, 3 flops each).  A launch runs 32 such steps (63 at every
+    FULL_EVERY-th step of a sweep); a sweep has Np/32 - 1 launches of Np/64 pairs.
+    """
+    np_ = (n_vis + 63) // 64 * 64
+    P, steps = np_ // 64, np_ // 32 - 1
+    per_step = 528 * 24 + 4096 * 3
+    full = len(range(0, steps, FULL_EVERY))
+    return P * per_step * (full * 63 + (steps - full) * 32)
 
 
 def jacobi_update_flops_per_image_step(n_vis):
@@ -131,6 +149,15 @@ def main():
         flops += active * per_img * steps_per_sweep
     achieved = flops / (upd_ms * 1e-3) / 1e12
     peak = PEAK_FP64_MFMA_TFLOPS if args.eig == "f64" else PEAK_FP32_MFMA_TFLOPS
+    # the rotation kernel: plain vector arithmetic (the float32 solver sweeps all 64 indices in every launch)
+    solve_ms, solve_launches = kinds["jacobi_solve"]
+    if args.eig == "f64":
+        solve_per_img = jacobi_solve_flops_per_image_sweep(N)
+    else:
+        solve_per_img = ((N + 63) // 64) * (528 * 24 + 4096 * 3) * 63 * steps_per_sweep
+    solve_flops = sum(int((sweeps > s).sum()) for s in range(p.jacobi_max_sweeps)) * solve_per_img
+    solve_achieved = solve_flops / (solve_ms * 1e-3) / 1e12
+    solve_peak = PEAK_FP64_VECTOR_TFLOPS if args.eig == "f64" else PEAK_FP32_VECTOR_TFLOPS
     total_kernel_ms = sum(v[0] for v in kinds.values())
     sustained = tc.tc_probe_rates()   # what this GPU delivers on register-only MFMA loops and a plain copy
     traffic = None   # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
@@ -163,6 +190,10 @@ def main():
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
                      "avg_launch_us": round(upd_ms * 1e3 / max(upd_launches, 1), 2), "launches": upd_launches,
                      "frac_of_sustained_mfma": round(achieved / sustained["mfma_f64_tflops" if args.eig == "f64" else "mfma_f32_tflops"], 4)},
+        "roofline_alu": {"kernel": "jacobi_solve", "bound": "alu", "achieved": round(solve_achieved, 3),
+                         "peak": solve_peak, "unit": "TFLOP/s", "frac": round(solve_achieved / solve_peak, 4),
+                         "avg_launch_us": round(solve_ms * 1e3 / max(solve_launches, 1), 2),
+                         "launches": solve_launches},
         "sustained_rates": {k: round(v, 1) for k, v in sustained.items()},
         "kernel_ms": {k: round(v[0], 3) for k, v in kinds.items()},
         "kernel_ms_total": round(total_kernel_ms, 3),
