@@ -9,7 +9,7 @@ namespace tc {
 typedef __attribute__((ext_vector_type(4))) double d4;
 
 constexpr int GK = 32;   // K chunk staged in LDS
-constexpr int GLD = 64;  // panel leading dimension: panel[k][row]
+constexpr int GLD = 66;  // panel leading dimension: panel[k][row]; 66 keeps the four contraction rows a wavefront reads at once in different banks
 
 // Eight consecutive stored elements of a row, still in the storage type (converted on the way into LDS).
 template <typename TIn> struct Raw8;
@@ -53,10 +53,15 @@ __device__ inline void widen8(const Raw8<TIn>& r, double* dst) {
 }
 
 // One workgroup: a 64x64 tile (ti >= tj) of G for one image, mirrored into (tj, ti).  Wavefront w
-// owns quadrant (w / 2, w % 2) as 2 x 2 matrix-core tiles whose 16 rows (columns) are the quadrant's
-// rows 2 m + mt (columns 2 n + nt): both operands of a product step are one 16-byte LDS read, and
-// the results leave as 16-byte pairs (along the row for the tile, along the column for its mirror).
-// The next 32 columns of O are fetched into registers while the matrix cores work on the current ones.
+// owns quadrant (w / 2, w % 2).  The products run on v_mfma_f64_4x4x4 (four independent 4x4x4 blocks
+// per instruction), which sustains half as much again as the 16x16x4 form on this chip; a plain
+// product with a long contraction can feed it: lane l = p + 4 q + 16 k holds A[p][k] of block q
+// (here the same for all four blocks), B[k][p] of block q, and gets D[k][p] of block q, so with
+//   A = rows 8 p + r of the quadrant (r = 0..7: eight products share one 16-byte-aligned run of LDS),
+//   B = columns 2 (4 q + p) + s    (s = 0, 1: both in one 16-byte read),
+// sixteen products per four contraction indices take five 16-byte LDS reads, and a lane ends with
+// rows 8 k + r, columns 2 (4 q + p) + s: 16-byte pairs along the row for the tile, runs of eight
+// along the column for its mirror.  The next 32 columns of O are fetched into registers meanwhile.
 template <typename TIn, typename TOut>
 __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TOut* __restrict__ G, int N, int D,
                                                    int Np, int B) {
@@ -75,11 +80,10 @@ __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TO
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l15 = lane & 15, q4 = lane >> 4;
   const int wr = wave >> 1, wc = wave & 1;
   const int lrow = tid & 63, kc = tid >> 6;  // loader: row within the panel, which 8-wide k chunk
-  d4 acc[2][2];
+  const int p4 = lane & 3, blk = (lane >> 2) & 3, kq = lane >> 4;
+  double acc[8][2];
 #pragma unroll
-  for (int i = 0; i < 2; i++)
-#pragma unroll
-    for (int j = 0; j < 2; j++) acc[i][j] = d4{0, 0, 0, 0};
+  for (int r = 0; r < 8; r++) acc[r][0] = acc[r][1] = 0.0;
   const int rowA = ti * 64 + lrow, rowB = tj * 64 + lrow;
   const bool diag = ti == tj;
   const TIn* srcA = Ob + (size_t)rowA * D + kc * 8;
@@ -104,30 +108,29 @@ __global__ __launch_bounds__(256) void gram_kernel(const TIn* __restrict__ O, TO
     const double(*Bp)[GLD] = diag ? As : Bs;
 #pragma unroll
     for (int kk = 0; kk < GK; kk += 4) {
-      const d2 a = *reinterpret_cast<const d2*>(&As[kk + q4][wr * 32 + 2 * l15]);
-      const d2 bb = *reinterpret_cast<const d2*>(&Bp[kk + q4][wc * 32 + 2 * l15]);
-      acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.x, bb.x, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.x, bb.y, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.y, bb.x, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a.y, bb.y, acc[1][1], 0, 0, 0);
-    }
-  }
-  // accumulator element j of a lane sits at tile row 4*j + lane/16, tile column lane%16
+      const double* arow = &As[kk + kq][wr * 32 + 8 * p4];
+      const d2 a01 = *reinterpret_cast<const d2*>(arow), a23 = *reinterpret_cast<const d2*>(arow + 2);
+      const d2 a45 = *reinterpret_cast<const d2*>(arow + 4), a67 = *reinterpret_cast<const d2*>(arow + 6);
+      const d2 bb = *reinterpret_cast<const d2*>(&Bp[kk + kq][wc * 32 + 2 * (4 * blk + p4)]);
+      const double a[8] = {a01.x, a01.y, a23.x, a23.y, a45.x, a45.y, a67.x, a67.y};
 #pragma unroll
-  for (int j = 0; j < 4; j++) {
-    const int m = 4 * j + q4;
-#pragma unroll
-    for (int mt = 0; mt < 2; mt++) {
-      const int r = ti * 64 + wr * 32 + 2 * m + mt, c = tj * 64 + wc * 32 + 2 * l15;
-      *reinterpret_cast<o2*>(&Gb[(size_t)r * Np + c]) = o2{(TOut)acc[mt][0][j], (TOut)acc[mt][1][j]};
-    }
-    if (!diag) {
-#pragma unroll
-      for (int nt = 0; nt < 2; nt++) {
-        const int r = ti * 64 + wr * 32 + 2 * m, c = tj * 64 + wc * 32 + 2 * l15 + nt;
-        *reinterpret_cast<o2*>(&Gb[(size_t)c * Np + r]) = o2{(TOut)acc[0][nt][j], (TOut)acc[1][nt][j]};
+      for (int r = 0; r < 8; r++) {
+        acc[r][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(a[r], bb.x, acc[r][0], 0, 0, 0);
+        acc[r][1] = __builtin_amdgcn_mfma_f64_4x4x4f64(a[r], bb.y, acc[r][1], 0, 0, 0);
       }
     }
+  }
+  // the lane holds rows 8 kq + r, columns 2 (4 blk + p4) + s of its quadrant
+  const int r0 = ti * 64 + wr * 32 + 8 * kq, c0 = tj * 64 + wc * 32 + 2 * (4 * blk + p4);
+#pragma unroll
+  for (int r = 0; r < 8; r++)
+    *reinterpret_cast<o2*>(&Gb[(size_t)(r0 + r) * Np + c0]) = o2{(TOut)acc[r][0], (TOut)acc[r][1]};
+  if (!diag) {
+#pragma unroll
+    for (int sc = 0; sc < 2; sc++)
+#pragma unroll
+      for (int r = 0; r < 8; r += 2)
+        *reinterpret_cast<o2*>(&Gb[(size_t)(c0 + sc) * Np + r0 + r]) = o2{(TOut)acc[r][sc], (TOut)acc[r + 1][sc]};
   }
 }
 
