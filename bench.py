@@ -147,7 +147,7 @@ def main():
     for s in range(p.jacobi_max_sweeps):
         active = int((sweeps > s).sum())            # images still iterating in sweep s
         flops += active * per_img * steps_per_sweep
-    achieved = flops / (upd_ms * 1e-3) / 1e12
+    achieved = flops / (upd_ms * 1e-3) / 1e12 if upd_launches else 0.0   # a single block pair (N <= 64) has no tile update
     peak = PEAK_FP64_MFMA_TFLOPS if args.eig == "f64" else PEAK_FP32_MFMA_TFLOPS
     # the rotation kernel: plain vector arithmetic (the float32 solver sweeps all 64 indices in every launch)
     solve_ms, solve_launches = kinds["jacobi_solve"]
