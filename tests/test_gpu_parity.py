@@ -294,6 +294,40 @@ def test_results_do_not_depend_on_the_number_of_stream_groups():
             assert torch.equal(runs[0][k], r[k]), k
 
 
+def test_two_calls_on_different_streams_with_their_own_workspaces_may_overlap():
+    # the helper streams of the eigensolver are shared by all calls on a device: two calls in flight at
+    # once, each on its own stream with its own workspace, must give what each gives alone
+    tc, gu, _, _, _ = _mods()
+    from workloads import make_batch
+    w = _small("bf16_ragged").with_(batch=9)
+    batches = [make_batch(w, list(range(9))), make_batch(w, list(range(20, 29)))]
+    p = tc.params_for(w)
+    sd = tc.storage_dtype(p)
+    B, N = p.batch, p.n_vis
+    args = [[gu.dev(b[k], p) for k in ("Q", "K", "V")] + [gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)]
+            for b in batches]
+    alone = [gu.compress(p, *a) for a in args]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs, wss = [], []
+    for _ in range(2):
+        outs.append({"X_out": torch.empty(B, p.k_final, p.hidden_dim, dtype=sd, device="cuda"),
+                     "kept_idx": torch.empty(B, p.k_final, dtype=torch.int32, device="cuda"),
+                     "merge_dst": torch.empty(B, N, dtype=torch.int32, device="cuda"),
+                     "E": torch.empty(B, N, dtype=torch.float32, device="cuda"),
+                     "info": torch.empty(B, dtype=torch.int32, device="cuda")})
+        wss.append(tc.new_workspace(p))
+    torch.cuda.synchronize()
+    for rep in range(3):   # both calls are enqueued before either can have finished
+        for i in (0, 1):
+            o = outs[i]
+            tc.tc_compress(p, *args[i], o["X_out"], o["kept_idx"], o["merge_dst"], wss[i], score=o["E"],
+                           info=o["info"], stream=streams[i].cuda_stream)
+    torch.cuda.synchronize()
+    for i in (0, 1):
+        for k in outs[i]:
+            assert torch.equal(outs[i][k], alone[i][k]), (i, k)
+
+
 def test_inputs_are_not_modified_and_binding_rejects_bad_tensors():
     tc, gu, _, _, _ = _mods()
     from workloads import make_batch
