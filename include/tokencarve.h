@@ -162,8 +162,13 @@ TC_API int tc_compress(const tc_params* p, const void* Q, const void* K, const v
  * kernel launch, waits for the stream, and returns on the HOST the summed duration in milliseconds
  * and the number of launches per kernel kind (arrays of TC_PROF_KINDS entries, order of tc_prof_kind).
  * jacobi_update_ms_by_sweep (host, max_sweeps_out floats, may be NULL) receives the tile-update time
- * of each eigensolver sweep.  Unlike every other entry point this one blocks the calling thread and
- * creates and destroys HIP events.
+ * of each eigensolver sweep; jacobi_work (host, 2 entries, may be NULL) the work the eigensolver has
+ * actually done in all sweeps and images together: [0] the number of 64x64 tiles of G the tile update
+ * has processed, [1] the number of rotation steps (32 plane rotations of a 64x64 subproblem each) the
+ * rotation kernel has applied (towards the end the eigensolver leaves converged block pairs alone;
+ * their visits and the tiles between two such pairs are not counted).  Unlike every
+ * other entry point this one blocks the calling thread, creates and destroys HIP events and copies a
+ * few bytes per image from the workspace to the host.
  */
 typedef enum {
   TC_PROF_ATTN = 0, TC_PROF_ATTN_REDUCE, TC_PROF_GRAM, TC_PROF_JACOBI_INIT, TC_PROF_JACOBI_SOLVE,
@@ -173,7 +178,8 @@ typedef enum {
 TC_API int tc_profile_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X,
                                void* X_out, int32_t* kept_idx, int32_t* merge_dst, int32_t* info, void* ws,
                                size_t ws_bytes, void* stream, float* ms_by_kind, int32_t* launches_by_kind,
-                               float* jacobi_update_ms_by_sweep, int32_t max_sweeps_out);
+                               float* jacobi_update_ms_by_sweep, int32_t max_sweeps_out,
+                               int64_t* jacobi_work);
 
 /*
  * Information quantity of a set of visual tokens (Section 3.2.2, "matrix rank as a proxy metric"; the

@@ -83,7 +83,7 @@ def load_library():
     lib.tc_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.tc_merge.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-    lib.tc_profile_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, ctypes.c_int32]
+    lib.tc_profile_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, ctypes.c_int32, vp]
     lib.tc_probe_rates.argtypes = [vp, sz, vp, vp]
     lib.tc_info_rank.argtypes = [pp, vp, vp, ctypes.c_int32, ctypes.c_float, vp, vp, vp, vp, sz, vp]
     lib.tc_assemble_sequence.argtypes = [pp, vp, vp, vp, vp, vp, ctypes.c_float, vp, vp, vp]
@@ -169,17 +169,24 @@ def tc_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, ws, O=None, score=Non
 
 
 def tc_profile_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, info, ws, max_sweeps_out=64, stream=None):
-    """Returns ({kind: (total_ms, launches)}, [jacobi_update ms per sweep]); blocks until the stream is idle."""
+    """Returns ({kind: (total_ms, launches)}, [jacobi_update ms per sweep]); blocks until the stream is idle.
+    The extra keys "jacobi_update_tiles" and "jacobi_rotation_steps" hold (0.0, count): the 64x64 tiles the
+    tile update processed and the rotation steps the rotation kernel applied."""
     sd = storage_dtype(p)
     n = len(PROF_KINDS)
     ms = (ctypes.c_float * n)()
     cnt = (ctypes.c_int32 * n)()
     per_sweep = (ctypes.c_float * max_sweeps_out)()
+    work = (ctypes.c_int64 * 2)()
     _check(load_library().tc_profile_compress(ctypes.byref(p), _ptr(Q, sd), _ptr(K, sd), _ptr(V, sd), _ptr(X, sd),
                                               _ptr(X_out, sd), _ptr(kept_idx, torch.int32),
                                               _ptr(merge_dst, torch.int32), _ptr(info, torch.int32), _ptr(ws),
-                                              ws.numel(), _stream(stream), ms, cnt, per_sweep, max_sweeps_out))
-    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(PROF_KINDS)}, [float(x) for x in per_sweep]
+                                              ws.numel(), _stream(stream), ms, cnt, per_sweep, max_sweeps_out,
+                                              work))
+    kinds = {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(PROF_KINDS)}
+    kinds["jacobi_update_tiles"] = (0.0, int(work[0]))
+    kinds["jacobi_rotation_steps"] = (0.0, int(work[1]))
+    return kinds, [float(x) for x in per_sweep]
 
 
 def tc_probe_rates(stream=None):

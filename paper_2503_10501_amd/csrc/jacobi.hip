@@ -75,10 +75,13 @@ __global__ void jacobi_init_state(const double* __restrict__ part, EigState* __r
   double s = 0.0;
   for (int i = lane; i < nblk; i += 64) s += part[(size_t)b * nblk + i];
   s = wave_sum(s);
+  for (int i = lane; i < MAX_NVIS / JT; i += 64) state[b].rot_steps[i] = 0u;
   if (lane == 0) {
     state[b].norm2 = s;
+    state[b].thr2 = 0.0;
     state[b].done = s > 0.0 ? 0 : 1;
     state[b].sweeps = 0;
+    state[b].tiles = 0u;
   }
 }
 
@@ -232,8 +235,8 @@ __device__ inline int slot_of(int a, int b) {
 
 template <typename T, bool CROSS>
 __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 8))) void jacobi_solve(T* __restrict__ G, T* __restrict__ R,
-                                                            const EigState* __restrict__ state, int Np, int nblk,
-                                                            int step, int img0, int nimg, int inner_steps) {
+                                                            EigState* __restrict__ state, int Np, int nblk,
+                                                            int step, int img0, int nimg, int inner_steps, int count_work) {
   // all pairs of an image on the XCD that runs the image's tile updates: the blocks they have just
   // written are read from that L2, and so is R by the updates that follow
   const int P = nblk / 2;
@@ -241,12 +244,14 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
   if (!group_on_xcd(blockIdx.x, P, nimg, &img, &pair)) return;
   const int b = img0 + img;
   const int done = state[b].done;  // tested after the loads below have been issued
+  const double thr2 = state[b].thr2;
   constexpr int BUF = 4 * N_BLOCKS;  // elements of one buffer: two planes of N_BLOCKS pairs
   constexpr int STAGE = JT * SLD;    // the finished R is staged here for row-contiguous stores
   constexpr int XCOPIES = CROSS ? 1 : 2;
   __shared__ __attribute__((aligned(16))) T SB[(2 * BUF > STAGE ? 2 * BUF : STAGE)];
   __shared__ T xch[2][XCOPIES][SOLVE_WAVES][JT];  // columns of R handed to the neighbouring wavefront: [parity][top/bottom]
   __shared__ Pair2<T> rcs[2][JB];                  // (c, z) of every seat, [parity]
+  __shared__ double mass[SOLVE_WAVES + 1];         // what this visit would remove, per wavefront
   int p, q;
   round_robin_pair(nblk, step, pair, &p, &q);
   T* Gb = G + (size_t)b * Np * Np;
@@ -294,19 +299,27 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
   const int rdxy = 2 * (swp ? block_id(Sy, Sx) : block_id(Sx, Sy));
 
   T d_tt = T(0), d_tb = T(0), d_bb = T(0);
+  double m = 0.0;  // squares of the elements this visit annihilates: a cross sweep's tops are in block p, its bottoms in block q
   if (act) {
     const int iTI = top0(sI), iBI = bot0(sI), iTJ = top0(sJ), iBJ = bot0(sJ);
     const T ett = gload(iTI, iTJ), etb = gload(iTI, iBJ), ebt = gload(iBI, iTJ), ebb = gload(iBI, iBJ);
     if (done) return;  // uniform over the workgroup
     *reinterpret_cast<Pair2<T>*>(&SB[rd]) = Pair2<T>{ett, etb};
     *reinterpret_cast<Pair2<T>*>(&SB[2 * N_BLOCKS + rd]) = Pair2<T>{ebt, ebb};
+    m = (double)etb * etb + (double)ebt * ebt;
+    if (!CROSS) m += (double)ett * ett + (double)ebb * ebb;
   } else if (rwave && lane < JB) {  // the diagonal block of the seat
     d_tt = gload(rt, rt); d_tb = gload(rt, rb); d_bb = gload(rb, rb);
     if (done) return;
     *reinterpret_cast<Pair2<T>*>(&SB[rd]) = Pair2<T>{d_tt, d_tb};
     SB[2 * N_BLOCKS + rd + 1] = d_bb;
+    m = (double)d_tb * d_tb;
   } else if (done) {
     return;
+  }
+  if (thr2 > 0.0) {  // uniform over the workgroup
+    m = wave_sum(m);
+    if (lane == 0) mass[wave] = m;
   }
   T rtop[SEATS], rbot[SEATS];  // columns of R in seat order (wavefronts 0..7), R = I at the start
 #pragma unroll
@@ -327,6 +340,21 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
   };
   if (rwave && lane < JB && inner_steps > 0) store_rotation(0, d_tt, d_tb, d_bb);  // rotations of step 0
   __syncthreads();
+  if (thr2 > 0.0) {
+    double tot = 0.0;
+#pragma unroll
+    for (int k = 0; k <= SOLVE_WAVES; k++) tot += mass[k];
+    if (2.0 * tot <= thr2) {  // nothing worth removing: R = I, G stays as it is, the updates skip this pair
+      T* Rb = R + ((size_t)b * P + pair) * JT * JT;
+      for (int e = tid; e < JT * JT; e += SOLVE_THREADS) Rb[e] = (e >> 6) == (e & 63) ? T(1) : T(0);
+      if (tid == 0) state[b].skip[pair] = 1;
+      return;
+    }
+  }
+  if (tid == 0) {  // no other workgroup touches this pair's slots during the launch
+    state[b].skip[pair] = 0;
+    if (count_work) state[b].rot_steps[pair] += (unsigned)inner_steps;  // only under the profiling entry point, which reads it
+  }
 
   for (int st = 0; st < inner_steps; st++) {  // a whole sweep brings the seats back to their starting order
     const int par = st & 1, cur = par * BUF, nxt = BUF - cur;
@@ -466,6 +494,7 @@ __global__ __launch_bounds__(SOLVE_BOUND) __attribute__((amdgpu_waves_per_eu(8, 
 // 64x64 tile spanned by the rows of pair I and the columns of pair J is gathered (a quadrant whose
 // block lies below the diagonal is read from its mirror block and transposed on the way into LDS),
 // becomes R_I^T G_IJ R_J, and goes back to the stored blocks.  The mirror tile (J,I) is never formed.
+constexpr double SKIP_START = 500.0;  // converged block pairs are skipped once off(G) < SKIP_START * tolerance
 constexpr int FULL_EVERY = 6;  // one solve in FULL_EVERY is a full 63-step sweep of its subproblem
 constexpr int G_CHUNK = 3;  // consecutive tiles handled by one workgroup (2 or 1 when the launch would not fill the chip)
 
@@ -493,19 +522,21 @@ constexpr int GLDP = JT + 2;  // row pitch of the tile in LDS: even (pairs stay 
 
 template <typename T>
 __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, const T* __restrict__ R,
-                                                       const EigState* __restrict__ state, int Np, int nblk, int step,
-                                                       int img0, int nimg, int gchunk) {
+                                                       EigState* __restrict__ state, int Np, int nblk, int step,
+                                                       int img0, int nimg, int gchunk, int count_work) {
   typedef typename MM<T>::acc_t acc_t;
   typedef typename MM<T>::pair_t T2;  // two neighbouring elements, moved as one 16-byte (8-byte) access
   const int P = nblk / 2, ntiles = P * (P - 1) / 2, nchunks = (ntiles + gchunk - 1) / gchunk;
   int img, chunk;
   if (!group_on_xcd(blockIdx.x, nchunks, nimg, &img, &chunk)) return;
   const int b = img0 + img;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int myskip = tid < P ? state[b].skip[tid] : 0;  // in flight together with the load of `done`
   if (state[b].done) return;
   __shared__ __attribute__((aligned(16))) T X[JT][GLDP];   // the tile, then W
   __shared__ __attribute__((aligned(16))) T RJs[JT][GLDP]; // the right factor R_J
   __shared__ int2 pairs[MAX_NVIS / JT];                     // the two blocks of every pair of this step
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ int skipped[MAX_NVIS / JT + 1];                // pairs the rotation kernel left alone (R = I)
   const int wr = wave >> 1, wc = wave & 1, l15 = lane & 15, q4 = lane >> 4;
   T* M = G + (size_t)b * Np * Np;
   const T* Rimg = R + (size_t)b * P * JT * JT;
@@ -514,8 +545,18 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
     int x, y;
     round_robin_pair(nblk, step, tid, &x, &y);
     pairs[tid] = int2{x, y};
+    skipped[tid] = myskip;
+  }
+  if (count_work && chunk == 0 && wave == 0) {  // under the profiling entry point one wavefront per image counts the tiles processed
+    const unsigned sk = __builtin_popcountll(__ballot(myskip != 0));  // P <= 64: all flags sit in this wavefront
+    if (lane == 0) state[b].tiles += (unsigned)ntiles - sk * (sk - 1) / 2;
   }
   __syncthreads();
+  // a tile between two skipped pairs stays as it is (uniform over the workgroup)
+  auto active = [&](int i, int j) { return __builtin_amdgcn_readfirstlane(skipped[i] & skipped[j]) == 0; };
+  auto advance = [&](int* i, int* j) {  // the next tile of the row, or the first of the next row
+    if (++*j == P) { ++*i; *j = *i + 1; }
+  };
   auto blocks_of = [&](int pr, int* blk) {  // uniform over the workgroup
     const int2 v = pairs[pr];
     blk[0] = __builtin_amdgcn_readfirstlane(v.x);
@@ -544,8 +585,10 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
 #pragma unroll
     for (int it = 0; it < 8; it++) x[it] = *reinterpret_cast<const T2*>(RJ + 8 * it * JT);
   };
-  int I, J, rowblk[2], colblk[2];
+  int I, J, rowblk[2], colblk[2], t = t0;
   decode_tile(t0, P, &I, &J);
+  while (t < t1 && !active(I, J)) { t++; advance(&I, &J); }
+  if (t >= t1) return;
   blocks_of(I, rowblk);
   blocks_of(J, colblk);
   T left[16][2];
@@ -587,17 +630,15 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
     for (int it = 0; it < 8; it++) *reinterpret_cast<T2*>(&RJs[(tid >> 5) + 8 * it][2 * (tid & 31)]) = rpre[it];
   };
   stage(rowblk, colblk);
-  for (int t = t0; t < t1; t++) {
+  for (;;) {
     __syncthreads();  // tile and right factor complete in LDS
-    // memory traffic for later: the next tile (the next of its row, or the first of the next row) and its right factor
-    int In = I, Jn = J + 1, rowblk_n[2] = {rowblk[0], rowblk[1]}, colblk_n[2];
-    const bool more = t + 1 < t1;
+    // memory traffic for later: the next tile of the chunk that has work to do, and its right factor
+    int In = I, Jn = J, tn = t + 1, rowblk_n[2] = {rowblk[0], rowblk[1]}, colblk_n[2];
+    advance(&In, &Jn);
+    while (tn < t1 && !active(In, Jn)) { tn++; advance(&In, &Jn); }
+    const bool more = tn < t1;
     if (more) {
-      if (Jn == P) {
-        In = I + 1;
-        Jn = In + 1;
-        blocks_of(In, rowblk_n);
-      }
+      if (In != I) blocks_of(In, rowblk_n);
       blocks_of(Jn, colblk_n);
     }
     acc_t acc[2][2];
@@ -698,12 +739,11 @@ __global__ __launch_bounds__(256, 2) void jacobi_update_g(T* __restrict__ G, con
       for (int it = 0; it < 8; it++)
         *reinterpret_cast<T2*>(dst + (size_t)(q4 + 4 * it) * Np) = *reinterpret_cast<const T2*>(&X[wr * 32 + q4 + 4 * it][wc * 32 + 2 * l15]);
     }
-    if (more) {
-      stage(rowblk_n, colblk_n);
-      I = In; J = Jn;
-      rowblk[0] = rowblk_n[0]; rowblk[1] = rowblk_n[1];
-      colblk[0] = colblk_n[0]; colblk[1] = colblk_n[1];
-    }
+    if (!more) break;
+    stage(rowblk_n, colblk_n);
+    I = In; J = Jn; t = tn;
+    rowblk[0] = rowblk_n[0]; rowblk[1] = rowblk_n[1];
+    colblk[0] = colblk_n[0]; colblk[1] = colblk_n[1];
   }
 }
 
@@ -727,10 +767,11 @@ __global__ __launch_bounds__(256) void jacobi_update_u(float* __restrict__ U, co
   int img, tile;
   if (!group_on_xcd(blockIdx.x, nchunk * P, nimg, &img, &tile)) return;
   const int b = img0 + img;
-  if (state[b].done) return;
+  const int J = tile % P, chunk = tile / P;
+  const int done = state[b].done, skipJ = state[b].skip[J];  // both loads in flight together
+  if (done | skipJ) return;  // skipped by the rotation kernel: R_J = I
   __shared__ __attribute__((aligned(16))) float X[JT][ULD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l15 = lane & 15, q4 = lane >> 4;
-  const int J = tile % P, chunk = tile / P;
   const int slab0 = chunk * uchunk, slab1 = min(nslab, slab0 + uchunk);
   float* M = U + (size_t)b * Np * Np;
   int colblk[2];
@@ -829,8 +870,14 @@ __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* _
   for (int i = lane; i < count; i += 64) s += op[i];
   s = wave_sum(s);
   if (lane == 0) {
+    const double limit = tol * tol * state[b].norm2;
     state[b].sweeps += 1;
-    if (s <= tol * tol * state[b].norm2) state[b].done = 1;
+    if (s <= limit) state[b].done = 1;
+    // Close to the end most block pairs have already converged far below the tolerance while a few still
+    // carry the remaining mass (convergence is quadratic pair by pair).  From here on a visit is skipped
+    // when it would remove less than limit / (64 nblk^2): all skipped visits of a sweep together
+    // leave less than 1/128 of the squared stopping threshold, and the stopping test itself keeps measuring G.
+    if (s <= SKIP_START * SKIP_START * limit) state[b].thr2 = limit / (64.0 * count * count);
   }
 }
 
@@ -869,6 +916,7 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
   const int ntiles = P * (P - 1) / 2, gchunk = ntiles * nimg >= 1024 ? G_CHUNK : (ntiles * nimg >= 512 ? 2 : 1);  // smaller launches: fewer tiles per workgroup, so that the chip is still filled
   const int gg = grid_for_groups((ntiles + gchunk - 1) / gchunk, nimg), uchunk = (Np / JT) * P * nimg >= 512 ? 3 : 1,
             gu = grid_for_groups(((Np / JT + uchunk - 1) / uchunk) * P, nimg);
+  const int count_work = profiling_active() ? 1 : 0;  // the kernels keep count of the work they really do only for the profiler
   for (int sweep = 0; sweep < pl.max_sweeps; sweep++) {
     for (int step = 0; step < pl.steps; step++) {
       // Step 0 of a sweep visits every block, and its full 63-step solve leaves the diagonal blocks
@@ -877,11 +925,11 @@ static void enqueue_group(const Plan& pl, T* G, float* U, T* R, double* offpart,
       // blocks converging (cross-only sweeps stall).
       // (float32 solver: always full sweeps; its rounding noise inside the diagonal blocks needs them)
       if (step % FULL_EVERY == 0 || sizeof(T) == 4)
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JT - 1)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, false><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JT - 1, count_work)));
       else
-        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JB)));
+        TC_TIMED(PK_JSOLVE, sweep, st, (jacobi_solve<T, true><<<gs, SOLVE_THREADS, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, JB, count_work)));
       if (ntiles > 0)  // a single pair: the rotation kernel has done it all
-        TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, gchunk)));
+        TC_TIMED(PK_JUPDATE, sweep, st, (jacobi_update_g<T><<<gg, 256, 0, st>>>(G, R, state, Np, nblk, step, img0, nimg, gchunk, count_work)));
       if (U) TC_TIMED(PK_JUPDATE_U, sweep, st, (jacobi_update_u<T><<<gu, 256, 0, st>>>(U, R, state, Np, nblk, step, img0, nimg, uchunk)));
     }
     TC_TIMED(PK_JSWEEPEND, sweep, st, (jacobi_offnorm<T><<<dim3(nblk, nimg), 256, 0, st>>>(G, state, offpart, Np, nblk, img0)));

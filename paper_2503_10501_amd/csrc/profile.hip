@@ -31,7 +31,8 @@ using namespace tc;
 extern "C" int tc_profile_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X,
                                    void* X_out, int32_t* kept_idx, int32_t* merge_dst, int32_t* info, void* ws,
                                    size_t ws_bytes, void* stream, float* ms_by_kind, int32_t* launches_by_kind,
-                                   float* jacobi_update_ms_by_sweep, int32_t max_sweeps_out) {
+                                   float* jacobi_update_ms_by_sweep, int32_t max_sweeps_out,
+                                   int64_t* jacobi_work) {
   if (!ms_by_kind || !launches_by_kind) return TC_ERR_NULL;
   Profiler prof;
   g_prof = &prof;
@@ -54,5 +55,19 @@ extern "C" int tc_profile_compress(const tc_params* p, const void* Q, const void
     (void)hipEventDestroy(r.stop);
   }
   if (rc != TC_OK) return rc;
-  return e == hipSuccess ? TC_OK : TC_ERR_HIP;
+  if (e != hipSuccess) return TC_ERR_HIP;
+  if (jacobi_work) {  // the solver state of every image is still in the workspace
+    jacobi_work[0] = jacobi_work[1] = 0;
+    Plan pl;
+    if (make_plan(p, &pl) == TC_OK && pl.B > 0) {
+      std::vector<EigState> host((size_t)pl.B);
+      if (hipMemcpy(host.data(), at<EigState>(ws, pl.off_state), host.size() * sizeof(EigState), hipMemcpyDeviceToHost) != hipSuccess)
+        return TC_ERR_HIP;
+      for (const EigState& st : host) {
+        jacobi_work[0] += st.tiles;
+        for (unsigned v : st.rot_steps) jacobi_work[1] += v;
+      }
+    }
+  }
+  return TC_OK;
 }

@@ -27,8 +27,12 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 // Per-image eigensolver state kept in the workspace.
 struct EigState {
   double norm2;    // ||G||_F^2, fixed for the whole solve
+  double thr2;     // a visit of a block pair is skipped when the mass it would remove is <= thr2 (0: never)
   int32_t done;    // 1 once the off-diagonal measure fell below the tolerance
   int32_t sweeps;  // sweeps executed so far
+  uint32_t tiles;  // 64x64 tiles the tile update has processed (skipped ones not counted); for the profiler
+  uint32_t rot_steps[MAX_NVIS / JT];  // rotation steps (32 plane rotations each) the rotation kernel has applied at pair slot i; for the profiler
+  int32_t skip[MAX_NVIS / JT];  // per pair of the current step: 1 = the rotation kernel left it alone (R = I)
 };
 
 // Everything an entry point needs to know about sizes and where its scratch lives.

@@ -229,6 +229,38 @@ def test_non_convergence_is_reported_in_info():
     assert gu.host(info)[0] == -1
 
 
+def test_converged_block_pairs_are_left_alone_and_the_work_done_is_counted():
+    # in its last sweeps the eigensolver skips visits of block pairs that have nothing left to remove;
+    # the profiling entry point reports the work actually done (accuracy with skipping is what every
+    # parity test above measures)
+    tc, gu, _, CONFIGS, _ = _mods()
+    from workloads import make_batch
+    w = CONFIGS["llava7b_b1"]
+    b = make_batch(w)
+    p = tc.params_for(w)
+    sd = tc.storage_dtype(p)
+    Q, K, V = (gu.dev(b[k], p) for k in ("Q", "K", "V"))
+    X = gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)
+    ws = tc.new_workspace(p)
+    X_out = torch.empty(1, p.k_final, p.hidden_dim, dtype=sd, device="cuda")
+    kept = torch.empty(1, p.k_final, dtype=torch.int32, device="cuda")
+    dst = torch.empty(1, p.n_vis, dtype=torch.int32, device="cuda")
+    info = torch.empty(1, dtype=torch.int32, device="cuda")
+    kinds, _ = tc.tc_profile_compress(p, Q, K, V, X, X_out, kept, dst, info, ws)
+    sweeps = int(info.cpu()[0])
+    assert sweeps > 0
+    P, steps = 9, 17
+    full_launches = len(range(0, steps, 6))
+    tiles_full = sweeps * steps * (P * (P - 1) // 2)
+    rot_full = P * (steps * 63 + (sweeps - 1) * (full_launches * 63 + (steps - full_launches) * 32))
+    tiles, rot = kinds["jacobi_update_tiles"][1], kinds["jacobi_rotation_steps"][1]
+    assert 0.7 * tiles_full < tiles < tiles_full, (tiles, tiles_full)
+    assert 0.7 * rot_full < rot < rot_full, (rot, rot_full)
+    # the same call without profiling gives the same result
+    ref = gu.compress(p, Q, K, V, X)
+    assert torch.equal(ref["kept_idx"], kept) and torch.equal(ref["X_out"], X_out) and torch.equal(ref["info"], info)
+
+
 def test_results_are_bit_reproducible():
     tc, gu, _, _, _ = _mods()
     from workloads import make_batch
