@@ -40,6 +40,10 @@ __device__ inline float lane_perm(float v) {
   return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(v), CTRL, 0xf, 0xf, false));
 }
 
+// 2^x by the hardware instruction alone: results below the smallest normal number come out as 0, which
+// a softmax term of that size may (the library routine spends five more instructions per call on them)
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 constexpr int AQ = 128;  // queries per workgroup
 constexpr int AK = 64;   // keys per LDS tile
 
@@ -146,6 +150,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   const int q_last = min(N, (qt + 1) * AQ) - 1;
   const int kend = causal ? min(L, Ls + q_last + 1) : L;
   const int n_tiles = (kend + AK - 1) / AK;
+  // keys [0, kvis_all) are visible to every query of this wavefront (its first query sees the fewest)
+  const int kvis_all = causal ? min(L, Ls + min(qt * AQ + wave * 32, N - 1) + 1) : L;
 
   vec8 qf[DH / 16];
 #pragma unroll
@@ -166,6 +172,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
 #pragma unroll
     for (int sub = 0; sub < 2; sub++) {
       const f16v acc = score_subtile<DH, F16>(Ks, sub, qf, lane);
+      if (k0 + sub * 32 + 32 <= kvis_all) {  // every key visible to every query of the wavefront: no masks
+        float mx = acc[0];
+#pragma unroll
+        for (int r = 1; r < 16; r++) mx = fmaxf(mx, acc[r]);
+        const float m_new = fmaxf(m_run, mx * scale_log2e);  // the scale is positive
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) sum += fast_exp2(fmaf(acc[r], scale_log2e, -m_new));
+        l_run = l_run * fast_exp2(m_run - m_new) + sum;
+        m_run = m_new;
+        continue;
+      }
       float s2[16], mx = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; r++) {
@@ -177,8 +195,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
         const float m_new = fmaxf(m_run, mx);
         float sum = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; r++) sum += exp2f(s2[r] - m_new);
-        l_run = l_run * exp2f(m_run - m_new) + sum;
+        for (int r = 0; r < 16; r++) sum += fast_exp2(s2[r] - m_new);
+        l_run = l_run * fast_exp2(m_run - m_new) + sum;
         m_run = m_new;
       }
     }
@@ -186,10 +204,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   {
     const float m_o = __shfl_xor(m_run, 32, 64), l_o = __shfl_xor(l_run, 32, 64);
     const float M = fmaxf(m_run, m_o);  // finite: key 0 is visible to every query
-    l_run = l_run * exp2f(m_run - M) + l_o * exp2f(m_o - M);
+    l_run = l_run * fast_exp2(m_run - M) + l_o * fast_exp2(m_o - M);
     m_run = M;
   }
-  const float inv_l = qvalid ? 1.0f / l_run : 0.f;  // rows past N contribute nothing
+  // p = 2^(s - m) / l = 2^(s - (m + log2 l)); rows past N contribute nothing (2^-inf = 0)
+  const float m_fold = qvalid ? m_run + log2f(l_run) : INFINITY;
 
   // ---------------- pass 2: probabilities, O^T accumulation, column sums ----------------
   f16v oacc[DH / 32];
@@ -215,10 +234,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
       float pr[16];
       {
         const f16v acc = score_subtile<DH, F16>(Ks, sub, qf, lane);
+        if (k0 + sub * 32 + 32 <= kvis_all) {
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-          pr[r] = key < kend_q ? exp2f(acc[r] * scale_log2e - m_run) * inv_l : 0.f;
+          for (int r = 0; r < 16; r++) pr[r] = fast_exp2(fmaf(acc[r], scale_log2e, -m_fold));
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            pr[r] = key < kend_q ? fast_exp2(fmaf(acc[r], scale_log2e, -m_fold)) : 0.f;
+          }
         }
       }
       // O^T += V^T P^T.  Matrix-core k-slot (half, i) of product u is key
