@@ -252,10 +252,10 @@ def test_converged_block_pairs_are_left_alone_and_the_work_done_is_counted():
     P, steps = 9, 17
     full_launches = len(range(0, steps, 6))
     tiles_full = sweeps * steps * (P * (P - 1) // 2)
-    rot_full = P * (steps * 63 + (sweeps - 1) * (full_launches * 63 + (steps - full_launches) * 32))
+    rot_full = P * sweeps * (full_launches * 63 + (steps - full_launches) * 32)   # every sixth step sweeps all 64 indices
     tiles, rot = kinds["jacobi_update_tiles"][1], kinds["jacobi_rotation_steps"][1]
-    assert 0.7 * tiles_full < tiles < tiles_full, (tiles, tiles_full)
-    assert 0.7 * rot_full < rot < rot_full, (rot, rot_full)
+    assert 0.8 * tiles_full < tiles < tiles_full, (tiles, tiles_full)
+    assert 0.8 * rot_full < rot < rot_full, (rot, rot_full)
     # the same call without profiling gives the same result
     ref = gu.compress(p, Q, K, V, X)
     assert torch.equal(ref["kept_idx"], kept) and torch.equal(ref["X_out"], X_out) and torch.equal(ref["info"], info)
