@@ -849,10 +849,12 @@ __global__ __launch_bounds__(256) void jacobi_offnorm(const T* __restrict__ G, c
   const T* Gb = G + (size_t)b * Np * Np;
   const int c0 = i * JB, width = Np - c0;
   double s = 0.0;
-  for (int e = tid; e < JB * width; e += 256) {
-    const int r = e / width, c = e % width;  // consecutive threads read consecutive columns of one row
-    const double v = (double)Gb[(size_t)(c0 + r) * Np + c0 + c];
-    s += (c > r ? 2.0 : 0.0) * v * v;  // strictly above the diagonal; the mirror half is not kept up to date
+  for (int r = tid >> 6; r < JB; r += 4) {  // a wavefront takes every fourth row, its lanes consecutive columns
+    const T* row = Gb + (size_t)(c0 + r) * Np + c0;
+    for (int c = r + 1 + (tid & 63); c < width; c += 64) {  // strictly above the diagonal; the mirror half is not kept up to date
+      const double v = (double)row[c];
+      s += 2.0 * v * v;
+    }
   }
   s = wave_sum(s);
   if ((tid & 63) == 0) red[tid >> 6] = s;
