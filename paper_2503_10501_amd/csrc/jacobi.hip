@@ -8,7 +8,9 @@
 // (jacobi_update), both as small matrix products on the matrix cores.  nblk-1 steps make a sweep;
 // sweeps repeat until the off-diagonal mass of G, measured after every sweep, is below the
 // tolerance, per image, with the iteration count fixed on the host and converged images skipped on
-// the device.
+// the device.  Close to convergence the rotation kernel also leaves alone every pair whose visit would
+// remove a negligible mass (R = I and a flag in the solver state), and the updates skip what such
+// pairs span.
 // After the Gram kernel has filled G in full, only its upper triangle is maintained: the blocks above
 // the block diagonal by the tile update, the blocks of a pair itself by the rotation kernel.
 // On exit diag(G) holds the eigenvalues sigma_i^2 and U the left singular vectors of O
@@ -24,10 +26,9 @@ typedef __attribute__((ext_vector_type(4))) float f4;
 
 // 16x16x4 matrix-core product for both element types.  A: lane holds A[lane%16][lane/16];
 // B: lane holds B[lane/16][lane%16]; accumulator element j of a lane is C[row(j)][lane%16].
-// Which four of the 64 contraction indices one product covers is free as long as A and B agree: the
-// eigenvector update gives product ks the indices ks, ks+16, ks+32, ks+48 (the four LDS rows a
-// wavefront reads at once fall into different banks with its 65-element row pitch), the tile update
-// of G the indices 4 ks .. 4 ks + 3 (conflict-free with its 66-element pitch).
+// Which four of the 64 contraction indices one product covers is free as long as A and B agree:
+// both updates give product ks the indices 4 ks .. 4 ks + 3 (lane / 16 picks one of them), and pad
+// their LDS rows (66 doubles, 68 floats) so that the operand reads of a wavefront are conflict-free.
 template <typename T> struct MM;
 template <> struct MM<double> {
   typedef d4 acc_t;
