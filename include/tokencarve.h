@@ -86,8 +86,8 @@ typedef struct {
                            (off = Frobenius norm of the off-diagonal part);
                            0 => 2e-9 (3e-6 for TC_EIG_F32)                                      */
   int32_t eig_dtype;    /* tc_eig_dtype                                                         */
-  int32_t stream_groups; /* eigensolver: 0 = cut the batch into up to 4 groups that run on helper
-                            streams and overlap; 1 = everything on `stream`; 2..4 = that many groups */
+  int32_t stream_groups; /* eigensolver: 0 = cut the batch into 1, 2 or 4 groups (by the amount of work) that
+                            run on helper streams and overlap; 1 = everything on `stream`; 2..4 = that many groups */
 } tc_params;
 
 /* Bytes of scratch that any entry point may need for `p` (0 if p is invalid). */

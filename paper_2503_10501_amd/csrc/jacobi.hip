@@ -946,7 +946,10 @@ static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, Eig
   if (U) TC_TIMED(PK_JINIT, 0, st, (jacobi_init_u<<<dim3(Np * Np / 1024 > 0 ? Np * Np / 1024 : 1, pl.B), 256, 0, st>>>(U, Np)));  // U == nullptr: eigenvalues only
   TC_TIMED(PK_JINIT, 1, st, (jacobi_norm_partial<T><<<dim3(pl.nblk, pl.B), 256, 0, st>>>(G, offpart, Np, pl.nblk)));
   TC_TIMED(PK_JINIT, 2, st, (jacobi_init_state<<<pl.B, 64, 0, st>>>(offpart, state, pl.nblk)));
-  int groups = pl.groups > 0 ? pl.groups : (pl.B >= 16 ? 4 : (pl.B >= 4 ? 2 : 1));
+  // Splitting pays once every group still fills the chip with its tile updates (measured at N = 576:
+  // one stream up to 12 images, two from 16, four from 32; N = 2880: four at 8 images)
+  const long tiles = (long)pl.B * pl.P * (pl.P - 1) / 2;
+  int groups = pl.groups > 0 ? pl.groups : (tiles >= 1152 ? 4 : (tiles >= 576 ? 2 : 1));
   if (groups > pl.B) groups = pl.B;
   if (profiling_active()) groups = 1;  // per-kernel timing wants kernels that run alone
   StreamPool* pool = groups > 1 ? helper_streams() : nullptr;

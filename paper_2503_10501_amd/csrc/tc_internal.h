@@ -153,22 +153,23 @@ __host__ __device__ inline void round_robin_pair(int n, int s, int i, int* a, in
 // The hardware deals workgroups to the 8 XCDs (each with its own L2) round-robin by linear id.
 // group_on_xcd() maps a linear id to (group, item) so that all `items` workgroups of a group land
 // on one XCD and run back to back there (what they share -- rotation blocks, K/V of a head, row
-// panels -- is then fetched into that L2 once).  Launch grid_for_groups() workgroups; the function
-// returns false for the padding.  With fewer than 8 groups the plain order is kept so that the
-// whole chip is used.
-__host__ __device__ inline int grid_for_groups(int items, int groups) {
-  return items * (groups >= 8 ? round_up(groups, 8) : groups);
-}
+// panels -- is then fetched into that L2 once).  Groups are taken eight at a time, one per XCD; the
+// groups left over when their number is not a multiple of 8 keep the plain order, spread over all
+// XCDs (one XCD with an extra group would finish long after the others).  Launch grid_for_groups()
+// workgroups; the function returns false for an id outside the grid.
+__host__ __device__ inline int grid_for_groups(int items, int groups) { return items * groups; }
 __device__ inline bool group_on_xcd(int id, int items, int groups, int* group, int* item) {
-  if (groups < 8) {
-    *group = id / items;
-    *item = id % items;
-    return true;
+  const int full = groups & ~7, lim = items * full;
+  if (id >= lim) {
+    const int r = id - lim;
+    *group = full + r / items;
+    *item = r % items;
+    return *group < groups;
   }
   const int k = id >> 3;
   *item = k % items;
   *group = (k / items) * 8 + (id & 7);
-  return *group < groups;
+  return true;
 }
 
 template <typename T>
