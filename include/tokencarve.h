@@ -56,7 +56,8 @@ typedef enum {
   TC_ERR_PARAM = -4,     /* lambda, k_prune, k_final, tolerances out of range        */
   TC_ERR_WORKSPACE = -5, /* ws_bytes < tc_workspace_bytes(p)                         */
   TC_ERR_ALIGN = -6,     /* a pointer is not 16-byte aligned                         */
-  TC_ERR_HIP = -7        /* a HIP launch failed (hipGetLastError was not hipSuccess) */
+  TC_ERR_HIP = -7,       /* a HIP launch failed (hipGetLastError was not hipSuccess) */
+  TC_ERR_SCRATCH = -8    /* tc_merge_noalloc: the sizes need more than TC_NOALLOC_SCRATCH_BYTES */
 } tc_status;
 
 typedef enum { TC_F32 = 0, TC_BF16 = 1, TC_F16 = 2 } tc_dtype;  /* storage of Q,K,V,O,X,X_out (TC_F16: IEEE half) */
@@ -145,6 +146,21 @@ TC_API int tc_select_topk(const tc_params* p, const float* score, int32_t* order
 TC_API int tc_merge(const tc_params* p, const void* X, const void* metric, const int32_t* order,
              void* X_out, int32_t* kept_idx, int32_t* merge_dst, void* ws, size_t ws_bytes,
              void* stream);
+
+/*
+ * tc_merge for callers that cannot allocate or pass a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as tc_merge, but
+ * the scratch (row norms, similarity matrix, merge list) comes from a static device array of
+ * TC_NOALLOC_SCRATCH_BYTES inside the library, which every GPU the library is used on holds from the
+ * first call until the process ends.  The call allocates and frees nothing and enqueues kernels only
+ * (no memset nodes).  It needs 4 B k_p + 4 B |A| |B| + 8 B max(m, 1) bytes (each term rounded up to 256) and returns
+ * TC_ERR_SCRATCH, launching nothing, when that exceeds the array.  All calls on one GPU share the array:
+ * calls that overlap in time on the same GPU (different streams or host threads) race; calls ordered on
+ * one stream are safe.
+ */
+#define TC_NOALLOC_SCRATCH_BYTES (16u << 20)
+TC_API int tc_merge_noalloc(const tc_params* p, const void* X, const void* metric, const int32_t* order,
+                            void* X_out, int32_t* kept_idx, int32_t* merge_dst, void* stream);
 
 /*
  * The whole path of Section 3.3 on one stream: tc_attn_output -> tc_ipgs_score ->

@@ -19,7 +19,7 @@ TC_NORM_NONE, TC_NORM_MINMAX = 0, 1
 TC_EIG_F64, TC_EIG_F32 = 0, 1
 
 SYMBOLS = ("tc_workspace_bytes", "tc_status_string", "tc_attn_output", "tc_ipgs_score", "tc_select_topk",
-           "tc_merge", "tc_compress", "tc_profile_compress", "tc_probe_rates", "tc_info_rank",
+           "tc_merge", "tc_merge_noalloc", "tc_compress", "tc_profile_compress", "tc_probe_rates", "tc_info_rank",
            "tc_assemble_sequence", "tc_kv_cache_fraction")
 PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_update_u", "jacobi_sweep_end",
               "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average")
@@ -82,6 +82,7 @@ def load_library():
     lib.tc_ipgs_score.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.tc_merge.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.tc_merge_noalloc.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
     lib.tc_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_profile_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, ctypes.c_int32, vp]
     lib.tc_probe_rates.argtypes = [vp, sz, vp, vp]
@@ -157,6 +158,13 @@ def tc_merge(p, X, metric, order, X_out, kept_idx, merge_dst, ws, stream=None):
     _check(load_library().tc_merge(ctypes.byref(p), _ptr(X, sd), _ptr(metric, sd), _ptr(order, torch.int32),
                                    _ptr(X_out, sd), _ptr(kept_idx, torch.int32), _ptr(merge_dst, torch.int32),
                                    _ptr(ws), ws.numel(), _stream(stream)))
+
+
+def tc_merge_noalloc(p, X, metric, order, X_out, kept_idx, merge_dst, stream=None):
+    sd = storage_dtype(p)
+    _check(load_library().tc_merge_noalloc(ctypes.byref(p), _ptr(X, sd), _ptr(metric, sd), _ptr(order, torch.int32),
+                                           _ptr(X_out, sd), _ptr(kept_idx, torch.int32),
+                                           _ptr(merge_dst, torch.int32), _stream(stream)))
 
 
 def tc_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, ws, O=None, score=None, order=None, info=None,

@@ -95,6 +95,7 @@ const char* tc_status_string(int status) {
     case TC_ERR_WORKSPACE: return "workspace too small";
     case TC_ERR_ALIGN: return "pointer not 16-byte aligned";
     case TC_ERR_HIP: return "HIP launch failed";
+    case TC_ERR_SCRATCH: return "sizes exceed the static scratch of tc_merge_noalloc (TC_NOALLOC_SCRATCH_BYTES)";
     default: return "unknown status";
   }
 }
