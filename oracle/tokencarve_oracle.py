@@ -212,15 +212,25 @@ def merge(X, metric, order, k_final, out_dtype=None):
     merged = np.array(sorted(rank[:m]), dtype=np.int64)
     for j in merged:
         merge_dst[set_b[j]] = best[j]
-    kept_idx = np.array(sorted(x for x in order if merge_dst[x] == x), dtype=np.int64)
+    kept_idx, X_out = average_rows(X, merge_dst, out_dtype)
+    return {"X_out": X_out, "kept_idx": kept_idx, "merge_dst": merge_dst,
+            "val": val, "best": best, "merged": merged, "set_a": set_a, "set_b": set_b}
+
+
+def average_rows(X, merge_dst, out_dtype=None):
+    """The averaging step of the merge for a given assignment: merge_dst[x] = -1 (pruned), x (output
+    row) or a (x is averaged into output row a).  Output row a is the unweighted mean of X[a] and of
+    every row sent to it; rows come out in ascending original position.  Returns (kept_idx, X_out)."""
+    X = np.asarray(X, dtype=np.float64)
+    merge_dst = np.asarray(merge_dst, dtype=np.int64)
+    kept_idx = np.nonzero(merge_dst == np.arange(len(merge_dst)))[0].astype(np.int64)
     X_out = np.zeros((len(kept_idx), X.shape[1]))
     for r, a in enumerate(kept_idx):
         members = np.nonzero(merge_dst == a)[0]   # a itself and everything merged into it
         X_out[r] = X[members].sum(axis=0) / len(members)
     if out_dtype is not None:
         X_out = to_storage(X_out, out_dtype)
-    return {"X_out": X_out, "kept_idx": kept_idx, "merge_dst": merge_dst,
-            "val": val, "best": best, "merged": merged, "set_a": set_a, "set_b": set_b}
+    return kept_idx, X_out
 
 
 # ----------------------------------------------------------------------------

@@ -12,6 +12,8 @@ def dev(a, p):
 
 
 def host(t):
+    if isinstance(t, np.ndarray):   # already on the host (the large configurations convert once, not per image)
+        return t
     return t.detach().to(torch.float32).cpu().numpy() if t.is_floating_point() else t.detach().cpu().numpy()
 
 
@@ -46,6 +48,16 @@ def select_topk(p, E_dev):
     tc.tc_select_topk(p, E_dev, order, ws)
     torch.cuda.synchronize()
     return order
+
+
+def similarity(p, metric_dev, order_dev):
+    ws = tc.new_workspace(p)
+    nA = p.k_prune // 2
+    nB = p.k_prune - nA
+    sim = torch.empty(p.batch, nB, max(nA, 1), dtype=torch.float32, device="cuda")
+    tc.tc_similarity(p, metric_dev, order_dev, sim, ws)
+    torch.cuda.synchronize()
+    return sim
 
 
 def merge(p, X_dev, metric_dev, order_dev):

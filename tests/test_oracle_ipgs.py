@@ -150,3 +150,31 @@ def test_gram_rounding_floor_is_reported_and_small_for_tiny(seed):
     O = orc.to_storage(Z, w.dtype)
     assert orc.gram_precision_floor(O, np.float64) < 1e-6
     assert orc.min_relative_gap(orc.ics(O)[1]) > 0
+
+
+def test_min_relative_gap_closed_form():
+    # gaps 3, 0.5 (and 6.5 down to the negligible value): relative to sigma_1 = 10 the smallest is 0.05;
+    # values below floor * sigma_1 do not count
+    s = np.array([10.0, 7.0, 6.5, 1e-9])
+    assert orc.min_relative_gap(s) == pytest.approx(0.05, rel=1e-12)
+    assert orc.min_relative_gap(s, floor=1e-12) == pytest.approx(0.05, rel=1e-12)          # 6.5 - 1e-9 is not smaller
+    assert orc.min_relative_gap(np.array([10.0, 7.0, 6.5, 6.4]), floor=0.69) == pytest.approx(0.3, rel=1e-12)  # only 10 and 7 lie above 6.9
+    assert orc.min_relative_gap(np.array([4.0, 4.0, 1.0])) == 0.0                           # a repeated value
+    assert orc.min_relative_gap(np.array([5.0])) == np.inf
+    # scaling the spectrum does not change a relative gap
+    assert orc.min_relative_gap(1e6 * s) == pytest.approx(orc.min_relative_gap(s), rel=1e-12)
+
+
+def test_gram_precision_floor_closed_form():
+    # Orthogonal rows: G is diagonal, C(x) = ||O_x|| = sqrt(G_xx), so rounding G to float32 changes C(x) by
+    # sqrt(fl32(G_xx)) / sqrt(G_xx) - 1 and nothing else.  Row 0 = 3 (1, 2^-13): G_00 = 9 (1 + 2^-26) rounds to 9
+    # in float32 (half a unit in the last place of 9 is 2^-21 > 9 * 2^-26), row 1 has G_11 = 4 exactly.  Every
+    # entry of O itself is a float32 number: rounding O instead of G would report 0.
+    O = np.zeros((2, 4))
+    O[0, 0], O[0, 1] = 3.0, 3.0 * 2.0 ** -13
+    O[1, 2] = 2.0
+    expect = 1.0 - 1.0 / np.sqrt(1.0 + 2.0 ** -26)     # relative, not absolute (which would be three times that)
+    assert orc.gram_precision_floor(O, np.float32) == pytest.approx(expect, rel=1e-6)
+    assert orc.gram_precision_floor(O, np.float64) < 1e-15
+    # the largest change over the tokens is reported: swapping the rows changes nothing
+    assert orc.gram_precision_floor(O[::-1].copy(), np.float32) == pytest.approx(expect, rel=1e-6)
