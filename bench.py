@@ -3,7 +3,7 @@
 
 One step = one tc_compress call (attention output -> IPGS score -> prune -> merge) over one batch of
 synthetic LLaVA-1.5-7B-shaped inputs (batch 64, 576 visual + 64 text tokens, D = 4096, bf16,
-576 -> 128 -> 64 tokens), inputs resident in HBM.  Prints ONE JSON line.
+576 -> 128 -> 64 tokens), inputs resident in HBM, library default parameters.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llava7b_b64] [--no-cpu-baseline]
 """
@@ -18,40 +18,53 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_FP64_MFMA_TFLOPS = 78.6   # MI355X dense fp64 matrix-core peak
-PEAK_FP32_MFMA_TFLOPS = 157.3
-PEAK_FP64_VECTOR_TFLOPS = 78.6  # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz
-PEAK_FP32_VECTOR_TFLOPS = 157.3
-FULL_EVERY = 6                   # one rotation launch in six sweeps all 64 indices of its pair (csrc/jacobi.hip)
+PEAK = {"hbm_gbps": 8000.0, "mfma_bf16": 2500.0, "mfma_f64": 78.6, "mfma_f32": 157.3, "vec_f64": 78.6, "vec_f32": 157.3}
+FULL_EVERY = 6   # Jacobi method: one rotation launch in six sweeps all 64 indices of its pair (csrc/jacobi.hip)
+
+
+# ---- algorithmic work per batch (what the method must move or compute; derivations in the design doc) -------------
+def work_model(w):
+    B, N, D, H, dh, Ls = w.batch, w.n_vis, w.hidden, w.n_heads, w.head_dim, w.n_sys
+    es = 4 if w.dtype == "f32" else 2
+    kp, kf = w.k_prune, w.k_final
+    nA = kp // 2
+    nB = kp - nA
+    pairs = N * Ls + N * (N + 1) // 2 if w.causal else N * (Ls + N + w.n_prompt)     # (query, key) pairs per head
+    keys = Ls + N if w.causal else Ls + N + w.n_prompt
+    return {
+        # Eq. 3-1/3-2: QK^T and PV, 2 * 2 * d_h flops per pair
+        "attn_flops": B * H * pairs * 4 * dh,
+        "attn_bytes": B * es * D * (N + 2 * keys + N),            # Q rows, K and V rows, O written
+        # Gram: lower triangle of 2 N^2 D
+        "gram_flops": B * N * N * D,
+        "gram_bytes": B * (es * N * D + 8 * N * N),
+        # reduction to tridiagonal form: per column the symmetric trailing matrix once (its lower half),
+        # plus the rank-2 updates (read and write of the lower half once per column pair v, w): N^3/6 * 8 * (1 + 2/nb)
+        "tridiag_bytes": B * 8 * sum((N - j - 1) * (N - j) // 2 for j in range(N - 1)),
+        "tridiag_flops": B * 4 * N ** 3 // 3,
+        # twisted factorisations: pivots and multipliers written and read once (2 * 8 N^2 each way), vectors written (4 N^2)
+        "twisted_bytes": B * N * N * (16 + 16 + 4),
+        # back-transformation: 4 N^3 / 2 ... each reflector touches (N-j-1) rows of N columns, 4 flops each
+        "backtf_flops": B * 4 * N * sum(N - j - 1 for j in range(N - 1)),
+        "backtf_bytes": B * N * N * (4 + 4),                      # vectors of T and reflectors read once
+        # Eq. 3-10 similarity and the merge
+        "sim_flops": B * 2 * nA * nB * D,
+        "sim_bytes": B * (kp * D * es + 4 * nA * nB),
+        "rownorm_bytes": B * kp * D * es,
+        "average_bytes": B * (kp + kf) * w.hidden * es,
+        # Jacobi method (when it runs): Eq. 3-6 reads U once
+        "ics_bytes": B * 4 * N * N,
+    }
 
 
 def jacobi_solve_flops_per_image_sweep(n_vis):
-    """Algorithmic flops of the rotation kernel for one image and sweep.
-
-    One step of a pair's 64x64 subproblem applies 32 disjoint plane rotations from both sides to the
-    symmetric S (528 2x2 blocks of its upper triangle, 4 results of 2 x 3 flops each) and from the right
-    to the accumulated R (4096 entries, 3 flops each).  A launch runs 32 such steps (63 at every
-    FULL_EVERY-th step of a sweep); a sweep has Np/32 - 1 launches of Np/64 pairs.
-    """
+    """Rotation kernel of the Jacobi method: one step of a pair's 64x64 subproblem applies 32 plane rotations from
+    both sides to the symmetric S (528 2x2 blocks, 24 flops each) and from the right to R (4096 entries, 3 flops)."""
     np_ = (n_vis + 63) // 64 * 64
     P, steps = np_ // 64, np_ // 32 - 1
     per_step = 528 * 24 + 4096 * 3
     full = len(range(0, steps, FULL_EVERY))
     return P * per_step * (full * 63 + (steps - full) * 32)
-
-
-def jacobi_update_flops_per_image_step(n_vis):
-    """Algorithmic flops of one block-Jacobi tile-update step of G for one image.
-
-    b = 32, a pair tile is 64x64.  With P pairs, symmetry leaves the P(P-1)/2 tiles I < J of G to
-    this kernel, each two 64x64x64 products (R_I^T G_IJ, then times R_J); the P tiles on the block
-    diagonal come back from the rotation kernel, which holds them rotated at its end.  (The float32
-    eigenvector update is a separate kernel: (Np/64) x P tiles with one product each.)
-    """
-    np_ = (n_vis + 63) // 64 * 64
-    P = np_ // 64
-    gemm = 2 * 64 ** 3
-    return P * (P - 1) // 2 * 2 * gemm
 
 
 def main():
@@ -60,15 +73,14 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llava7b_b64")
-    ap.add_argument("--eig", default="f64", choices=["f64", "f32"])
-    ap.add_argument("--sweeps", type=int, default=0,
-                    help="eigensolver sweeps to launch; 0 = find the number the slowest image needs with one untimed run")
-    ap.add_argument("--groups", type=int, default=0, help="eigensolver stream groups (0 = library default, 1 = one stream)")
+    ap.add_argument("--method", default="auto", choices=["auto", "jacobi", "tridiagonal"])
+    ap.add_argument("--groups", type=int, default=0, help="Jacobi method: stream groups (0 = library default, 1 = one stream)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path-only", action="store_true",
-                    help="skip the timings of the entry points beyond the compression path (keeps kernel traces clean)")
+                    help="time the compression path only: no rate probe, no other workloads or methods, no entry points "
+                         "beyond the path (keeps kernel traces clean)")
     ap.add_argument("--cpu-sample", type=int, default=12, help="images timed through the CPU oracle")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -88,8 +100,8 @@ def main():
     t0 = time.time()
     batch = make_batch(w)
     gen_s = time.time() - t0
-    eig = tc.TC_EIG_F64 if args.eig == "f64" else tc.TC_EIG_F32
-    p = tc.params_for(w, eig_dtype=eig, stream_groups=args.groups)
+    method = {"auto": tc.TC_EIG_AUTO, "jacobi": tc.TC_EIG_JACOBI, "tridiagonal": tc.TC_EIG_TRIDIAGONAL}[args.method]
+    p = tc.params_for(w, eig_method=method, stream_groups=args.groups)
     sd = tc.storage_dtype(p)
 
     def dev(a):
@@ -98,10 +110,14 @@ def main():
     Q, K, V = dev(batch["Q"]), dev(batch["K"]), dev(batch["V"])
     X = dev(np.ascontiguousarray(batch["X"][:, w.n_sys:w.n_sys + w.n_vis]))
     B, N = w.batch, w.n_vis
-    X_out = torch.empty(B, w.k_final, w.hidden, dtype=sd, device="cuda")
-    kept = torch.empty(B, w.k_final, dtype=torch.int32, device="cuda")
-    dst = torch.empty(B, N, dtype=torch.int32, device="cuda")
-    info = torch.empty(B, dtype=torch.int32, device="cuda")
+
+    def outputs(pp):
+        return (torch.empty(B, pp.k_final, w.hidden, dtype=sd, device="cuda"),
+                torch.empty(B, pp.k_final, dtype=torch.int32, device="cuda"),
+                torch.empty(B, N, dtype=torch.int32, device="cuda"),
+                torch.empty(B, dtype=torch.int32, device="cuda"))
+
+    X_out, kept, dst, info = outputs(p)
     ws = tc.new_workspace(p)
     if args.copy_calib:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -110,67 +126,105 @@ def main():
         torch.cuda.synchronize()
         del src, dst_c
 
-    # How many eigensolver sweeps to launch.  The library default (30) enqueues launches that find every
-    # image converged and return at once; here the count is fixed to what the slowest image needs,
-    # found by one untimed run unless --sweeps gives it.  Convergence of every image is checked below.
-    if args.sweeps > 0:
-        p.jacobi_max_sweeps = args.sweeps
+    def timed_steps(pp, outs, wsp, steps, warmup):
+        """ms per tc_compress call, and host time per call spent enqueuing it."""
+        for _ in range(warmup):
+            tc.tc_compress(pp, Q, K, V, X, outs[0], outs[1], outs[2], wsp, info=outs[3])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        host = 0.0
+        for _ in range(steps):
+            h0 = time.perf_counter()
+            tc.tc_compress(pp, Q, K, V, X, outs[0], outs[1], outs[2], wsp, info=outs[3])
+            host += time.perf_counter() - h0
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, host * 1e3 / steps
+
+    # the timed region: library default parameters, nothing calibrated
     tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, info=info)
     torch.cuda.synchronize()
-    sweeps = info.cpu().numpy()
-    if (sweeps <= 0).any():
-        print("bench.py: eigensolver did not converge for some image: %s" % sweeps, file=sys.stderr)
+    status = info.cpu().numpy()
+    if (status <= 0).any():
+        print("bench.py: eigensolver failed for some image: %s" % status, file=sys.stderr)
         sys.exit(1)
-    p.jacobi_max_sweeps = int(sweeps.max())
     kept_ref = kept.clone()
-
-    for _ in range(args.warmup):
-        tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, info=info)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        tc.tc_compress(p, Q, K, V, X, X_out, kept, dst, ws, info=info)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step, host_ms = timed_steps(p, (X_out, kept, dst, info), ws, args.steps, args.warmup)
     if (info.cpu().numpy() <= 0).any() or not torch.equal(kept, kept_ref):
-        print("bench.py: timed runs disagree with the calibration run", file=sys.stderr)
+        print("bench.py: timed runs disagree with the first run", file=sys.stderr)
         sys.exit(1)
 
-    # per-kernel durations, measured live with HIP events on the launch stream
-    kinds, upd_by_sweep = tc.tc_profile_compress(p, Q, K, V, X, X_out, kept, dst, info, ws)
-    kinds, upd_by_sweep = tc.tc_profile_compress(p, Q, K, V, X, X_out, kept, dst, info, ws)
-    upd_ms, upd_launches = kinds["jacobi_update"]
-    tiles_done = kinds.pop("jacobi_update_tiles")[1]   # counted by the kernel: tiles between two converged block pairs are skipped
-    rot_steps = kinds.pop("jacobi_rotation_steps")[1]  # likewise: visits of converged block pairs apply no rotations
-    steps_per_sweep = (N + 63) // 64 * 2 - 1
-    per_img = jacobi_update_flops_per_image_step(N)
-    Pp = (N + 63) // 64
-    tiles_full = 0
-    for s in range(p.jacobi_max_sweeps):
-        active = int((sweeps > s).sum())            # images still iterating in sweep s
-        tiles_full += active * (Pp * (Pp - 1) // 2) * steps_per_sweep
-    flops = tiles_done * (per_img / max(Pp * (Pp - 1) // 2, 1))
-    achieved = flops / (upd_ms * 1e-3) / 1e12 if upd_launches else 0.0   # a single block pair (N <= 64) has no tile update
-    peak = PEAK_FP64_MFMA_TFLOPS if args.eig == "f64" else PEAK_FP32_MFMA_TFLOPS
-    # the rotation kernel: plain vector arithmetic (the float32 solver sweeps all 64 indices in every launch)
-    solve_ms, solve_launches = kinds["jacobi_solve"]
-    solve_flops = rot_steps * (528 * 24 + 4096 * 3)
-    if args.eig == "f64":
-        solve_full = jacobi_solve_flops_per_image_sweep(N)
+    # per-kernel durations, measured live with HIP events on the launch stream (kernels run one at a time)
+    kinds, _ = tc.tc_profile_compress(p, Q, K, V, X, X_out, kept, dst, info, ws)
+    kinds, _ = tc.tc_profile_compress(p, Q, K, V, X, X_out, kept, dst, info, ws)
+    tiles_done = kinds.pop("jacobi_update_tiles")[1]
+    rot_steps = kinds.pop("jacobi_rotation_steps")[1]
+    kernel_ms = {k: round(v[0], 4) for k, v in kinds.items() if v[1] > 0}
+    launches = {k: v[1] for k, v in kinds.items() if v[1] > 0}
+    wm = work_model(w)
+
+    def ms(k):
+        return kinds[k][0] if kinds[k][1] > 0 else None
+
+    def rate(work, k, unit):   # work / time of kernel kind k; unit "T" = 1e12 per s, "G" = 1e9 per s
+        t = ms(k)
+        return None if not t else work / (t * 1e-3) / (1e12 if unit == "T" else 1e9)
+
+    def entry(kernel, bound, achieved, peak, unit, **extra):
+        d = {"kernel": kernel, "bound": bound, "achieved": None if achieved is None else round(achieved, 3),
+             "peak": peak, "unit": unit, "frac": None if achieved is None else round(achieved / peak, 4)}
+        d.update(extra)
+        return d
+
+    # ---- per row of the path: achieved rate against the peak of the unit that bounds it -------------------
+    attn_t = rate(wm["attn_flops"], "attn", "T")
+    attn_ai = wm["attn_flops"] / wm["attn_bytes"]
+    attn_cap = min(PEAK["mfma_bf16"], attn_ai * PEAK["hbm_gbps"] / 1e3)       # TFLOP/s the HBM can feed at this intensity
+    per_row = {
+        "a1_a2_attention": entry("attn", "mfma", attn_t, PEAK["mfma_bf16"] if w.dtype != "f32" else PEAK["vec_f32"], "TFLOP/s",
+                                 ms=ms("attn"), flop_per_byte=round(attn_ai, 1),
+                                 frac_of_min_mfma_hbm=None if attn_t is None else round(attn_t / attn_cap, 4)),
+        "a3_gram": entry("gram", "mfma", rate(wm["gram_flops"], "gram", "T"), PEAK["mfma_f64"], "TFLOP/s", ms=ms("gram"),
+                         hbm_gbps=None if not ms("gram") else round(rate(wm["gram_bytes"], "gram", "G"), 1)),
+        "a8_similarity": entry("sim", "hbm", rate(wm["sim_bytes"], "sim", "G"), PEAK["hbm_gbps"], "GB/s", ms=ms("sim"),
+                               mfma_tflops=None if not ms("sim") else round(rate(wm["sim_flops"], "sim", "T"), 2)),
+        "a8_rownorm_gather": entry("rownorm", "hbm", rate(wm["rownorm_bytes"], "rownorm", "G"), PEAK["hbm_gbps"], "GB/s",
+                                   ms=ms("rownorm")),
+        "a9_average": entry("average", "hbm", rate(wm["average_bytes"], "average", "G"), PEAK["hbm_gbps"], "GB/s",
+                            ms=ms("average")),
+        "a7_topk": {"kernel": "topk", "bound": "lds/latency", "ms": ms("topk")},
+        "a9_assign": {"kernel": "assign", "bound": "lds/latency", "ms": ms("assign")},
+    }
+    if kinds["tridiag"][1] > 0:   # the tridiagonal route ran
+        per_row["a4_tridiagonal_reduction"] = entry("tridiag", "hbm", rate(wm["tridiag_bytes"], "tridiag", "G"), PEAK["hbm_gbps"],
+                                                    "GB/s", ms=ms("tridiag"))
+        per_row["a4_bisection"] = {"kernel": "bisect", "bound": "alu (float64 divisions, one lane per eigenvalue)", "ms": ms("bisect")}
+        per_row["a4_twisted_factorisation"] = entry("twisted", "hbm", rate(wm["twisted_bytes"], "twisted", "G"), PEAK["hbm_gbps"],
+                                                    "GB/s", ms=ms("twisted"))
+        per_row["a4_a5_backtransform_ics"] = entry("backtransform", "alu", rate(wm["backtf_flops"], "backtransform", "T"),
+                                                   PEAK["vec_f32"], "TFLOP/s", ms=ms("backtransform"))
     else:
-        solve_full = ((N + 63) // 64) * (528 * 24 + 4096 * 3) * 63 * steps_per_sweep
-    solve_full *= sum(int((sweeps > s).sum()) for s in range(p.jacobi_max_sweeps))
-    solve_achieved = solve_flops / (solve_ms * 1e-3) / 1e12
-    solve_peak = PEAK_FP64_VECTOR_TFLOPS if args.eig == "f64" else PEAK_FP32_VECTOR_TFLOPS
-    total_kernel_ms = sum(v[0] for v in kinds.values())
-    sustained = tc.tc_probe_rates()   # what this GPU delivers on register-only MFMA loops and a plain copy
-    traffic = None   # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
-    pmc = os.path.join(ROOT, "profiles", "jacobi_update_g.%s.pmc.txt" % w.name)
-    if os.path.exists(pmc) and args.eig == "f64":
+        per_row["a5_ics"] = entry("ics", "hbm", rate(wm["ics_bytes"], "ics", "G"), PEAK["hbm_gbps"], "GB/s", ms=ms("ics"))
+        solve_flops = rot_steps * (528 * 24 + 4096 * 3)
+        per_row["a4_jacobi_solve"] = entry("jacobi_solve", "alu", rate(solve_flops, "jacobi_solve", "T"), PEAK["vec_f64"], "TFLOP/s",
+                                           ms=ms("jacobi_solve"))
+        per_row["a4_jacobi_update_g"] = entry("jacobi_update", "mfma", rate(tiles_done * 4 * 64 ** 3, "jacobi_update", "T"),
+                                              PEAK["mfma_f64"], "TFLOP/s", ms=ms("jacobi_update"))
+        per_row["a4_jacobi_update_u"] = {"kernel": "jacobi_update_u", "bound": "mfma", "ms": ms("jacobi_update_u")}
+
+    # ---- roofline of the dominant kernel: the one with the largest summed time ------------------------------
+    dominant = max(kernel_ms, key=kernel_ms.get)
+    dom_row = next((v for v in per_row.values() if v.get("kernel") == dominant and "achieved" in v), None)
+    traffic = None   # HBM bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload, if any
+    pmc = os.path.join(ROOT, "profiles", "%s.%s.pmc.txt" % (dominant, w.name))
+    if os.path.exists(pmc):
         for line in open(pmc):
             if line.startswith("hbm_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
+    roofline = {"kernel": dominant, "bound": dom_row["bound"] if dom_row else None,
+                "achieved": dom_row["achieved"] if dom_row else None, "peak": dom_row["peak"] if dom_row else None,
+                "unit": dom_row["unit"] if dom_row else None, "frac": dom_row["frac"] if dom_row else None,
+                "traffic": traffic, "launches": launches[dominant],
+                "avg_launch_us": round(kernel_ms[dominant] * 1e3 / launches[dominant], 2)}
 
     out = {
         "metric": "images/sec compressed (576x4096 -> k_prune -> k_final tokens, batch 64)",
@@ -180,32 +234,49 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3),
+        "host_enqueue_ms_per_step": round(host_ms, 3),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 storage; fp32-accumulate bf16 MFMA (attention, similarity); %s Gram + eigensolver" % args.eig,
+        "dtype": "bf16 storage; fp32-accumulate bf16 MFMA (attention, similarity); f64 Gram + eigensolver",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "n_vis": N, "n_text": w.n_sys + w.n_prompt,
                    "hidden": w.hidden, "heads": w.n_heads, "head_dim": w.head_dim,
                    "k_prune": w.k_prune, "k_final": w.k_final, "lambda": w.lam, "causal": w.causal,
-                   "qkv": w.qkv_mode, "stream_groups": args.groups, "jacobi_max_sweeps": int(p.jacobi_max_sweeps),
-                   "sweeps_used_min_max": [int(sweeps.min()), int(sweeps.max())],
+                   "qkv": w.qkv_mode, "params": "library defaults", "eig_method": args.method,
+                   "eig_method_used": "tridiagonal" if kinds["tridiag"][1] > 0 else "jacobi",
+                   "eigensolver_status_min_max": [int(status.min()), int(status.max())],
                    "input_generation_s": round(gen_s, 1)},
-        "roofline": {"kernel": "jacobi_update", "bound": "mfma", "achieved": round(achieved, 3), "peak": peak,
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
-                     "avg_launch_us": round(upd_ms * 1e3 / max(upd_launches, 1), 2), "launches": upd_launches,
-                     "tiles_processed": tiles_done, "tiles_without_skipping": tiles_full,
-                     "frac_of_sustained_mfma": round(achieved / sustained["mfma_f64_tflops" if args.eig == "f64" else "mfma_f32_tflops"], 4)},
-        "roofline_alu": {"kernel": "jacobi_solve", "bound": "alu", "achieved": round(solve_achieved, 3),
-                         "peak": solve_peak, "unit": "TFLOP/s", "frac": round(solve_achieved / solve_peak, 4),
-                         "avg_launch_us": round(solve_ms * 1e3 / max(solve_launches, 1), 2),
-                         "launches": solve_launches, "flops_counted": solve_flops, "flops_without_skipping": solve_full},
-        "sustained_rates": {k: round(v, 1) for k, v in sustained.items()},
-        "kernel_ms": {k: round(v[0], 3) for k, v in kinds.items()},
-        "kernel_ms_total": round(total_kernel_ms, 3),
+        "roofline": roofline,
+        "per_row": per_row,
+        "kernel_ms": kernel_ms,
+        "kernel_launches": launches,
+        "kernel_ms_total": round(sum(kernel_ms.values()), 3),
     }
 
     if not args.path_only:
+        out["sustained_rates"] = {k: round(v, 1) for k, v in tc.tc_probe_rates().items()}
+        # the counts of the metric string (576 -> 256 -> 192 tokens) at the same batch
+        p2 = tc.params_for(w.with_(k_prune=256, k_final=192), eig_method=method, stream_groups=args.groups)
+        o2 = outputs(p2)
+        ms2, _ = timed_steps(p2, o2, ws if tc.tc_workspace_bytes(p2) <= ws.numel() else tc.new_workspace(p2), max(args.steps // 2, 3), 2)
+        out["metric_string_counts"] = {"k_prune": 256, "k_final": 192, "ms_per_step": round(ms2, 3),
+                                       "value": round(B / (ms2 * 1e-3), 2), "unit": "images/s"}
+        # the iterative method on the same workload: default parameters (30 sweeps enqueued, converged images skip)
+        # and with the sweep count set to what the slowest image needed
+        pj = tc.params_for(w, eig_method=tc.TC_EIG_JACOBI, stream_groups=args.groups)
+        oj = outputs(pj)
+        wj = tc.new_workspace(pj)
+        msj, hostj = timed_steps(pj, oj, wj, max(args.steps // 4, 3), 1)
+        sweeps = oj[3].cpu().numpy()
+        jac = {"ms_per_step_default_params": round(msj, 3), "host_enqueue_ms_default_params": round(hostj, 3),
+               "sweeps_used_min_max": [int(sweeps.min()), int(sweeps.max())]}
+        if (sweeps > 0).all():
+            pj.jacobi_max_sweeps = int(sweeps.max())
+            msc, hostc = timed_steps(pj, oj, wj, max(args.steps // 4, 3), 1)
+            jac.update({"ms_per_step_calibrated_sweeps": round(msc, 3), "host_enqueue_ms_calibrated": round(hostc, 3)})
+        out["jacobi_method"] = jac
+        del wj
         next_rows(args, tc, torch, w, p, batch, dev, sd, Q, K, V, X, X_out, kept, dst, info, ws, out)
 
     if not args.no_cpu_baseline:

@@ -65,6 +65,12 @@ typedef enum { TC_NORM_NONE = 0, TC_NORM_MINMAX = 1 } tc_norm;
 /* arithmetic of the Gram matrix and of the eigenvalue iteration (the eigenvectors are accumulated in
    float32 either way); TC_EIG_F32 is only accurate enough for well-conditioned spectra */
 typedef enum { TC_EIG_F64 = 0, TC_EIG_F32 = 1 } tc_eig_dtype;
+/* how the eigen-decomposition of the Gram matrix (the SVD of Section 3.3.1) is computed:
+   TC_EIG_TRIDIAGONAL  Householder reduction to tridiagonal form, eigenvalues by bisection, eigenvectors from
+                       twisted factorisations, back-transformation; float64 only, n_vis <= 1024;
+   TC_EIG_JACOBI       two-sided block Jacobi iteration (any n_vis, float64 or float32);
+   TC_EIG_AUTO         the tridiagonal route where it applies, else Jacobi */
+typedef enum { TC_EIG_AUTO = 0, TC_EIG_JACOBI = 1, TC_EIG_TRIDIAGONAL = 2 } tc_eig_method;
 
 typedef struct {
   int32_t batch;        /* B >= 0 (B == 0: nothing is launched, TC_OK)                         */
@@ -82,12 +88,13 @@ typedef struct {
   float sv_rtol;        /* Eq. 3-6 drops terms with sigma_i <= sv_rtol * sigma_max; 0 keeps all */
   int32_t k_prune;      /* k_p: 1 <= k_final <= k_prune <= n_vis, k_prune - k_final <= |B|      */
   int32_t k_final;      /* k_f                                                                  */
-  int32_t jacobi_max_sweeps; /* 0 => 30                                                         */
+  int32_t jacobi_max_sweeps; /* 0 => 30 (Jacobi method only)                                    */
   float jacobi_tol;     /* an image stops after the first sweep that leaves off(G)/||G||_F < tol
                            (off = Frobenius norm of the off-diagonal part);
-                           0 => 2e-9 (3e-6 for TC_EIG_F32)                                      */
+                           0 => 2e-9 * min(1, 576 / N) (3e-6 for TC_EIG_F32)                    */
   int32_t eig_dtype;    /* tc_eig_dtype                                                         */
-  int32_t stream_groups; /* eigensolver: 0 = cut the batch into 1, 2 or 4 groups (by the amount of work) that
+  int32_t eig_method;   /* tc_eig_method; TC_EIG_TRIDIAGONAL with TC_EIG_F32 or n_vis > 1024 is rejected (TC_ERR_PARAM) */
+  int32_t stream_groups; /* Jacobi eigensolver: 0 = cut the batch into 1, 2 or 4 groups (by the amount of work) that
                             run on helper streams and overlap; 1 = everything on `stream`; 2..4 = that many groups */
 } tc_params;
 
@@ -116,8 +123,11 @@ TC_API int tc_attn_output(const tc_params* p, const void* Q, const void* K, cons
  *   score       [B, N] float  E of Eq. 3-8
  *   ics         [B, N] float  C of Eq. 3-6 (before any normalisation); optional (NULL)
  *   sigma       [B, N] float  singular values, descending; optional
- *   info        [B] int32     number of Jacobi sweeps used, negated if the tolerance was not
- *                             reached within jacobi_max_sweeps; optional
+ *   info        [B] int32     > 0: done, < 0: failed, never 0.  Jacobi method: the number of sweeps used
+ *                             (1 for an all-zero matrix, which needs none), negated if the tolerance was
+ *                             not reached within jacobi_max_sweeps.  Tridiagonal method: 1, or -1 if an
+ *                             eigenvector came out non-finite or two eigenvalues closer than 1e-10 of the
+ *                             spectral norm could not be given independent vectors.  Optional
  */
 TC_API int tc_ipgs_score(const tc_params* p, const void* O, const float* attn_score, float* score,
                   float* ics, float* sigma, int32_t* info, void* ws, size_t ws_bytes, void* stream);
@@ -130,6 +140,17 @@ TC_API int tc_ipgs_score(const tc_params* p, const void* O, const float* attn_sc
  */
 TC_API int tc_select_topk(const tc_params* p, const float* score, int32_t* order, void* ws,
                    size_t ws_bytes, void* stream);
+
+/*
+ * Eq. 3-10 on its own: SetA = order[0 : k_p/2], SetB = the rest (Eq. 3-9);
+ *     sim[b, j, i] = <z_Bj, z_Ai> / (|z_Bj| |z_Ai|),   z = rows of `metric`, |z| >= 1e-30 enforced.
+ *   metric  [B, N, D] dtype            (the attention output O)
+ *   order   [B, k_prune] int32         from tc_select_topk; an entry outside [0, N) is clamped
+ *   sim     [B, |B|, |A|] float        written; nothing is written when |A| = 0 (k_prune = 1)
+ * tc_merge computes the same matrix into its workspace.
+ */
+TC_API int tc_similarity(const tc_params* p, const void* metric, const int32_t* order, float* sim, void* ws,
+                         size_t ws_bytes, void* stream);
 
 /*
  * Stage II (Section 3.3.2).  SetA = order[0 : k_p/2], SetB = the rest (Eq. 3-9); cosine
@@ -189,7 +210,8 @@ TC_API int tc_compress(const tc_params* p, const void* Q, const void* K, const v
 typedef enum {
   TC_PROF_ATTN = 0, TC_PROF_ATTN_REDUCE, TC_PROF_GRAM, TC_PROF_JACOBI_INIT, TC_PROF_JACOBI_SOLVE,
   TC_PROF_JACOBI_UPDATE, TC_PROF_JACOBI_UPDATE_U, TC_PROF_JACOBI_SWEEP_END, TC_PROF_SIGMA, TC_PROF_ICS, TC_PROF_COMBINE, TC_PROF_TOPK,
-  TC_PROF_ROWNORM, TC_PROF_SIM, TC_PROF_ASSIGN, TC_PROF_AVERAGE, TC_PROF_KINDS
+  TC_PROF_ROWNORM, TC_PROF_SIM, TC_PROF_ASSIGN, TC_PROF_AVERAGE, TC_PROF_TRIDIAG, TC_PROF_BISECT, TC_PROF_TWISTED,
+  TC_PROF_BACKTRANSFORM, TC_PROF_KINDS
 } tc_prof_kind;
 TC_API int tc_profile_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X,
                                void* X_out, int32_t* kept_idx, int32_t* merge_dst, int32_t* info, void* ws,
@@ -254,7 +276,7 @@ TC_API double tc_kv_cache_fraction(int32_t n_text, int32_t n_vis, int32_t n_kept
 /*
  * Measurement aid: sustained rates of this GPU, for reading roofline fractions against what the part
  * actually delivers.  Runs register-only loops of independent matrix-core products (fp64 16x16x4,
- * fp32 16x16x4, bf16 32x32x16) and a streaming copy of 128 MiB inside `ws` (ws_bytes >= 256 MiB,
+ * fp32 16x16x4, bf16 32x32x16) and a streaming copy of 1 GiB inside `ws` (ws_bytes >= 2 GiB,
  * contents destroyed), waits for them, and writes to the HOST array rates[5]:
  * TFLOP/s fp64 (16x16x4), TFLOP/s fp32, TFLOP/s bf16, GB/s copied (read + written), TFLOP/s fp64 with
  * the 4x4x4 four-block product.  Blocks the calling thread.

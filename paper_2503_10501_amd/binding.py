@@ -17,12 +17,14 @@ TC_F32, TC_BF16, TC_F16 = 0, 1, 2
 _DTYPES = {"f32": TC_F32, "bf16": TC_BF16, "f16": TC_F16}
 TC_NORM_NONE, TC_NORM_MINMAX = 0, 1
 TC_EIG_F64, TC_EIG_F32 = 0, 1
+TC_EIG_AUTO, TC_EIG_JACOBI, TC_EIG_TRIDIAGONAL = 0, 1, 2
 
 SYMBOLS = ("tc_workspace_bytes", "tc_status_string", "tc_attn_output", "tc_ipgs_score", "tc_select_topk",
-           "tc_merge", "tc_merge_noalloc", "tc_compress", "tc_profile_compress", "tc_probe_rates", "tc_info_rank",
+           "tc_merge", "tc_merge_noalloc", "tc_similarity", "tc_compress", "tc_profile_compress", "tc_probe_rates", "tc_info_rank",
            "tc_assemble_sequence", "tc_kv_cache_fraction")
 PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_update_u", "jacobi_sweep_end",
-              "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average")
+              "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average", "tridiag", "bisect", "twisted",
+              "backtransform")
 
 
 class TokenCarveError(RuntimeError):
@@ -39,16 +41,16 @@ class tc_params(ctypes.Structure):
         ("softmax_scale", ctypes.c_float), ("lambda_", ctypes.c_float), ("norm_mode", ctypes.c_int32),
         ("sv_rtol", ctypes.c_float), ("k_prune", ctypes.c_int32), ("k_final", ctypes.c_int32),
         ("jacobi_max_sweeps", ctypes.c_int32), ("jacobi_tol", ctypes.c_float), ("eig_dtype", ctypes.c_int32),
-        ("stream_groups", ctypes.c_int32),
+        ("eig_method", ctypes.c_int32), ("stream_groups", ctypes.c_int32),
     ]
 
 
 def make_params(batch, seq_len, vis_start, n_vis, n_heads, head_dim, hidden_dim, dtype, k_prune, k_final,
                 lam=0.5, causal=1, norm_mode=TC_NORM_MINMAX, sv_rtol=0.0, softmax_scale=0.0,
-                jacobi_max_sweeps=0, jacobi_tol=0.0, eig_dtype=TC_EIG_F64, stream_groups=0):
+                jacobi_max_sweeps=0, jacobi_tol=0.0, eig_dtype=TC_EIG_F64, stream_groups=0, eig_method=0):
     return tc_params(batch, seq_len, vis_start, n_vis, n_heads, head_dim, hidden_dim, dtype, causal,
                      softmax_scale, lam, norm_mode, sv_rtol, k_prune, k_final, jacobi_max_sweeps, jacobi_tol,
-                     eig_dtype, stream_groups)
+                     eig_dtype, eig_method, stream_groups)
 
 
 def params_for(w, batch=None, **overrides):
@@ -83,6 +85,7 @@ def load_library():
     lib.tc_select_topk.argtypes = [pp, vp, vp, vp, sz, vp]
     lib.tc_merge.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_merge_noalloc.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp]
+    lib.tc_similarity.argtypes = [pp, vp, vp, vp, vp, sz, vp]
     lib.tc_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.tc_profile_compress.argtypes = [pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, ctypes.c_int32, vp]
     lib.tc_probe_rates.argtypes = [vp, sz, vp, vp]
@@ -167,6 +170,11 @@ def tc_merge_noalloc(p, X, metric, order, X_out, kept_idx, merge_dst, stream=Non
                                            _ptr(merge_dst, torch.int32), _stream(stream)))
 
 
+def tc_similarity(p, metric, order, sim, ws, stream=None):
+    _check(load_library().tc_similarity(ctypes.byref(p), _ptr(metric, storage_dtype(p)), _ptr(order, torch.int32),
+                                        _ptr(sim, torch.float32), _ptr(ws), ws.numel(), _stream(stream)))
+
+
 def tc_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, ws, O=None, score=None, order=None, info=None,
                 stream=None):
     sd = storage_dtype(p)
@@ -199,7 +207,7 @@ def tc_profile_compress(p, Q, K, V, X, X_out, kept_idx, merge_dst, info, ws, max
 
 def tc_probe_rates(stream=None):
     """Sustained {fp64, fp32, bf16} matrix-core TFLOP/s and streaming-copy GB/s of the current GPU."""
-    ws = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(1 << 31, dtype=torch.uint8, device="cuda")
     rates = (ctypes.c_float * 5)()
     _check(load_library().tc_probe_rates(_ptr(ws), ws.numel(), _stream(stream), rates))
     return {"mfma_f64_tflops": float(rates[0]), "mfma_f32_tflops": float(rates[1]),

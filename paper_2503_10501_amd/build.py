@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtokencarve.so")
-SOURCES = ["api.hip", "attn.hip", "gram.hip", "jacobi.hip", "scores.hip", "topk.hip", "merge.hip", "profile.hip", "probe.hip", "rank.hip", "sequence.hip", "noalloc.hip"]
+SOURCES = ["api.hip", "attn.hip", "gram.hip", "jacobi.hip", "scores.hip", "topk.hip", "merge.hip", "profile.hip", "probe.hip", "rank.hip", "sequence.hip", "noalloc.hip", "tridiag.hip", "tdeig.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-value", "-Wno-unknown-warning-option",

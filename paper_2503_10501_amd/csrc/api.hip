@@ -18,8 +18,12 @@ int make_plan(const tc_params* p, Plan* pl) {
   if (!(p->lambda >= 0.f && p->lambda <= 1.f) || (p->norm_mode != TC_NORM_NONE && p->norm_mode != TC_NORM_MINMAX) ||
       !(p->sv_rtol >= 0.f && p->sv_rtol < 1.f) || (p->causal != 0 && p->causal != 1) || !(p->softmax_scale >= 0.f) ||
       !std::isfinite(p->softmax_scale) || p->jacobi_max_sweeps < 0 || p->jacobi_max_sweeps > 1000 ||
-      !(p->jacobi_tol >= 0.f) || !(p->jacobi_tol < 1.f) || p->stream_groups < 0 || p->stream_groups > 4)
+      !(p->jacobi_tol >= 0.f) || !(p->jacobi_tol < 1.f) || p->stream_groups < 0 || p->stream_groups > 4 ||
+      p->eig_method < TC_EIG_AUTO || p->eig_method > TC_EIG_TRIDIAGONAL)
     return TC_ERR_PARAM;
+  // the tridiagonal route works in float64 and keeps its panels in the LDS of one compute unit
+  const bool direct_ok = p->eig_dtype == TC_EIG_F64 && p->n_vis <= 1024 && tridiag_panel_width(p->n_vis) >= 4;
+  if (p->eig_method == TC_EIG_TRIDIAGONAL && !direct_ok) return TC_ERR_PARAM;
   if (p->k_final < 1 || p->k_final > p->k_prune || p->k_prune > p->n_vis) return TC_ERR_PARAM;
   const int nA = p->k_prune / 2, nB = p->k_prune - nA;
   if (p->k_prune - p->k_final > nB) return TC_ERR_PARAM;
@@ -33,8 +37,12 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.esize = p->dtype == TC_F32 ? 4 : 2;
   q.tsize = p->eig_dtype == TC_EIG_F64 ? 8 : 4;
   q.groups = p->stream_groups;
+  q.method = (p->eig_method == TC_EIG_JACOBI || !direct_ok) ? TC_EIG_JACOBI : TC_EIG_TRIDIAGONAL;
   q.max_sweeps = p->jacobi_max_sweeps > 0 ? p->jacobi_max_sweeps : 30;
-  q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 2e-9 : 3e-6);
+  // The error of Eq. 3-6 grows like off(G) / (gap between neighbouring eigenvalues), and with more tokens the
+  // gaps shrink like 1/N: the default tolerance found at N = 576 is scaled accordingly for larger N.
+  const double tol_scale = q.Np > 576 ? 576.0 / q.Np : 1.0;
+  q.tol = p->jacobi_tol > 0.f ? (double)p->jacobi_tol : (p->eig_dtype == TC_EIG_F64 ? 2e-9 * tol_scale : 3e-6);
   q.scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / std::sqrt((float)q.dh);
 
   size_t off = 0;
@@ -56,8 +64,41 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.off_sim = take(B * (size_t)q.nB * (q.nA > 0 ? q.nA : 1) * 4);
   q.off_mlist = take(B * (size_t)(q.m > 0 ? q.m : 1) * 8);
   q.off_info = take(B * 4);
+  if (q.method == TC_EIG_TRIDIAGONAL) {
+    const size_t nstrip = (N + 63) / 64;
+    q.off_td_d = take(B * Np * 8);
+    q.off_td_e = take(B * Np * 8);
+    q.off_td_tau = take(B * Np * 4);
+    q.off_td_lam = take(B * Np * 8);
+    q.off_td_blk = take(B * Np * 8);
+    q.off_td_tnorm = take(B * 8);
+    q.off_td_rn = take(B * Np * 8);
+    q.off_td_bad = take(B * 4);
+    q.off_td_wgt = take(B * Np * 8);
+    q.off_td_W = take(B * Np * Np * 4);        // eigenvectors of T (the reflectors use the region of U)
+    q.off_td_tw = take(B * Np * Np * 16);      // pivots and multipliers of the twisted factorisations
+    q.off_td_Cpart = take(B * nstrip * Np * 8);
+  }
   q.total = off > 0 ? off : 256;
   return TC_OK;
+}
+
+// Eigenvalues (and, with `vectors`, Eq. 3-6) of the Gram matrices in the workspace by the tridiagonal route.
+static int direct_chain(const Plan& pl, const tc_params* p, bool vectors, float* C_ws, float* ics, float* sigma,
+                        int32_t* info, void* ws, hipStream_t st) {
+  double* G = at<double>(ws, pl.off_G);
+  double* dvec = at<double>(ws, pl.off_td_d);
+  double* evec = at<double>(ws, pl.off_td_e);
+  float* tauv = at<float>(ws, pl.off_td_tau);
+  float* Vc = at<float>(ws, pl.off_U);
+  int rc = launch_tridiag(pl, G, dvec, evec, tauv, Vc, st);
+  if (rc != TC_OK) return rc;
+  double* tw = at<double>(ws, pl.off_td_tw);
+  return launch_td_eigen(pl, dvec, evec, tauv, Vc, at<double>(ws, pl.off_td_lam), at<int2>(ws, pl.off_td_blk),
+                         at<double>(ws, pl.off_td_tnorm), tw, tw + (size_t)pl.B * pl.Np * pl.Np, at<float>(ws, pl.off_td_W),
+                         at<double>(ws, pl.off_td_rn), at<int32_t>(ws, pl.off_td_bad), at<double>(ws, pl.off_sig),
+                         at<double>(ws, pl.off_td_wgt), at<double>(ws, pl.off_td_Cpart), p->sv_rtol, vectors, C_ws, ics,
+                         sigma, info, st);
 }
 
 static int ipgs_chain(const Plan& pl, const tc_params* p, const void* O, const float* S, float* score, float* ics,
@@ -67,10 +108,20 @@ static int ipgs_chain(const Plan& pl, const tc_params* p, const void* O, const f
   EigState* state = at<EigState>(ws, pl.off_state);
   int rc = launch_gram(pl, p->dtype, p->eig_dtype, O, G, st);
   if (rc != TC_OK) return rc;
+  if (pl.method == TC_EIG_TRIDIAGONAL) {
+    float* C_ws = at<float>(ws, pl.off_C);
+    rc = direct_chain(pl, p, true, C_ws, ics, sigma, info, ws, st);
+    if (rc != TC_OK) return rc;
+    return launch_combine(pl, C_ws, S, p->lambda, p->norm_mode, score, st);
+  }
   rc = launch_jacobi(pl, p->eig_dtype, G, U, at<char>(ws, pl.off_R), at<double>(ws, pl.off_offpart), state, st);
   if (rc != TC_OK) return rc;
   return launch_scores(pl, p->eig_dtype, G, U, state, S, p->lambda, p->norm_mode, p->sv_rtol, at<char>(ws, pl.off_sig),
                        at<float>(ws, pl.off_C), score, ics, sigma, info, st);
+}
+
+int direct_eigenvalues(const Plan& pl, const tc_params* p, float* sigma, int32_t* info, void* ws, hipStream_t st) {
+  return direct_chain(pl, p, false, nullptr, nullptr, sigma, info, ws, st);
 }
 
 }  // namespace tc
@@ -152,6 +203,18 @@ int tc_merge(const tc_params* p, const void* X, const void* metric, const int32_
   if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
   return launch_merge(pl, p->dtype, X, metric, order, X_out, kept_idx, merge_dst, at<float>(ws, pl.off_rnorm),
                       at<float>(ws, pl.off_sim), at<int32_t>(ws, pl.off_mlist), (hipStream_t)stream);
+}
+
+int tc_similarity(const tc_params* p, const void* metric, const int32_t* order, float* sim, void* ws, size_t ws_bytes,
+                  void* stream) {
+  Plan pl;
+  int rc = make_plan(p, &pl);
+  if (rc != TC_OK) return rc;
+  if (pl.B == 0) return TC_OK;  // an empty batch: nothing to check, nothing to launch
+  if (!metric || !order || !sim) return TC_ERR_NULL;
+  if (misaligned(metric) || misaligned(order) || misaligned(sim)) return TC_ERR_ALIGN;
+  if ((rc = check_ws(pl, ws, ws_bytes)) != TC_OK) return rc;
+  return launch_similarity(pl, p->dtype, metric, order, at<float>(ws, pl.off_rnorm), sim, (hipStream_t)stream);
 }
 
 int tc_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X, void* X_out,

@@ -893,6 +893,7 @@ __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* _
 constexpr int MAX_GROUPS = 4;
 struct StreamPool {
   hipStream_t s[MAX_GROUPS - 1];
+  hipEvent_t fork, join[MAX_GROUPS - 1];  // re-recorded by every call (a wait captures the state at the time it is enqueued)
   bool ok = false;
 };
 static std::mutex g_pool_mutex;
@@ -904,8 +905,23 @@ static StreamPool* helper_streams() {
   std::lock_guard<std::mutex> lock(g_pool_mutex);
   StreamPool& pool = g_pools[dev];
   if (!pool.ok) {
-    for (int i = 0; i < MAX_GROUPS - 1; i++)
-      if (hipStreamCreateWithFlags(&pool.s[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
+    int ns = 0, ne = 0;
+    bool good = hipEventCreateWithFlags(&pool.fork, hipEventDisableTiming) == hipSuccess;
+    const bool have_fork = good;
+    while (good && ns < MAX_GROUPS - 1) {
+      good = hipStreamCreateWithFlags(&pool.s[ns], hipStreamNonBlocking) == hipSuccess;
+      if (good) ns++;
+    }
+    while (good && ne < MAX_GROUPS - 1) {
+      good = hipEventCreateWithFlags(&pool.join[ne], hipEventDisableTiming) == hipSuccess;
+      if (good) ne++;
+    }
+    if (!good) {  // release what was created; the caller falls back to one stream
+      if (have_fork) (void)hipEventDestroy(pool.fork);
+      for (int i = 0; i < ns; i++) (void)hipStreamDestroy(pool.s[i]);
+      for (int i = 0; i < ne; i++) (void)hipEventDestroy(pool.join[i]);
+      return nullptr;
+    }
     pool.ok = true;
   }
   return &pool;
@@ -953,16 +969,14 @@ static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, Eig
   if (groups > pl.B) groups = pl.B;
   if (profiling_active()) groups = 1;  // per-kernel timing wants kernels that run alone
   StreamPool* pool = groups > 1 ? helper_streams() : nullptr;
-  hipEvent_t fork = nullptr, join[MAX_GROUPS - 1] = {};
-  if (pool) {
-    bool ok = hipEventCreateWithFlags(&fork, hipEventDisableTiming) == hipSuccess;
-    for (int g = 0; ok && g < groups - 1; g++) ok = hipEventCreateWithFlags(&join[g], hipEventDisableTiming) == hipSuccess;
-    if (!ok) pool = nullptr;
-  }
   if (!pool) groups = 1;
+  // The pool's events are shared by all calls on the device; two host threads enqueuing at the same time
+  // must not interleave their record/wait pairs.
+  std::unique_lock<std::mutex> lock(g_pool_mutex, std::defer_lock);
   if (groups > 1) {
-    (void)hipEventRecord(fork, st);
-    for (int g = 0; g < groups - 1; g++) (void)hipStreamWaitEvent(pool->s[g], fork, 0);
+    lock.lock();
+    (void)hipEventRecord(pool->fork, st);
+    for (int g = 0; g < groups - 1; g++) (void)hipStreamWaitEvent(pool->s[g], pool->fork, 0);
   }
   const int per = (pl.B + groups - 1) / groups;
   for (int g = 0; g < groups; g++) {
@@ -972,13 +986,10 @@ static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, Eig
   }
   if (groups > 1) {
     for (int g = 0; g < groups - 1; g++) {
-      (void)hipEventRecord(join[g], pool->s[g]);
-      (void)hipStreamWaitEvent(st, join[g], 0);
+      (void)hipEventRecord(pool->join[g], pool->s[g]);
+      (void)hipStreamWaitEvent(st, pool->join[g], 0);
     }
   }
-  if (fork) (void)hipEventDestroy(fork);  // released by the runtime once the recorded work has finished
-  for (int g = 0; g < MAX_GROUPS - 1; g++)
-    if (join[g]) (void)hipEventDestroy(join[g]);
   return check_launch();
 }
 

@@ -158,9 +158,10 @@ __global__ __launch_bounds__(256) void assign_kernel(const float* __restrict__ s
     float bv = -INFINITY;
     int bi = 0x7fffffff;
     for (int i = lane; i < nA; i += 64) {
-      const float v = row[i];
+      float v = row[i];
+      if (v != v) v = -INFINITY;  // a NaN similarity (a NaN in the metric row) loses against everything
       const int a = ord[i];
-      if (v > bv || (v == bv && a < bi)) { bv = v; bi = a; }
+      if (v > bv || (v == bv && a < bi)) { bv = v; bi = a; }  // v == bv == -inf still takes the lowest index: the destination is always a Set-A token
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -272,25 +273,32 @@ __global__ __launch_bounds__(256) void average_kernel(const TIn* __restrict__ X,
   }
 }
 
+// Eq. 3-10: row norms of the k_prune surviving rows, then Sim [B, |B|, |A|].
+int launch_similarity(const Plan& pl, int dtype, const void* metric, const int32_t* order, float* rnorm, float* sim,
+                      hipStream_t st) {
+  if (pl.nA == 0) return TC_OK;  // a single survivor: Set A is empty, there is nothing to compare
+  const dim3 gn((pl.kp + 3) / 4, pl.B);
+  if (dtype == TC_BF16 || dtype == TC_F16) {
+    const dim3 gsim(((pl.nB + 63) / 64) * ((pl.nA + 63) / 64), pl.B);
+    if (dtype == TC_F16) {
+      TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<f16_t><<<gn, 256, 0, st>>>((const f16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
+      TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<true><<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
+    } else {
+      TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
+      TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<false><<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
+    }
+  } else {
+    TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<float><<<gn, 256, 0, st>>>((const float*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
+    const dim3 gsim(((pl.nB + 15) / 16) * ((pl.nA + 15) / 16), pl.B);
+    TC_TIMED(PK_SIM, 0, st, (sim_f32_kernel<<<gsim, 256, 0, st>>>((const float*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
+  }
+  return check_launch();
+}
+
 int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, const int32_t* order, void* X_out,
                  int32_t* kept_idx, int32_t* merge_dst, float* rnorm, float* sim, int32_t* mlist, hipStream_t st) {
-  const dim3 gn((pl.kp + 3) / 4, pl.B);
-  if (pl.nA > 0) {
-    if (dtype == TC_BF16 || dtype == TC_F16) {
-      const dim3 gsim(((pl.nB + 63) / 64) * ((pl.nA + 63) / 64), pl.B);
-      if (dtype == TC_F16) {
-        TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<f16_t><<<gn, 256, 0, st>>>((const f16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
-        TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<true><<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
-      } else {
-        TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
-        TC_TIMED(PK_SIM, 0, st, (sim_bf16_kernel<false><<<gsim, 256, 0, st>>>((const uint16_t*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
-      }
-    } else {
-      TC_TIMED(PK_ROWNORM, 0, st, (rownorm_kernel<float><<<gn, 256, 0, st>>>((const float*)metric, order, rnorm, pl.N, pl.D, pl.kp)));
-      const dim3 gsim(((pl.nB + 15) / 16) * ((pl.nA + 15) / 16), pl.B);
-      TC_TIMED(PK_SIM, 0, st, (sim_f32_kernel<<<gsim, 256, 0, st>>>((const float*)metric, order, rnorm, sim, pl.N, pl.D, pl.kp, pl.nA, pl.nB)));
-    }
-  }
+  const int rc = launch_similarity(pl, dtype, metric, order, rnorm, sim, st);
+  if (rc != TC_OK) return rc;
   const size_t lds = ((size_t)pl.N + 2 * (size_t)pl.nB + 512) * 4;
   TC_TIMED(PK_ASSIGN, 0, st, (assign_kernel<<<pl.B, 256, lds, st>>>(sim, order, kept_idx, merge_dst, mlist, pl.N, pl.kp, pl.kf, pl.nA, pl.nB)));
   const dim3 ga(pl.kf, pl.B);

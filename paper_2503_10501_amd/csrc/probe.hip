@@ -77,7 +77,7 @@ using namespace tc;
 extern "C" int tc_probe_rates(void* ws, size_t ws_bytes, void* stream, float* rates) {
   if (!ws || !rates) return TC_ERR_NULL;
   if (misaligned(ws)) return TC_ERR_ALIGN;
-  const size_t need = (size_t)1 << 28;  // two 128 MiB halves for the copy
+  const size_t need = (size_t)1 << 31;  // two 1 GiB halves for the copy: four times the 256 MB last-level cache, so the rate is an HBM rate
   if (ws_bytes < need) return TC_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int blocks = 2048, iters = 20000;

@@ -13,15 +13,21 @@ bool profiling_active() { return g_prof != nullptr; }
 
 void prof_begin(int kind, int tag, hipStream_t st) {
   if (!g_prof) return;
+  // A record is pushed even when its events could not be created (both stay null): prof_end() always
+  // pairs with the record of its own prof_begin() and never stamps an older one.
   ProfRecord r{kind, tag, nullptr, nullptr};
-  if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) return;
-  (void)hipEventRecord(r.start, st);
+  if (hipEventCreate(&r.start) != hipSuccess) r.start = nullptr;
+  if (r.start && hipEventCreate(&r.stop) != hipSuccess) {
+    (void)hipEventDestroy(r.start);
+    r.start = r.stop = nullptr;
+  }
+  if (r.start) (void)hipEventRecord(r.start, st);
   g_prof->recs.push_back(r);
 }
 
 void prof_end(hipStream_t st) {
   if (!g_prof || g_prof->recs.empty()) return;
-  (void)hipEventRecord(g_prof->recs.back().stop, st);
+  if (g_prof->recs.back().stop) (void)hipEventRecord(g_prof->recs.back().stop, st);
 }
 
 }  // namespace tc
@@ -45,6 +51,7 @@ extern "C" int tc_profile_compress(const tc_params* p, const void* Q, const void
     for (int s = 0; s < max_sweeps_out; s++) jacobi_update_ms_by_sweep[s] = 0.f;
   for (auto& r : prof.recs) {
     float ms = 0.f;
+    if (!r.start) continue;  // its events could not be created: not timed
     if (e == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
       ms_by_kind[r.kind] += ms;
       launches_by_kind[r.kind] += 1;

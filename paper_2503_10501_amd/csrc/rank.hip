@@ -82,9 +82,13 @@ extern "C" int tc_info_rank(const tc_params* p, const void* O, const int32_t* ro
   void* G = at<char>(ws, pl.off_G);
   EigState* state = at<EigState>(ws, pl.off_state);
   if ((rc = launch_gram(pl, p->dtype, p->eig_dtype, Osub, G, st)) != TC_OK) return rc;
-  if ((rc = launch_jacobi(pl, p->eig_dtype, G, nullptr, at<char>(ws, pl.off_R), at<double>(ws, pl.off_offpart), state, st)) != TC_OK)
-    return rc;
-  if ((rc = launch_sigma(pl, p->eig_dtype, G, state, at<double>(ws, pl.off_sig), sigma, info, st)) != TC_OK) return rc;
+  if (pl.method == TC_EIG_TRIDIAGONAL) {  // eigenvalues only: reduction and bisection, no vectors
+    if ((rc = direct_eigenvalues(pl, &q, sigma, info, ws, st)) != TC_OK) return rc;
+  } else {
+    if ((rc = launch_jacobi(pl, p->eig_dtype, G, nullptr, at<char>(ws, pl.off_R), at<double>(ws, pl.off_offpart), state, st)) != TC_OK)
+      return rc;
+    if ((rc = launch_sigma(pl, p->eig_dtype, G, state, at<double>(ws, pl.off_sig), sigma, info, st)) != TC_OK) return rc;
+  }
   const double tol = rtol > 0.f ? (double)rtol : (double)(n_rows > pl.D ? n_rows : pl.D) * 1.1920928955078125e-07;  // 2^-23
   rank_kernel<<<pl.B, 256, 0, st>>>(at<double>(ws, pl.off_sig), tol, rank, pl.Np);
   return check_launch();

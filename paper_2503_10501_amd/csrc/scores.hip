@@ -17,7 +17,10 @@ __global__ __launch_bounds__(256) void sigma_kernel(const T* __restrict__ G, con
     const double lam = (double)Gb[(size_t)i * Np + i];
     sb[i] = lam > 0.0 ? sqrt(lam) : 0.0;
   }
-  if (tid == 0 && info_out) info_out[b] = state[b].done ? state[b].sweeps : -state[b].sweeps;
+  if (tid == 0 && info_out) {  // > 0: converged (an all-zero matrix needs no sweep and reports 1); < 0: not converged
+    const int sw = state[b].sweeps > 0 ? state[b].sweeps : 1;
+    info_out[b] = state[b].done ? sw : -sw;
+  }
   if (!sigma_out) return;
   int n2 = 1;
   while (n2 < Np) n2 <<= 1;
@@ -115,6 +118,11 @@ static int run_scores(const Plan& pl, const T* G, const float* U, const EigState
   while (n2 < pl.Np) n2 <<= 1;
   TC_TIMED(PK_SIGMA, 0, st, (sigma_kernel<T><<<pl.B, 256, sigma_out ? n2 * sizeof(float) : 0, st>>>(G, state, sig, sigma_out, info_out, pl.N, pl.Np)));
   TC_TIMED(PK_ICS, 0, st, (ics_kernel<<<dim3((pl.N + 3) / 4, pl.B), 256, 0, st>>>(U, sig, sv_rtol, C_ws, C_out, pl.N, pl.Np)));
+  TC_TIMED(PK_COMBINE, 0, st, (combine_kernel<<<pl.B, 256, 0, st>>>(C_ws, S, lambda, norm_mode, E, pl.N)));
+  return check_launch();
+}
+
+int launch_combine(const Plan& pl, const float* C_ws, const float* S, float lambda, int norm_mode, float* E, hipStream_t st) {
   TC_TIMED(PK_COMBINE, 0, st, (combine_kernel<<<pl.B, 256, 0, st>>>(C_ws, S, lambda, norm_mode, E, pl.N)));
   return check_launch();
 }

@@ -48,10 +48,13 @@ struct Plan {
   int tsize;     // bytes of one eigensolver element (4 or 8)
   int max_sweeps;
   int groups;    // requested stream groups (0 = automatic)
+  int method;    // eigensolver actually used: TC_EIG_JACOBI or TC_EIG_TRIDIAGONAL
   double tol;
   float scale;
   size_t off_O, off_S, off_Spart, off_G, off_U, off_R, off_offpart, off_state, off_sig, off_C, off_E, off_order,
       off_rnorm, off_sim, off_mlist, off_info;
+  size_t off_td_d, off_td_e, off_td_tau, off_td_lam, off_td_blk, off_td_tnorm, off_td_rn, off_td_bad, off_td_wgt,
+      off_td_W, off_td_tw, off_td_Cpart;  // direct eigensolver only
   size_t total;
 };
 
@@ -80,14 +83,25 @@ int launch_scores(const Plan& pl, int eig_dtype, const void* G, const void* U, c
                   float* C_out, float* sigma_out, int32_t* info_out, hipStream_t st);
 int launch_sigma(const Plan& pl, int eig_dtype, const void* G, const EigState* state, double* sig_ws, float* sigma_out,
                  int32_t* info_out, hipStream_t st);
+int launch_combine(const Plan& pl, const float* C_ws, const float* S, float lambda, int norm_mode, float* E, hipStream_t st);
+// direct eigensolver (tridiag.hip, tdeig.hip)
+int tridiag_panel_width(int N);
+int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, hipStream_t st);
+int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, const float* tauv, const float* Vc,
+                    double* lam, int2* blk, double* tnorm, double* DP, double* UM, float* W, double* rn, int32_t* bad,
+                    double* sig, double* wgt, double* Cpart, float sv_rtol, bool vectors, float* C, float* C_out,
+                    float* sigma_out, int32_t* info_out, hipStream_t st);
+int direct_eigenvalues(const Plan& pl, const tc_params* p, float* sigma, int32_t* info, void* ws, hipStream_t st);  // api.hip
 int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st);
+int launch_similarity(const Plan& pl, int dtype, const void* metric, const int32_t* order, float* rnorm, float* sim,
+                      hipStream_t st);
 int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, const int32_t* order, void* X_out,
                  int32_t* kept_idx, int32_t* merge_dst, float* rnorm, float* sim, int32_t* mlist, hipStream_t st);
 
 // ---- optional per-kernel timing (only active inside tc_profile_compress) ----------------------
 enum ProfKind {
   PK_ATTN = 0, PK_ATTN_REDUCE, PK_GRAM, PK_JINIT, PK_JSOLVE, PK_JUPDATE, PK_JUPDATE_U, PK_JSWEEPEND, PK_SIGMA, PK_ICS, PK_COMBINE,
-  PK_TOPK, PK_ROWNORM, PK_SIM, PK_ASSIGN, PK_AVERAGE, PK_COUNT
+  PK_TOPK, PK_ROWNORM, PK_SIM, PK_ASSIGN, PK_AVERAGE, PK_TRIDIAG, PK_BISECT, PK_TWISTED, PK_BACKTF, PK_COUNT
 };
 static_assert((int)PK_COUNT == (int)TC_PROF_KINDS, "internal and public kernel kinds must match");
 void prof_begin(int kind, int tag, hipStream_t st);  // no-ops unless a profile run is active on this thread

@@ -29,16 +29,28 @@ SMALL = {
 }
 
 
+def _say(capsys):
+    """Progress lines that reach the terminal although pytest captures output."""
+    def say(msg):
+        with capsys.disabled():
+            print("\n[progress] " + msg, flush=True)
+    return say
+
+
 def _small(name):
     _, _, _, _, Workload = _mods()
     return Workload(name, *SMALL[name])
 
 
-def test_tiny_config_all_stages():
+METHODS = {"tridiagonal": 2, "jacobi": 1}   # tc_eig_method; 0 (automatic) picks the tridiagonal route up to 1024 tokens
+
+
+@pytest.mark.parametrize("method", list(METHODS))
+def test_tiny_config_all_stages(method):
     tc, gu, parity, CONFIGS, _ = _mods()
-    rep = parity.run_all_stages(CONFIGS["tiny"])
+    rep = parity.run_all_stages(CONFIGS["tiny"], eig_method=METHODS[method])
     assert min(rep["jaccard_vs_independent_oracle"]) == 1.0
-    rep = parity.run_all_stages(CONFIGS["tiny"].with_(causal=0))
+    rep = parity.run_all_stages(CONFIGS["tiny"].with_(causal=0), eig_method=METHODS[method])
     assert min(rep["jaccard_vs_independent_oracle"]) == 1.0
 
 
@@ -61,10 +73,10 @@ def test_tiny_config_matches_the_stored_oracle_fixture():
 
 
 @pytest.mark.parametrize("name", list(SMALL))
-@pytest.mark.parametrize("causal", [1, 0])
-def test_small_shapes_all_stages(name, causal):
+@pytest.mark.parametrize("causal,method", [(1, "tridiagonal"), (0, "tridiagonal"), (1, "jacobi")])
+def test_small_shapes_all_stages(name, causal, method):
     tc, gu, parity, _, _ = _mods()
-    parity.run_all_stages(_small(name).with_(causal=causal))
+    parity.run_all_stages(_small(name).with_(causal=causal), eig_method=METHODS[method])
 
 
 @pytest.mark.parametrize("lam,norm", [(0.0, 1), (1.0, 1), (0.3, 0), (0.5, 1)])
@@ -85,11 +97,13 @@ def test_sv_rtol_and_custom_scale():
     parity.run_all_stages(_small("f32_ragged"), softmax_scale=0.2)
 
 
-def test_llava7b_batch1_full_size():
+@pytest.mark.parametrize("method", list(METHODS))
+def test_llava7b_batch1_full_size(method):
     tc, gu, parity, CONFIGS, _ = _mods()
-    rep = parity.run_all_stages(CONFIGS["llava7b_b1"])
-    print("llava7b_b1", rep)
+    rep = parity.run_all_stages(CONFIGS["llava7b_b1"], eig_method=METHODS[method])
+    print("llava7b_b1", method, rep)
     assert max(rep["C_rel"]) < 1e-4
+    assert rep["min_rel_gap"][0] > 0 and rep["f32_gram_floor"][0] < 1e-2   # the conditioning report is there
 
 
 def test_llava7b_shape_with_half_precision_storage():
@@ -100,24 +114,29 @@ def test_llava7b_shape_with_half_precision_storage():
     assert max(rep["C_rel"]) < 1e-4
 
 
-def test_llava7b_batch64_in_the_benchmarked_launch_configuration():
-    # the whole batch runs exactly as bench.py launches it; the oracle checks sampled images
+@pytest.mark.parametrize("method", list(METHODS))
+def test_llava7b_batch64_in_the_benchmarked_launch_configuration(method, capsys):
+    # the whole batch runs exactly as bench.py launches it; the oracle checks every image
     tc, gu, parity, CONFIGS, _ = _mods()
-    rep = parity.run_all_stages(CONFIGS["llava7b_b64"], oracle_images=[0, 21, 42, 63])
-    print("llava7b_b64", rep)
+    # (the iterative method, no longer the default at this size, is checked on every fourth image)
+    rep = parity.run_all_stages(CONFIGS["llava7b_b64"], conditioning_images=(0, 21, 42, 63), progress=_say(capsys),
+                                oracle_images=None if method == "tridiagonal" else range(0, 64, 4),
+                                eig_method=METHODS[method])
+    print("llava7b_b64", method, parity.summary(rep))
+    assert rep["images_checked"] == (64 if method == "tridiagonal" else 16)
 
 
 def test_llava7b_batch64_on_one_stream():
     # stream_groups = 1: every eigensolver launch covers the whole batch (three tiles per workgroup in the
     # tile update, the shape bench.py's per-kernel timing and the committed profiles use)
     tc, gu, parity, CONFIGS, _ = _mods()
-    parity.run_all_stages(CONFIGS["llava7b_b64"], oracle_images=[13, 50], stream_groups=1)
+    parity.run_all_stages(CONFIGS["llava7b_b64"], oracle_images=[13, 50], stream_groups=1, eig_method=METHODS["jacobi"])
 
 
 def test_llava7b_batch64_with_the_256_to_192_counts():
     tc, gu, parity, CONFIGS, _ = _mods()
-    parity.run_all_stages(CONFIGS["llava7b_b64"].with_(k_prune=256, k_final=192), images=range(8),
-                          oracle_images=[0, 7])
+    rep = parity.run_all_stages(CONFIGS["llava7b_b64"].with_(k_prune=256, k_final=192), images=range(8))
+    print("llava7b_b64 256->192", parity.summary(rep))
 
 
 def test_token_counts_and_selection_strategies_of_the_ablation_table():
@@ -149,10 +168,15 @@ def test_token_counts_and_selection_strategies_of_the_ablation_table():
             assert kept.shape[1] == kf and int((gu.host(dst)[0] >= 0).sum()) == kp
 
 
-def test_hires_2880_tokens_sampled():
+@pytest.mark.parametrize("first", [0, 4])
+def test_hires_2880_tokens_every_image(first, capsys):
+    # the batch of 8 runs on the GPU as a whole both times; the oracle takes four images per test (about 20 s
+    # each), so that the two tests together cover every image
     tc, gu, parity, CONFIGS, _ = _mods()
-    rep = parity.run_all_stages(CONFIGS["hires_b8"], oracle_images=[3])
-    print("hires_b8", rep)
+    rep = parity.run_all_stages(CONFIGS["hires_b8"], oracle_images=range(first, first + 4), conditioning_images=(3,),
+                                progress=_say(capsys))
+    print("hires_b8", parity.summary(rep))
+    assert rep["images_checked"] == 4
 
 
 def test_maximum_number_of_visual_tokens():
@@ -166,10 +190,22 @@ def test_maximum_number_of_visual_tokens():
     assert max(rep["C_rel"]) < 1e-4
 
 
-def test_llava13b_batch128_sampled():
+@pytest.mark.parametrize("first", [0, 64])
+def test_llava13b_batch128_every_image(first, capsys):
+    # the batch of 128 runs on the GPU as a whole both times; the oracle takes one half per test
     tc, gu, parity, CONFIGS, _ = _mods()
-    rep = parity.run_all_stages(CONFIGS["llava13b_b128"], oracle_images=[0, 127])
-    print("llava13b_b128", rep)
+    rep = parity.run_all_stages(CONFIGS["llava13b_b128"], oracle_images=range(first, first + 64), conditioning_images=(0, 63),
+                                progress=_say(capsys))
+    print("llava13b_b128", parity.summary(rep))
+    assert rep["images_checked"] == 64
+
+
+def test_llava13b_batch128_jacobi_sampled(capsys):
+    # the iterative method on the same batch (every image's convergence is asserted; the oracle checks a sample)
+    tc, gu, parity, CONFIGS, _ = _mods()
+    rep = parity.run_all_stages(CONFIGS["llava13b_b128"], oracle_images=[0, 41, 86, 127], progress=_say(capsys),
+                                eig_method=METHODS["jacobi"])
+    print("llava13b_b128 jacobi", parity.summary(rep))
 
 
 # ---------------------------------------------------------------------------------------------
@@ -223,7 +259,7 @@ def test_non_convergence_is_reported_in_info():
     from workloads import make_batch
     w = CONFIGS["tiny"]
     b = make_batch(w)
-    p = tc.params_for(w, jacobi_max_sweeps=1)
+    p = tc.params_for(w, jacobi_max_sweeps=1, eig_method=METHODS["jacobi"])
     O, S = gu.attn_output(p, b["Q"], b["K"], b["V"])
     _, _, _, info = gu.ipgs_score(p, O, S)
     assert gu.host(info)[0] == -1
@@ -237,7 +273,7 @@ def test_converged_block_pairs_are_left_alone_and_the_work_done_is_counted():
     from workloads import make_batch
     w = CONFIGS["llava7b_b1"]
     b = make_batch(w)
-    p = tc.params_for(w)
+    p = tc.params_for(w, eig_method=METHODS["jacobi"])
     sd = tc.storage_dtype(p)
     Q, K, V = (gu.dev(b[k], p) for k in ("Q", "K", "V"))
     X = gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)
@@ -261,12 +297,13 @@ def test_converged_block_pairs_are_left_alone_and_the_work_done_is_counted():
     assert torch.equal(ref["kept_idx"], kept) and torch.equal(ref["X_out"], X_out) and torch.equal(ref["info"], info)
 
 
-def test_results_are_bit_reproducible():
+@pytest.mark.parametrize("method", list(METHODS))
+def test_results_are_bit_reproducible(method):
     tc, gu, _, _, _ = _mods()
     from workloads import make_batch
     w = _small("bf16_ragged")
     b = make_batch(w)
-    p = tc.params_for(w)
+    p = tc.params_for(w, eig_method=METHODS[method])
     args = [gu.dev(b[k], p) for k in ("Q", "K", "V")] + [gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)]
     r1 = gu.compress(p, *args)
     r2 = gu.compress(p, *args)
@@ -274,15 +311,16 @@ def test_results_are_bit_reproducible():
         assert torch.equal(r1[k], r2[k]), k
 
 
+@pytest.mark.parametrize("method", list(METHODS))
 @pytest.mark.parametrize("name", ["tiny", "bf16_ragged", "llava7b_b1"])
-def test_results_do_not_depend_on_what_the_workspace_held_before(name):
+def test_results_do_not_depend_on_what_the_workspace_held_before(name, method):
     # every byte the kernels read from the workspace must have been written by the same call: a read of
     # stale scratch (or of LDS another wavefront has already reused) shows up as a run-to-run difference
     tc, gu, _, CONFIGS, _ = _mods()
     from workloads import make_batch
     w = CONFIGS[name] if name in CONFIGS else _small(name)
     b = make_batch(w)
-    p = tc.params_for(w)
+    p = tc.params_for(w, eig_method=METHODS[method])
     sd = tc.storage_dtype(p)
     Q, K, V = (gu.dev(b[k], p) for k in ("Q", "K", "V"))
     X = gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)
@@ -318,7 +356,7 @@ def test_results_do_not_depend_on_the_number_of_stream_groups():
     b = make_batch(w)
     runs = []
     for groups in (1, 2, 3, 4, 0):
-        p = tc.params_for(w, stream_groups=groups)
+        p = tc.params_for(w, stream_groups=groups, eig_method=METHODS["jacobi"])
         args = [gu.dev(b[k], p) for k in ("Q", "K", "V")] + [gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)]
         runs.append(gu.compress(p, *args))
     for r in runs[1:]:
@@ -326,14 +364,15 @@ def test_results_do_not_depend_on_the_number_of_stream_groups():
             assert torch.equal(runs[0][k], r[k]), k
 
 
-def test_two_calls_on_different_streams_with_their_own_workspaces_may_overlap():
+@pytest.mark.parametrize("method", list(METHODS))
+def test_two_calls_on_different_streams_with_their_own_workspaces_may_overlap(method):
     # the helper streams of the eigensolver are shared by all calls on a device: two calls in flight at
     # once, each on its own stream with its own workspace, must give what each gives alone
     tc, gu, _, _, _ = _mods()
     from workloads import make_batch
     w = _small("bf16_ragged").with_(batch=9)
     batches = [make_batch(w, list(range(9))), make_batch(w, list(range(20, 29)))]
-    p = tc.params_for(w)
+    p = tc.params_for(w, eig_method=METHODS[method])
     sd = tc.storage_dtype(p)
     B, N = p.batch, p.n_vis
     args = [[gu.dev(b[k], p) for k in ("Q", "K", "V")] + [gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)]
