@@ -78,6 +78,7 @@ int make_plan(const tc_params* p, Plan* pl) {
     q.off_td_W = take(B * Np * Np * 4);        // eigenvectors of T (the reflectors use the region of U)
     q.off_td_tw = take(B * Np * Np * 16);      // pivots and multipliers of the twisted factorisations
     q.off_td_Cpart = take(B * nstrip * Np * 8);
+    q.off_td_Tf = take(B * ((N + 15) / 16) * 256 * 4);   // T factors of the blocks of 16 reflectors
   }
   q.total = off > 0 ? off : 256;
   return TC_OK;
@@ -97,7 +98,7 @@ static int direct_chain(const Plan& pl, const tc_params* p, bool vectors, float*
   return launch_td_eigen(pl, dvec, evec, tauv, Vc, at<double>(ws, pl.off_td_lam), at<int2>(ws, pl.off_td_blk),
                          at<double>(ws, pl.off_td_tnorm), tw, tw + (size_t)pl.B * pl.Np * pl.Np, at<float>(ws, pl.off_td_W),
                          at<double>(ws, pl.off_td_rn), at<int32_t>(ws, pl.off_td_bad), at<double>(ws, pl.off_sig),
-                         at<double>(ws, pl.off_td_wgt), at<double>(ws, pl.off_td_Cpart), p->sv_rtol, vectors, C_ws, ics,
+                         at<double>(ws, pl.off_td_wgt), at<double>(ws, pl.off_td_Cpart), at<float>(ws, pl.off_td_Tf), p->sv_rtol, vectors, C_ws, ics,
                          sigma, info, st);
 }
 

@@ -54,7 +54,7 @@ struct Plan {
   size_t off_O, off_S, off_Spart, off_G, off_U, off_R, off_offpart, off_state, off_sig, off_C, off_E, off_order,
       off_rnorm, off_sim, off_mlist, off_info;
   size_t off_td_d, off_td_e, off_td_tau, off_td_lam, off_td_blk, off_td_tnorm, off_td_rn, off_td_bad, off_td_wgt,
-      off_td_W, off_td_tw, off_td_Cpart;  // direct eigensolver only
+      off_td_W, off_td_tw, off_td_Cpart, off_td_Tf;  // direct eigensolver only
   size_t total;
 };
 
@@ -89,7 +89,7 @@ int tridiag_panel_width(int N);
 int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, hipStream_t st);
 int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, const float* tauv, const float* Vc,
                     double* lam, int2* blk, double* tnorm, double* DP, double* UM, float* W, double* rn, int32_t* bad,
-                    double* sig, double* wgt, double* Cpart, float sv_rtol, bool vectors, float* C, float* C_out,
+                    double* sig, double* wgt, double* Cpart, float* Tf, float sv_rtol, bool vectors, float* C, float* C_out,
                     float* sigma_out, int32_t* info_out, hipStream_t st);
 int direct_eigenvalues(const Plan& pl, const tc_params* p, float* sigma, int32_t* info, void* ws, hipStream_t st);  // api.hip
 int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st);
@@ -192,5 +192,31 @@ __device__ inline T wave_sum(T v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
+
+// Sum over the 64 lanes with data-parallel lane permutations (no LDS round trips): partners L^1, L^2, 7-L and
+// 15-L inside a row of 16, then the four row totals through scalar registers, in a fixed order.  Every lane
+// returns the same bits.
+template <int CTRL>
+__device__ inline double dpp_f64(double x) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
+  return __hiloint2double(hi, lo);
+}
+__device__ inline double readlane_f64(double x, int l) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(x), l), __builtin_amdgcn_readlane(__double2loint(x), l));
+}
+// total of each row of 16 lanes, in every lane of the row
+__device__ inline double row16_sum_dpp(double x) {
+  x += dpp_f64<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_f64<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_f64<0x141>(x);  // row_half_mirror
+  x += dpp_f64<0x140>(x);  // row_mirror
+  return x;
+}
+__device__ inline double wave_sum_dpp(double x) {
+  x = row16_sum_dpp(x);
+  return (readlane_f64(x, 0) + readlane_f64(x, 16)) + (readlane_f64(x, 32) + readlane_f64(x, 48));
+}
+
 
 }  // namespace tc

@@ -3,9 +3,10 @@
 //   2b  eigenvector of every eigenvalue from the twisted factorisation of T - lambda I
 //       (forward L D+ L^T, backward U D- U^T, joined at the index r that minimises |gamma_r|;
 //       the vector solves (T - lambda I) z = gamma_r e_r), one lane per eigenvector;
-//   3   back-transformation U = Q W = H_0 ... H_{N-2} W in float32 with the columns of a strip held in
-//       registers, and, since U is only needed for it, the information contribution score of Eq. 3-6,
-//       C(x) = sum_i |U[x][i]| sigma_i, accumulated right there: U is never written.
+//   3   back-transformation U = Q W = H_0 ... H_{N-2} W in float32 on the matrix cores, the reflectors sixteen
+//       at a time in compact WY form, a strip of 64 eigenvectors held in accumulator registers; since U is
+//       only needed for it, the information contribution score of Eq. 3-6, C(x) = sum_i |U[x][i]| sigma_i,
+//       is accumulated right there: U is never written.
 // T is first split where an off-diagonal element is negligible (|e_k| <= eps ||T||); each eigenpair then
 // belongs to one unreduced block and its vector is zero outside that block, so equal eigenvalues of
 // decoupled blocks (block-diagonal Gram matrices, null spaces) get orthogonal vectors for free.
@@ -23,13 +24,20 @@ constexpr double TD_EPS = 2.220446049250313e-16;
 // ---- 2a -----------------------------------------------------------------------------------------------
 // dvec, evec [B][Np] from the reduction.  Writes lam [B][Np] (eigenvalue of slot k: the (k - s)-th smallest
 // of the block [s, t) that row k lies in), blk [B][Np] = (s, t), and tnorm [B] = ||T||_inf.
+//
+// The number of eigenvalues below x is the number of sign changes in the sequence of leading principal
+// minors p_0 = 1, p_1 = d_s - x, p_i = (d_i - x) p_{i-1} - e_{i-1}^2 p_{i-2}.  In this form the chain from one step to the next is a single fused multiply-add;
+// the quotient form q_i = d_i - x - e^2 / q_{i-1} puts a float64 division (thirty dependent instructions)
+// on it, and with one eigenvalue per lane there is nothing to hide that latency behind: measured 3.4 ms
+// per batch against 0.2.  T is scaled by a power of two to ||T|| <= 1 so that the minors change by at most a
+// factor 3 per step, and they are brought back into range every eight steps.
 __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict__ dvec, const double* __restrict__ evec,
                                                         double* __restrict__ lam, int2* __restrict__ blk,
                                                         double* __restrict__ tnorm, int32_t* __restrict__ bad, int N,
                                                         int Np) {
   extern __shared__ __attribute__((aligned(16))) unsigned char tb_smem[];
-  double* ds = reinterpret_cast<double*>(tb_smem);  // [N]
-  double* es = ds + N;                               // [N]: es[i] = |coupling of rows i-1 and i|, es[0] = 0
+  double* ds = reinterpret_cast<double*>(tb_smem);  // [N], scaled
+  double* es = ds + N;                               // [N]: es[i] = |coupling of rows i-1 and i|, es[0] = 0, scaled
   double* e2 = es + N;                               // [N]: its square, 0 where T is split
   __shared__ double wmax[4];
   const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -48,7 +56,17 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
   __syncthreads();
   const double tn = fmax(fmax(wmax[0], wmax[1]), fmax(wmax[2], wmax[3]));
   const double split = TD_EPS * tn;
-  for (int i = tid; i < N; i += 256) e2[i] = es[i] > split ? es[i] * es[i] : 0.0;
+  // power of two that brings ||T|| into (1/2, 1] (exact); a zero or non-finite norm leaves T as it is
+  int ex = 0;
+  if (tn > 0.0 && tn < DBL_MAX) (void)frexp(tn, &ex);
+  const double down = ldexp(1.0, -ex), up = ldexp(1.0, ex);
+  __syncthreads();  // every thread has read the unscaled values it needs
+  for (int i = tid; i < N; i += 256) {
+    const double e = es[i];
+    ds[i] *= down;
+    es[i] = e * down;
+    e2[i] = e > split ? (e * down) * (e * down) : 0.0;
+  }
   __syncthreads();
   if (blockIdx.x == 0 && tid == 0) { tnorm[b] = tn; bad[b] = 0; }
   const int k = blockIdx.x * 256 + tid;
@@ -57,34 +75,65 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
   while (s > 0 && e2[s] != 0.0) s--;
   while (t < N && e2[t] != 0.0) t++;
   const int m = k - s;
-  // Gershgorin interval of the block, slightly widened
-  double lo = DBL_MAX, hi = -DBL_MAX, e2max = 0.0;
+  // Gershgorin interval of the block, slightly widened (scaled units: ||T|| <= 1)
+  double lo = DBL_MAX, hi = -DBL_MAX;
   for (int i = s; i < t; i++) {
-    const double r = (i > s ? es[i] : 0.0) + (i + 1 < t ? es[i + 1] : 0.0);
+    const double r = (i > s && e2[i] != 0.0 ? es[i] : 0.0) + (i + 1 < t && e2[i + 1] != 0.0 ? es[i + 1] : 0.0);
     lo = fmin(lo, ds[i] - r);
     hi = fmax(hi, ds[i] + r);
-    e2max = fmax(e2max, e2[i]);
   }
-  const double widen = 2.0 * TD_EPS * tn * (t - s) + 2.0 * DBL_MIN;
+  const double widen = 2.0 * TD_EPS * (t - s) + 2.0 * DBL_MIN;
   lo -= widen;
   hi += widen;
-  const double pivmin = DBL_MIN * fmax(1.0, e2max);
+  const double BIG = 0x1p256, SMALL = 0x1p-256;
   for (int it = 0; it < 128; it++) {
     const double mid = 0.5 * (lo + hi);
-    if (!(mid > lo && mid < hi)) break;                                   // the interval cannot be halved any more
-    if (hi - lo <= 0.25 * TD_EPS * tn) break;  // the entries of T carry errors of eps ||T|| themselves; same count for every lane
-    // number of eigenvalues of the block below mid = number of negative pivots of T - mid I
-    double q = ds[s] - mid;
-    if (fabs(q) < pivmin) q = -pivmin;
-    int cnt = q < 0.0 ? 1 : 0;
-    for (int i = s + 1; i < t; i++) {
-      q = (ds[i] - mid) - e2[i] / q;
-      if (fabs(q) < pivmin) q = -pivmin;
-      cnt += q < 0.0 ? 1 : 0;
-    }
+    if (!(mid > lo && mid < hi)) break;     // the interval cannot be halved any more
+    if (hi - lo <= 0.25 * TD_EPS) break;    // the entries of T carry errors of eps ||T|| themselves; same count for every lane
+    double pp = 1.0, p = ds[s] - mid;       // p_{i-2}, p_{i-1}
+    int cnt = __double2hiint(p) < 0 ? 1 : 0; // p_0 = 1 is positive
+    // Sign changes are counted on the sign bits: (bits of p_i xor bits of p_{i-1}) >> 63.  An exact zero needs
+    // no special case: its successor is -e^2 times its predecessor, so the three minors around it contain one
+    // sign change whichever sign the zero is given.  Eight rows at a time: their coefficients are fetched
+    // from LDS together (sixteen independent reads in flight; read one by one inside the chain each would
+    // cost its full latency), rows past the block's end are replaced by the identity step p_i = p_{i-1};
+    // then the pair of minors is brought back into range (a common factor does not change any sign).
+    auto chunk = [&](int i0, bool whole) {
+      double a[8], c[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int ii = whole ? i0 + u : min(i0 + u, t - 1);
+        a[u] = ds[ii];
+        c[u] = e2[ii];
+      }
+      // all sixteen reads are issued before any is used, and none conditionally (the optimiser would put each
+      // behind a branch with a wait of its own)
+      asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
+                        "+v"(c[0]), "+v"(c[1]), "+v"(c[2]), "+v"(c[3]), "+v"(c[4]), "+v"(c[5]), "+v"(c[6]), "+v"(c[7]));
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const bool in = whole || i0 + u < t;
+        a[u] = in ? a[u] - mid : 1.0;
+        c[u] = in ? c[u] : 0.0;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const double pn = fma(a[u], p, -(c[u] * pp));
+        cnt += (int)((unsigned)(__double2hiint(pn) ^ __double2hiint(p)) >> 31);
+        pp = p;
+        p = pn;
+      }
+      const double mag = fmax(fabs(p), fabs(pp));
+      const double f = mag > BIG ? SMALL : (mag < SMALL && mag > 0.0 ? BIG : 1.0);
+      p *= f;
+      pp *= f;
+    };
+    int i0 = s + 1;
+    for (; i0 + 8 <= t; i0 += 8) chunk(i0, true);   // whole chunks: no selects
+    if (i0 < t) chunk(i0, false);                   // the last, shorter one
     if (cnt > m) hi = mid; else lo = mid;
   }
-  lam[(size_t)b * Np + k] = 0.5 * (lo + hi);
+  lam[(size_t)b * Np + k] = 0.5 * (lo + hi) * up;
   blk[(size_t)b * Np + k] = int2{s, t};
 }
 
@@ -287,97 +336,185 @@ __global__ __launch_bounds__(256) void td_weights_kernel(const double* __restric
 }
 
 // ---- 3 ------------------------------------------------------------------------------------------------
-// U = H_0 H_1 ... H_{N-2} W for a strip of 64 columns (eigenvectors), H_j = I - tau_j v_j v_j^T, applied from
-// j = N-2 down to 0.  A workgroup of 16 wavefronts owns the strip: lane = column, wavefront w the rows
-// i = 16 r + w (r < RT), held in registers for the whole kernel.  Per reflector: every wavefront forms
-// its part of v_j^T U, the 16 parts are added in a fixed order through LDS (one barrier per reflector, two
-// alternating buffers), then the rows are updated.  v_j comes through LDS too (three rotating buffers), reordered so that a
-// wavefront reads its RT values as consecutive 16-byte pieces; only the chunks of four rows that a
-// reflector reaches (rows > j) are touched.  At the end the strip's share of Eq. 3-6,
-//     Cpart[strip][x] = sum_{k in strip} |U[x][k]| wgt[k],
-// is reduced across the lanes and written; U itself is not.
-template <int RT>
-__global__ __launch_bounds__(1024) void td_backtransform_kernel(const float* __restrict__ W, const float* __restrict__ Vc,
-                                                                const float* __restrict__ tauv,
-                                                                const double* __restrict__ wgt,
-                                                                double* __restrict__ Cpart, float* __restrict__ U_out,
-                                                                int N, int Np, int nstrip) {
-  static_assert(RT % 4 == 0, "rows are handled four at a time");
-  __shared__ __attribute__((aligned(16))) float vbuf[3][16 * RT];  // v_j reordered: [row % 16][row / 16]; three in rotation
-  __shared__ float red[2][16][64];
+// U = H_0 H_1 ... H_{N-2} W, sixteen reflectors at a time in compact WY form (the scheme of LAPACK's
+// dlarft/dlarfb): H_j0 ... H_j0+15 = I - V T V^T with V the 16 reflectors and T upper triangular,
+//     T[c][c] = tau_c,   T[0:c, c] = -tau_c T[0:c, 0:c] (V[:, 0:c]^T v_c).
+typedef __attribute__((ext_vector_type(4))) float f4;
+constexpr int BT_K = 16;  // reflectors per block
+
+// T of every block of 16 reflectors: one workgroup per (block, image).
+__global__ __launch_bounds__(256) void td_tfactor_kernel(const float* __restrict__ Vc, const float* __restrict__ tauv,
+                                                         float* __restrict__ Tf, int N, int Np, int npanel) {
+  __shared__ float S[BT_K][BT_K];   // S[a][c] = v_a^T v_c, a < c
+  __shared__ float T[BT_K][BT_K];
+  const int p = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j0 = BT_K * p;
+  const float* Vb = Vc + (size_t)b * Np * Np;
+  for (int pair = wave; pair < BT_K * BT_K; pair += 4) {
+    const int a = pair / BT_K, c = pair % BT_K;
+    if (a >= c) continue;  // uniform over the wavefront
+    float dot = 0.f;
+    if (j0 + c <= N - 2) {  // reflectors past the last one are zero; v_c is zero up to row j0 + c
+      const float* vp = Vb + (size_t)p * Np * BT_K;  // [row][16]
+      for (int i = j0 + c + 1 + lane; i < N; i += 64) dot += vp[(size_t)i * BT_K + a] * vp[(size_t)i * BT_K + c];
+    }
+    dot = wave_sum(dot);
+    if (lane == 0) S[a][c] = dot;
+  }
+  T[tid / BT_K][tid % BT_K] = 0.f;
+  __syncthreads();
+  if (wave == 0) {  // column by column; lane a owns row a
+    for (int c = 0; c < BT_K; c++) {
+      const float tau = j0 + c <= N - 2 ? tauv[(size_t)b * Np + j0 + c] : 0.f;
+      float acc = 0.f;
+      if (lane < c)
+        for (int r = lane; r < c; r++) acc += T[lane][r] * S[r][c];
+      if (lane < c) T[lane][c] = -tau * acc;
+      if (lane == c) T[c][c] = tau;
+      // (a wavefront runs in lockstep and the LDS serves its accesses in order: column c is complete before c + 1 reads it)
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  __syncthreads();
+  Tf[((size_t)b * npanel + p) * (BT_K * BT_K) + tid] = T[tid / BT_K][tid % BT_K];
+}
+
+// The strip of 64 eigenvectors (columns k0 .. k0+63 of W) lives in the accumulator registers of the four
+// wavefronts of a workgroup for the whole kernel: wavefront w owns the row tiles rt = 4 t + w (16 rows each),
+// as four 16x16 column tiles; element j of a lane is (row 4 (lane / 16) + j, column lane % 16) of its tile.
+// Per block of reflectors, last block first:
+//   Z  = V^T U     contraction over rows; the B operand of matrix-core step j is accumulator element j itself
+//                  (rows j, 4 + j, 8 + j, 12 + j of the tile), the A operand the matching rows of V;
+//                  the four wavefronts' parts are added in a fixed order through LDS
+//   Z2 = T Z       one 16x16x16 product per column tile, same trick on the accumulator of Z
+//   U -= V Z2      likewise on the accumulator of Z2.
+// V of the block goes through LDS, transposed to [row][reflector].  Only row tiles that the block reaches
+// (rows > j0) take part.  At the end the strip's share of Eq. 3-6, Cpart[strip][x] = sum_k |U[x][k]| wgt[k],
+// is reduced across the 16 lanes of a row and written; U itself is not.
+template <int TPW>
+__global__ __launch_bounds__(256) void td_backtransform_kernel(const float* __restrict__ W, const float* __restrict__ Vc,
+                                                               const float* __restrict__ Tf,
+                                                               const double* __restrict__ wgt,
+                                                               double* __restrict__ Cpart, int N, int Np, int nstrip,
+                                                               int npanel) {
+  constexpr int VP = BT_K + 1;       // LDS pitch of a row of V
+  constexpr int ROWS = 64 * TPW;     // rows covered by the workgroup (>= Np)
+  extern __shared__ __attribute__((aligned(16))) float bt_smem[];
+  float* vt = bt_smem;                         // [ROWS][VP]
+  float* zbuf = vt + ROWS * VP;                // [4][16][64] the wavefronts' parts of Z
+  float* tl = zbuf + 4 * BT_K * 64;            // [16][16]
   const int b = blockIdx.y, strip = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int k = strip * 64 + lane;  // this lane's eigenvector
-  const bool live = k < N;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l15 = lane & 15, q4 = lane >> 4;
+  const int k0 = strip * 64;
   const float* Wb = W + (size_t)b * Np * Np;
   const float* Vb = Vc + (size_t)b * Np * Np;
-  const float* tb = tauv + (size_t)b * Np;
-  float u[RT];
+  f4 acc[TPW][4];
 #pragma unroll
-  for (int r = 0; r < RT; r++) {
-    const int i = 16 * r + w;
-    u[r] = (live && i < N) ? Wb[(size_t)i * Np + k] : 0.f;
-  }
-  // the slot of row i in the reordered v: (i % 16) * RT + i / 16
-  auto stage = [&](int j, int buf) {
-    for (int i = tid; i < 16 * RT; i += 1024) vbuf[buf][(i & 15) * RT + (i >> 4)] = i < N ? Vb[(size_t)j * Np + i] : 0.f;
-  };
-  if (N >= 2) stage(N - 2, 0);
-  __syncthreads();
-  for (int j = N - 2; j >= 0; j--) {
-    const int step = N - 2 - j, cur = step & 1, vcur = step % 3;
-    // v of the next reflector, published by this step's barrier.  Three buffers: the one of the previous step
-    // may still be read by wavefronts that are in that step's update (which comes after its barrier).
-    if (j > 0) stage(j - 1, (step + 1) % 3);
-    const float* vj = &vbuf[vcur][w * RT];
-    // rows 16 r + w > j  <=>  r >= (j - w) / 16 + 1 (for j >= w), else every r: first chunk of four that matters
-    const int rlo = j >= w ? (j - w) / 16 + 1 : 0;
-    const int c0 = rlo >> 2;
-    float part = 0.f;
+  for (int t = 0; t < TPW; t++)
 #pragma unroll
-    for (int c = 0; c < RT / 4; c++) {
-      if (c >= c0) {  // uniform over the wavefront
-        const float4 q = *reinterpret_cast<const float4*>(vj + 4 * c);
-        part += q.x * u[4 * c];
-        part += q.y * u[4 * c + 1];
-        part += q.z * u[4 * c + 2];
-        part += q.w * u[4 * c + 3];
+    for (int ct = 0; ct < 4; ct++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const int row = 16 * (4 * t + wave) + 4 * q4 + j, col = k0 + 16 * ct + l15;
+        acc[t][ct][j] = (row < N && col < N) ? Wb[(size_t)row * Np + col] : 0.f;
+      }
+  for (int p = npanel - 1; p >= 0; p--) {
+    const int j0 = BT_K * p;
+    __syncthreads();  // the previous block no longer reads vt, tl, zbuf
+    {  // the block's reflectors [row][16]: a straight copy, 16 bytes per access, every load issued before the first store
+      const f4* src = reinterpret_cast<const f4*>(Vb + (size_t)p * Np * BT_K);
+      constexpr int PER = ROWS * 4 / 256;  // 16-byte pieces per thread when the block covers every row
+      f4 piece[PER];
+#pragma unroll
+      for (int u = 0; u < PER; u++) {
+        const int e = tid + 256 * u, i = e >> 2;      // row i, quarter e & 3
+        piece[u] = (i >= j0 && i < N) ? src[e] : f4{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int u = 0; u < PER; u++) {
+        const int e = tid + 256 * u, i = e >> 2, m = 4 * (e & 3);
+        if (i >= j0) {
+          const bool last = j0 + m + 3 > N - 2;  // reflectors past N-2 do not exist: their slots were never written
+          float* d = &vt[i * VP + m];
+          d[0] = (!last || j0 + m <= N - 2) ? piece[u][0] : 0.f;
+          d[1] = (!last || j0 + m + 1 <= N - 2) ? piece[u][1] : 0.f;
+          d[2] = (!last || j0 + m + 2 <= N - 2) ? piece[u][2] : 0.f;
+          d[3] = (!last || j0 + m + 3 <= N - 2) ? piece[u][3] : 0.f;
+        }
       }
     }
-    red[cur][w][lane] = part;
+    tl[tid] = Tf[((size_t)b * npanel + p) * (BT_K * BT_K) + tid];
     __syncthreads();
-    float s = 0.f;
+    f4 z[4];
 #pragma unroll
-    for (int x = 0; x < 16; x++) s += red[cur][x][lane];
-    s *= tb[j];
+    for (int ct = 0; ct < 4; ct++) z[ct] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int c = 0; c < RT / 4; c++) {
-      if (c >= c0) {  // v_j is read a second time rather than kept: 64 rows of u leave no registers for it
-        const float4 q = *reinterpret_cast<const float4*>(vj + 4 * c);
-        u[4 * c] -= s * q.x;
-        u[4 * c + 1] -= s * q.y;
-        u[4 * c + 2] -= s * q.z;
-        u[4 * c + 3] -= s * q.w;
+    for (int t = 0; t < TPW; t++) {
+      const int rt = 4 * t + wave;
+      if (rt >= p) {  // uniform: rows 16 rt .. 16 rt + 15 reach beyond j0 = 16 p
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const float a = vt[(16 * rt + 4 * q4 + j) * VP + l15];
+#pragma unroll
+          for (int ct = 0; ct < 4; ct++) z[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, acc[t][ct][j], z[ct], 0, 0, 0);
+        }
       }
     }
-  }
-  if (U_out && live) {
-    float* Ub = U_out + (size_t)b * Np * Np;
 #pragma unroll
-    for (int r = 0; r < RT; r++) {
-      const int i = 16 * r + w;
-      if (i < N) Ub[(size_t)i * Np + k] = u[r];
+    for (int ct = 0; ct < 4; ct++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) zbuf[(wave * BT_K + 4 * q4 + j) * 64 + 16 * ct + l15] = z[ct][j];
+    __syncthreads();
+#pragma unroll
+    for (int ct = 0; ct < 4; ct++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const int o = (4 * q4 + j) * 64 + 16 * ct + l15;
+        z[ct][j] = (zbuf[o] + zbuf[BT_K * 64 + o]) + (zbuf[2 * BT_K * 64 + o] + zbuf[3 * BT_K * 64 + o]);
+      }
+    f4 z2[4];
+#pragma unroll
+    for (int ct = 0; ct < 4; ct++) z2[ct] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const float a = tl[l15 * BT_K + 4 * q4 + j];
+#pragma unroll
+      for (int ct = 0; ct < 4; ct++) z2[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, z[ct][j], z2[ct], 0, 0, 0);
+    }
+#pragma unroll
+    for (int t = 0; t < TPW; t++) {
+      const int rt = 4 * t + wave;
+      if (rt >= p) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const float a = -vt[(16 * rt + l15) * VP + 4 * q4 + j];
+#pragma unroll
+          for (int ct = 0; ct < 4; ct++) acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, z2[ct][j], acc[t][ct], 0, 0, 0);
+        }
+      }
     }
   }
   // Eq. 3-6, this strip's share
-  const double wk = live ? wgt[(size_t)b * Np + k] : 0.0;
+  double wk[4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ct++) {
+    const int col = k0 + 16 * ct + l15;
+    wk[ct] = col < N ? wgt[(size_t)b * Np + col] : 0.0;
+  }
   double* Cp = Cpart + ((size_t)b * nstrip + strip) * Np;
 #pragma unroll
-  for (int r = 0; r < RT; r++) {
-    const int i = 16 * r + w;
-    const double term = wave_sum(fabs((double)u[r]) * wk);
-    if (lane == 0 && i < N) Cp[i] = term;
-  }
+  for (int t = 0; t < TPW; t++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      double term = 0.0;
+#pragma unroll
+      for (int ct = 0; ct < 4; ct++) term += fabs((double)acc[t][ct][j]) * wk[ct];
+      term = row16_sum_dpp(term);
+      const int row = 16 * (4 * t + wave) + 4 * q4 + j;
+      if (l15 == 0 && row < N) Cp[row] = term;
+    }
 }
 
 // C(x) = sum over the strips of their shares, in a fixed order.
@@ -393,7 +530,7 @@ __global__ __launch_bounds__(256) void td_ics_finish_kernel(const double* __rest
 
 int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, const float* tauv, const float* Vc,
                     double* lam, int2* blk, double* tnorm, double* DP, double* UM, float* W, double* rn, int32_t* bad,
-                    double* sig, double* wgt, double* Cpart, float sv_rtol, bool vectors, float* C, float* C_out,
+                    double* sig, double* wgt, double* Cpart, float* Tf, float sv_rtol, bool vectors, float* C, float* C_out,
                     float* sigma_out, int32_t* info_out, hipStream_t st) {
   const int N = pl.N, Np = pl.Np, B = pl.B;
   TC_TIMED(PK_BISECT, 0, st, (td_bisect_kernel<<<dim3((N + 255) / 256, B), 256, (size_t)3 * N * 8, st>>>(dvec, evec, lam, blk, tnorm, bad, N, Np)));
@@ -407,18 +544,25 @@ int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, cons
   TC_TIMED(PK_TWISTED, 0, st, (td_twisted_kernel<<<dim3((N + 63) / 64, B), 64, (size_t)2 * N * 8, st>>>(dvec, evec, lam, blk, tnorm, DP, UM, W, rn, bad, N, Np)));
   TC_TIMED(PK_TWISTED, 1, st, (td_cluster_kernel<<<B, 256, 0, st>>>(lam, blk, tnorm, W, rn, bad, N, Np)));
   TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, rn, bad, sv_rtol, sig, wgt, sigma_out, info_out, N, Np)));
-  const int nstrip = (N + 63) / 64;
+  const int nstrip = (N + 63) / 64, npanel = (N + BT_K - 1) / BT_K;
   const dim3 gb(nstrip, B);
-  if (Np <= 64)
-    TC_TIMED(PK_BACKTF, 0, st, (td_backtransform_kernel<4><<<gb, 1024, 0, st>>>(W, Vc, tauv, wgt, Cpart, nullptr, N, Np, nstrip)));
-  else if (Np <= 256)
-    TC_TIMED(PK_BACKTF, 0, st, (td_backtransform_kernel<16><<<gb, 1024, 0, st>>>(W, Vc, tauv, wgt, Cpart, nullptr, N, Np, nstrip)));
-  else if (Np <= 576)
-    TC_TIMED(PK_BACKTF, 0, st, (td_backtransform_kernel<36><<<gb, 1024, 0, st>>>(W, Vc, tauv, wgt, Cpart, nullptr, N, Np, nstrip)));
-  else if (Np <= 1024)
-    TC_TIMED(PK_BACKTF, 0, st, (td_backtransform_kernel<64><<<gb, 1024, 0, st>>>(W, Vc, tauv, wgt, Cpart, nullptr, N, Np, nstrip)));
-  else
-    return TC_ERR_SHAPE;
+  TC_TIMED(PK_BACKTF, 0, st, (td_tfactor_kernel<<<dim3(npanel, B), 256, 0, st>>>(Vc, tauv, Tf, N, Np, npanel)));
+#define TC_BACKTF(TPW_)                                                                                                     \
+  {                                                                                                                         \
+    const size_t shm = ((size_t)64 * TPW_ * (BT_K + 1) + 4 * BT_K * 64 + BT_K * BT_K) * sizeof(float);                      \
+    if (shm > 64 * 1024 &&                                                                                                  \
+        hipFuncSetAttribute(reinterpret_cast<const void*>(td_backtransform_kernel<TPW_>),                                   \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)                            \
+      return TC_ERR_HIP;                                                                                                    \
+    TC_TIMED(PK_BACKTF, 1, st, (td_backtransform_kernel<TPW_><<<gb, 256, shm, st>>>(W, Vc, Tf, wgt, Cpart, N, Np, nstrip, npanel))); \
+  }
+  if (Np <= 64) TC_BACKTF(1)
+  else if (Np <= 128) TC_BACKTF(2)
+  else if (Np <= 256) TC_BACKTF(4)
+  else if (Np <= 576) TC_BACKTF(9)
+  else if (Np <= 1024) TC_BACKTF(16)
+  else return TC_ERR_SHAPE;
+#undef TC_BACKTF
   TC_TIMED(PK_ICS, 0, st, (td_ics_finish_kernel<<<dim3((N + 255) / 256, B), 256, 0, st>>>(Cpart, C, C_out, N, Np, nstrip)));
   return check_launch();
 }

@@ -13,7 +13,8 @@
 // dlatrd/dsytrd): inside a panel the reflectors v and the vectors w of the rank-2 updates
 // A <- A - v w^T - w v^T are kept in LDS (panels Vp, Wp) and applied on the fly to the column being
 // reduced and to the matrix-vector product; at the end of the panel the trailing matrix gets the
-// rank-2nb update on the matrix cores (both triangles: the matrix-vector product reads whole rows).
+// rank-2nb update on the matrix cores (computed for the lower triangle, stored to both: the matrix-vector
+// product reads whole rows).
 // G is symmetric and stored in full, so the product p = A v is formed as column sums over rows,
 // p_c = sum_i A[i][c] v_i: a lane owns two neighbouring columns, loads are 16 bytes wide and contiguous
 // across the wavefront, and no cross-lane reduction is needed; 4 row groups x 4 column groups of
@@ -29,22 +30,24 @@ constexpr int TD_THREADS = 1024;
 constexpr int TD_WAVES = TD_THREADS / 64;
 constexpr int TD_LDS_BYTES = 160 * 1024;  // LDS of one compute unit, all of it for the one workgroup
 
-// Panel width that fits the LDS next to the vectors: v, p and four rows of partial sums (7 vectors of Nr
-// doubles), the two panels (2 nb Nr doubles) and 1 KB of small scratch.
+constexpr int TD_RED = 2048;              // partial column sums of the matrix-vector product
+
+// Panel width that fits the LDS next to the current reflector and column (2 vectors of Nr doubles), the
+// partial sums, the two panels (2 nb Nr doubles) and 1 KB of small scratch.
 int tridiag_panel_width(int N) {
   const int Nr = round_up(N, 16);
-  long nb = ((long)TD_LDS_BYTES - 1024 - 7L * Nr * 8) / (16L * Nr);
+  long nb = ((long)TD_LDS_BYTES - 1024 - TD_RED * 8 - 2L * Nr * 8) / (16L * Nr);
   nb &= ~3L;
   return nb > 32 ? 32 : (int)nb;
 }
 size_t tridiag_lds_bytes(int N, int nb) {
   const int Nr = round_up(N, 16);
-  return (size_t)(2 * nb + 7) * Nr * 8 + 1024;
+  return (size_t)(2 * nb + 2) * Nr * 8 + TD_RED * 8 + 1024;
 }
 
-// Sum over the workgroup in a fixed order: lanes by the butterfly of lane 0, wavefronts left to right.
+// Sum over the workgroup in a fixed order: lanes as above, wavefronts left to right.
 __device__ inline double td_block_sum(double x, double* scratch, int wave, int lane) {
-  x = wave_sum(x);
+  x = wave_sum_dpp(x);
   if (lane == 0) scratch[wave] = x;
   __syncthreads();
   double s = 0.0;
@@ -58,7 +61,8 @@ __device__ inline double td_block_sum(double x, double* scratch, int wave, int l
 // dvec   [B][Np]      out: diagonal of T
 // evec   [B][Np]      out: evec[j] = T[j+1][j], j < N-1
 // tauv   [B][Np]      out: tau_j (0 for a reflector that is the identity)
-// Vc     [B][Np][Np]  out, float: row j holds v_j (zeros up to index j, 1 at j+1); rows j >= N-1 are not written
+// Vc     [B][Np/16][Np][16] out, float: the reflectors in blocks of sixteen, Vc[j / 16][i][j % 16] = v_j[i] (zeros up to
+//                     i = j, 1 at j + 1) -- the layout stage 3 copies into LDS; reflectors j >= N-1 are not written
 __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict__ G, int N, int Np, int nb,
                                                              double* __restrict__ dvec, double* __restrict__ evec,
                                                              float* __restrict__ tauv, float* __restrict__ Vc) {
@@ -68,8 +72,8 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
   double* Wp = Vp + (size_t)Nr * nb;                 // [Nr][nb] their update vectors
   double* vs = Wp + (size_t)Nr * nb;                 // [Nr] current reflector
   double* as = vs + Nr;                              // [Nr] current column
-  double* red = as + Nr;                             // [4][Nr] partial column sums of the four row groups
-  double* dots = red + 4 * (size_t)Nr;               // [64] W^T v and V^T v
+  double* red = as + Nr;                             // [nrg][128 ncg] partial column sums of the row groups, <= 2048 in all
+  double* dots = red + TD_RED;                       // [64] W^T v and V^T v
   double* wsum = dots + 64;                          // [16] wavefront partials of td_block_sum
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -113,45 +117,48 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
       }
       __syncthreads();
       // ---- p = A v over the trailing matrix (rows and columns j+1 .. N-1), as column sums -------------------
+      // Wavefront (rg, cg): column group cg = 128 columns (a lane owns two neighbours, one 16-byte load per row),
+      // row group rg = every nrg-th row.  As the trailing matrix shrinks there are fewer column groups and more
+      // row groups; sixteen rows are in flight per wavefront (16 KB), which is what it takes to keep a compute
+      // unit's share of the fabric busy at 2 us of latency.
       const int r0 = j + 1;
-      const int cbase = r0 & ~1;                 // column pairs start at an even column (16-byte loads)
-      const int npair = (N - cbase + 1) >> 1;
-      const int np4 = (npair + 3) >> 2;          // pairs per column group, <= 128
-      {
-        const int rg = wave & 3, cg = wave >> 2;
-        const int qa = cg * np4 + lane, qb = qa + 64;
-        const bool oka = lane < np4 && qa < npair, okb = lane + 64 < np4 && qb < npair;
-        const double* cola = A + cbase + 2 * (oka ? qa : 0);
-        const double* colb = A + cbase + 2 * (okb ? qb : 0);
-        d2 acca = d2{0.0, 0.0}, accb = d2{0.0, 0.0};
-        const bool two = np4 > 64;  // uniform: only matrices with more than 512 trailing columns need the second pair
-        for (int ib = r0 + rg; ib < N; ib += 32) {
-          d2 xa[8], xb[8];
-          double vi[8];
+      const int cbase = r0 & ~1;                 // column pairs start at an even column
+      const int ncols = N - cbase;
+      const int ncg = (ncols + 127) >> 7;        // <= 8 for N <= 1024
+      const int nrg = TD_WAVES / ncg;            // >= 2
+      const int pitch = ncg << 7;                // nrg * pitch <= 2048 partial sums
+#ifndef TD_PROBE_NO_MATVEC
+      if (wave < ncg * nrg) {
+        const int cg = wave % ncg, rg = wave / ncg;
+        const int c = cbase + (cg << 7) + 2 * lane;
+        const bool ok = c < N;                   // (an odd N reads the zero padding column N as the pair's second half)
+        const double* col = A + (ok ? c : cbase);
+        d2 acc = d2{0.0, 0.0};
+        for (int ib = r0 + rg; ib < N; ib += 16 * nrg) {
+          d2 x[16];
 #pragma unroll
-          for (int u = 0; u < 8; u++) {
-            const int i = ib + 4 * u;
-            const bool in = i < N;
-            const size_t ro = (size_t)(in ? i : r0) * Np;  // a row past the end is replaced by a valid one and gets weight 0
-            vi[u] = in ? vs[i] : 0.0;
-            xa[u] = *reinterpret_cast<const d2*>(cola + ro);
-            if (two) xb[u] = *reinterpret_cast<const d2*>(colb + ro);
+          for (int u = 0; u < 16; u++) {
+            const int i = ib + u * nrg;
+            x[u] = *reinterpret_cast<const d2*>(col + (size_t)(i < N ? i : r0) * Np);  // a row past the end: a valid one, weight 0
           }
 #pragma unroll
-          for (int u = 0; u < 8; u++) {
-            acca += xa[u] * vi[u];
-            if (two) accb += xb[u] * vi[u];
+          for (int u = 0; u < 16; u++) {
+            const int i = ib + u * nrg;
+            acc += x[u] * (i < N ? vs[i] : 0.0);
           }
         }
-        if (oka) { red[rg * Nr + cbase + 2 * qa] = acca.x; red[rg * Nr + cbase + 2 * qa + 1] = acca.y; }
-        if (okb) { red[rg * Nr + cbase + 2 * qb] = accb.x; red[rg * Nr + cbase + 2 * qb + 1] = accb.y; }
+        if (ok) {
+          red[rg * pitch + (c - cbase)] = acc.x;
+          red[rg * pitch + (c - cbase) + 1] = acc.y;
+        }
       }
+#endif
       // ---- W^T v and V^T v for the panel's earlier columns: one wavefront per dot product ------------------
       for (int id = wave; id < 2 * jj; id += TD_WAVES) {
         const double* P = id < jj ? Wp + id : Vp + (id - jj);
         double s = 0.0;
         for (int i = r0 + lane; i < N; i += 64) s += P[i * nb] * vs[i];
-        s = wave_sum(s);
+        s = wave_sum_dpp(s);
         if (lane == 0) dots[id] = s;
       }
       __syncthreads();
@@ -159,7 +166,7 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
       const int c = r0 + tid;
       double pc = 0.0, vc = 0.0;
       if (c < N) {
-        pc = (red[c] + red[Nr + c]) + (red[2 * Nr + c] + red[3 * Nr + c]);
+        for (int g = 0; g < nrg; g++) pc += red[g * pitch + (c - cbase)];  // fixed order
         for (int k = 0; k < jj; k++) pc -= Vp[c * nb + k] * dots[k] + Wp[c * nb + k] * dots[jj + k];
         pc *= tau;
         vc = vs[c];
@@ -175,7 +182,7 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
     for (int jj = 0; jj < cnt; jj++) {
       const int j = j0 + jj;
       for (int i = tid; i < N; i += TD_THREADS)
-        Vout[(size_t)j * Np + i] = i > j ? (float)Vp[i * nb + jj] : 0.f;
+        Vout[((size_t)(j >> 4) * Np + i) * 16 + (j & 15)] = i > j ? (float)Vp[i * nb + jj] : 0.f;
     }
     if (kcols > cnt) {  // a last, shorter panel: columns cnt .. kcols-1 still hold the previous panel
       for (int e = tid; e < Nr * (kcols - cnt); e += TD_THREADS) {
@@ -192,42 +199,56 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
       const int base = jend & ~15;
       const int nrt = (N - base + 15) >> 4, ncc = (N - base + 63) >> 6;
       const int ksteps = kcols >> 2;
-      for (int task = wave; task < nrt * ncc; task += TD_WAVES) {
-        const int rt = base + 16 * (task / ncc), ct = base + 64 * (task % ncc);
-        d4 acc[4];
+#ifndef TD_PROBE_NO_SYR2K
+      // Only strips that reach the diagonal or lie below it are computed (column chunk b of row tile a with
+      // 64 b <= 16 a + 15); a strip strictly below the diagonal also writes its mirror image, which is a
+      // strip that is skipped.  Strips are dealt to the wavefronts round-robin in this order.
+      int idx = 0;
+      for (int a = 0; a < nrt; a++) {
+        const int nb_a = min(ncc, (a >> 2) + 1);
+        for (int bch = 0; bch < nb_a; bch++, idx++) {
+          if ((idx & (TD_WAVES - 1)) != wave) continue;  // uniform over the wavefront
+          const int rt = base + 16 * a, ct = base + 64 * bch;
+          const bool below = 64 * bch + 63 < 16 * a;
+          d4 acc[4];
 #pragma unroll
-        for (int t = 0; t < 4; t++) {
-          const int cc = ct + 16 * t + l15;
+          for (int t = 0; t < 4; t++) {
+            const int cc = ct + 16 * t + l15;
 #pragma unroll
-          for (int e = 0; e < 4; e++) {
-            const int rr = rt + 4 * e + q4;
-            acc[t][e] = (rr < N && cc < N) ? A[(size_t)rr * Np + cc] : 0.0;
+            for (int e = 0; e < 4; e++) {
+              const int rr = rt + 4 * e + q4;
+              acc[t][e] = (rr < N && cc < N) ? A[(size_t)rr * Np + cc] : 0.0;
+            }
           }
-        }
-        const int arow = min(rt + l15, Nr - 1);
-        for (int half = 0; half < 2; half++) {
-          const double* L = half == 0 ? Vp : Wp;   // row factor
-          const double* R = half == 0 ? Wp : Vp;   // column factor
-          for (int ks = 0; ks < ksteps; ks++) {
-            const int k = 4 * ks + q4;
-            const double a = -L[arow * nb + k];
+          const int arow = min(rt + l15, Nr - 1);
+          for (int half = 0; half < 2; half++) {
+            const double* L = half == 0 ? Vp : Wp;   // row factor
+            const double* R = half == 0 ? Wp : Vp;   // column factor
+            for (int ks = 0; ks < ksteps; ks++) {
+              const int k = 4 * ks + q4;
+              const double av = -L[arow * nb + k];
 #pragma unroll
-            for (int t = 0; t < 4; t++) {
-              const int crow = min(ct + 16 * t + l15, Nr - 1);
-              acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, R[crow * nb + k], acc[t], 0, 0, 0);
+              for (int t = 0; t < 4; t++) {
+                const int crow = min(ct + 16 * t + l15, Nr - 1);
+                acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, R[crow * nb + k], acc[t], 0, 0, 0);
+              }
+            }
+          }
+#pragma unroll
+          for (int t = 0; t < 4; t++) {
+            const int cc = ct + 16 * t + l15;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              const int rr = rt + 4 * e + q4;
+              if (rr >= jend && cc >= jend && rr < N && cc < N) {
+                A[(size_t)rr * Np + cc] = acc[t][e];
+                if (below) A[(size_t)cc * Np + rr] = acc[t][e];
+              }
             }
           }
         }
-#pragma unroll
-        for (int t = 0; t < 4; t++) {
-          const int cc = ct + 16 * t + l15;
-#pragma unroll
-          for (int e = 0; e < 4; e++) {
-            const int rr = rt + 4 * e + q4;
-            if (rr >= jend && cc >= jend && rr < N && cc < N) A[(size_t)rr * Np + cc] = acc[t][e];
-          }
-        }
       }
+#endif
     }
     __syncthreads();  // the rewritten matrix is visible to the whole workgroup
   }

@@ -197,13 +197,18 @@ def seeded_batch(w, images, progress=None):
            w.noise, w.qkv_mode, tuple(images))
     if key in _LAST_BATCH:
         return _LAST_BATCH[key]
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    from threadpoolctl import threadpool_limits
     weights = projection_weights(w) if w.qkv_mode == "proj" else None
     items, t0 = [], time.time()
-    for n, b in enumerate(images):
-        items.append(make_image(w, b, weights))
-        if progress and time.time() - t0 > 30:
-            progress("%s: generated %d of %d images" % (w.name, n + 1, len(images)))
-            t0 = time.time()
+    # every image has its own seed: generating several at a time (single-threaded BLAS each) changes nothing
+    with threadpool_limits(limits=1), ThreadPoolExecutor(max_workers=max(1, min(16, os.cpu_count() or 1))) as pool:
+        for n, it in enumerate(pool.map(lambda b: make_image(w, b, weights), list(images))):
+            items.append(it)
+            if progress and time.time() - t0 > 30:
+                progress("%s: generated %d of %d images" % (w.name, n + 1, len(images)))
+                t0 = time.time()
     batch = {k: np.stack([it[k] for it in items]) for k in ("X", "Q", "K", "V")}
     _LAST_BATCH.clear()
     _LAST_BATCH[key] = batch
@@ -271,12 +276,16 @@ def run_all_stages(w, images=None, eig=tc.TC_EIG_F64, oracle_images=None, tight=
         rep["jaccard"] = len(a & b) / len(a | b)
         return rep
 
-    # The oracle is numpy: its LAPACK and BLAS calls release the interpreter lock, so a few images at a time
-    # use the host's cores better than one (the large batches would otherwise take minutes).
+    # The oracle is numpy: its LAPACK and BLAS calls release the interpreter lock.  One image per core with
+    # single-threaded BLAS is several times faster than one image at a time with threaded BLAS (and threaded
+    # BLAS under a thread pool is slower than either).
+    import os
     from concurrent.futures import ThreadPoolExecutor
+    from threadpoolctl import threadpool_limits
+    workers = max(1, min(16, os.cpu_count() or 1, len(idx)))
     jac, ties, done = [], [], 0
     t0 = time.time()
-    with ThreadPoolExecutor(max_workers=min(4, max(1, len(idx)))) as pool:
+    with threadpool_limits(limits=1), ThreadPoolExecutor(max_workers=workers) as pool:
         for rep in pool.map(lambda ni: one_image(*ni), list(enumerate(idx))):
             done += 1
             if progress and time.time() - t0 > 30:   # a long oracle loop says where it is (a silent run looks hung)
