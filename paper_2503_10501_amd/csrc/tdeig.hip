@@ -278,6 +278,7 @@ __global__ __launch_bounds__(256) void td_cluster_kernel(const double* __restric
 // turns the unnormalised vector of slot k into its term of C.  Also the optional outputs of tc_ipgs_score that
 // do not need the vectors: sigma sorted in descending order, and info.
 __global__ __launch_bounds__(256) void td_weights_kernel(const double* __restrict__ lam, const double* __restrict__ rn,
+                                                         const double* __restrict__ tnorm,
                                                          const int32_t* __restrict__ bad, float sv_rtol,
                                                          double* __restrict__ sig, double* __restrict__ wgt,
                                                          float* __restrict__ sigma_out, int32_t* __restrict__ info_out,
@@ -287,6 +288,9 @@ __global__ __launch_bounds__(256) void td_weights_kernel(const double* __restric
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const double* lb = lam + (size_t)b * Np;
   double* sb = sig + (size_t)b * Np;
+  // Eigenvalues come out of the reduction and the bisection with an absolute error of a few eps ||T||: what lies
+  // below that is zero (an all-zero matrix, the null space of a rank-deficient one).
+  const double floor0 = tnorm[b] > 0.0 ? 8.0 * TD_EPS * tnorm[b] : DBL_MAX;  // (every eigenvalue of an all-zero matrix is zero)
   double mx = 0.0;
   int nanflag = 0;
   for (int i = tid; i < Np; i += 256) {
@@ -294,7 +298,7 @@ __global__ __launch_bounds__(256) void td_weights_kernel(const double* __restric
     if (i < N) {
       const double l = lb[i];
       nanflag |= (l == l) ? 0 : 1;
-      s = l > 0.0 ? sqrt(l) : 0.0;
+      s = l > floor0 ? sqrt(l) : 0.0;
     }
     sb[i] = s;
     mx = fmax(mx, s);
@@ -538,12 +542,12 @@ int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, cons
   while (n2 < N) n2 <<= 1;
   const size_t shm_sig = sigma_out ? (size_t)n2 * sizeof(float) : 0;
   if (!vectors) {  // eigenvalues only (the information-quantity tool)
-    TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, nullptr, bad, 0.f, sig, nullptr, sigma_out, info_out, N, Np)));
+    TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, nullptr, tnorm, bad, 0.f, sig, nullptr, sigma_out, info_out, N, Np)));
     return check_launch();
   }
   TC_TIMED(PK_TWISTED, 0, st, (td_twisted_kernel<<<dim3((N + 63) / 64, B), 64, (size_t)2 * N * 8, st>>>(dvec, evec, lam, blk, tnorm, DP, UM, W, rn, bad, N, Np)));
   TC_TIMED(PK_TWISTED, 1, st, (td_cluster_kernel<<<B, 256, 0, st>>>(lam, blk, tnorm, W, rn, bad, N, Np)));
-  TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, rn, bad, sv_rtol, sig, wgt, sigma_out, info_out, N, Np)));
+  TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, rn, tnorm, bad, sv_rtol, sig, wgt, sigma_out, info_out, N, Np)));
   const int nstrip = (N + 63) / 64, npanel = (N + BT_K - 1) / BT_K;
   const dim3 gb(nstrip, B);
   TC_TIMED(PK_BACKTF, 0, st, (td_tfactor_kernel<<<dim3(npanel, B), 256, 0, st>>>(Vc, tauv, Tf, N, Np, npanel)));
