@@ -94,8 +94,10 @@ typedef struct {
                            0 => 2e-9 * min(1, 576 / N) (3e-6 for TC_EIG_F32)                    */
   int32_t eig_dtype;    /* tc_eig_dtype                                                         */
   int32_t eig_method;   /* tc_eig_method; TC_EIG_TRIDIAGONAL with TC_EIG_F32 or n_vis > 1024 is rejected (TC_ERR_PARAM) */
-  int32_t stream_groups; /* Jacobi eigensolver: 0 = cut the batch into 1, 2 or 4 groups (by the amount of work) that
-                            run on helper streams and overlap; 1 = everything on `stream`; 2..4 = that many groups */
+  int32_t stream_groups; /* groups of images whose eigensolver work (tridiagonal route: attention and Gram matrix
+                            too) runs on helper streams and overlaps: 0 = the library chooses (Jacobi: 1, 2 or 4 by
+                            the amount of work; tridiagonal: 2 from 16 images on), 1 = everything on `stream`,
+                            2..4 = that many groups.  Results do not depend on it.                      */
 } tc_params;
 
 /* Bytes of scratch that any entry point may need for `p` (0 if p is invalid). */

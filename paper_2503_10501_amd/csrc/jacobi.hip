@@ -893,7 +893,7 @@ __global__ void jacobi_sweep_end(const double* __restrict__ offpart, EigState* _
 constexpr int MAX_GROUPS = 4;
 struct StreamPool {
   hipStream_t s[MAX_GROUPS - 1];
-  hipEvent_t fork, join[MAX_GROUPS - 1];  // re-recorded by every call (a wait captures the state at the time it is enqueued)
+  hipEvent_t fork, join[MAX_GROUPS - 1], stage[MAX_GROUPS - 1];  // re-recorded by every call (a wait captures the state at the time it is enqueued)
   bool ok = false;
 };
 static std::mutex g_pool_mutex;
@@ -905,7 +905,7 @@ static StreamPool* helper_streams() {
   std::lock_guard<std::mutex> lock(g_pool_mutex);
   StreamPool& pool = g_pools[dev];
   if (!pool.ok) {
-    int ns = 0, ne = 0;
+    int ns = 0, ne = 0, nst = 0;
     bool good = hipEventCreateWithFlags(&pool.fork, hipEventDisableTiming) == hipSuccess;
     const bool have_fork = good;
     while (good && ns < MAX_GROUPS - 1) {
@@ -916,15 +916,64 @@ static StreamPool* helper_streams() {
       good = hipEventCreateWithFlags(&pool.join[ne], hipEventDisableTiming) == hipSuccess;
       if (good) ne++;
     }
+    while (good && nst < MAX_GROUPS - 1) {
+      good = hipEventCreateWithFlags(&pool.stage[nst], hipEventDisableTiming) == hipSuccess;
+      if (good) nst++;
+    }
     if (!good) {  // release what was created; the caller falls back to one stream
       if (have_fork) (void)hipEventDestroy(pool.fork);
       for (int i = 0; i < ns; i++) (void)hipStreamDestroy(pool.s[i]);
       for (int i = 0; i < ne; i++) (void)hipEventDestroy(pool.join[i]);
+      for (int i = 0; i < nst; i++) (void)hipEventDestroy(pool.stage[i]);
       return nullptr;
     }
     pool.ok = true;
   }
   return &pool;
+}
+
+// Fork: streams[0] = st, streams[1 .. n-1] = helper streams that wait for what is already enqueued on st.
+// Returns the number of streams available (1 if the helpers could not be created).  The pool's events are
+// shared by all calls on the device, so the pool stays locked until join_streams(): two host threads enqueuing
+// at the same time cannot interleave their record/wait pairs.
+static std::unique_lock<std::mutex>& pool_lock() {
+  static thread_local std::unique_lock<std::mutex> lock(g_pool_mutex, std::defer_lock);
+  return lock;
+}
+int fork_streams(hipStream_t st, int groups, hipStream_t* streams) {
+  streams[0] = st;
+  if (groups > MAX_GROUPS) groups = MAX_GROUPS;
+  StreamPool* pool = groups > 1 ? helper_streams() : nullptr;
+  if (!pool) return 1;
+  pool_lock().lock();
+  (void)hipEventRecord(pool->fork, st);
+  for (int g = 1; g < groups; g++) {
+    streams[g] = pool->s[g - 1];
+    (void)hipStreamWaitEvent(streams[g], pool->fork, 0);
+  }
+  return groups;
+}
+// Between a fork and its join: what is enqueued on stream g + 1 from now on waits for what is on stream g now
+// (g = 0 is the caller's stream).  Lets the groups start one after the other instead of all at once.
+void stagger_streams(hipStream_t st, int g, int groups) {
+  if (g + 1 >= groups) return;
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  StreamPool& pool = g_pools[dev];
+  (void)hipEventRecord(pool.stage[g], g == 0 ? st : pool.s[g - 1]);
+  (void)hipStreamWaitEvent(pool.s[g], pool.stage[g], 0);
+}
+// Join: st waits for everything enqueued on the helper streams since the fork.
+void join_streams(hipStream_t st, int groups) {
+  if (groups <= 1) return;
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  StreamPool& pool = g_pools[dev];
+  for (int g = 0; g < groups - 1; g++) {
+    (void)hipEventRecord(pool.join[g], pool.s[g]);
+    (void)hipStreamWaitEvent(st, pool.join[g], 0);
+  }
+  pool_lock().unlock();
 }
 
 template <typename T>
@@ -968,28 +1017,15 @@ static int run_jacobi(const Plan& pl, T* G, float* U, T* R, double* offpart, Eig
   int groups = pl.groups > 0 ? pl.groups : (tiles >= 1152 ? 4 : (tiles >= 576 ? 2 : 1));
   if (groups > pl.B) groups = pl.B;
   if (profiling_active()) groups = 1;  // per-kernel timing wants kernels that run alone
-  StreamPool* pool = groups > 1 ? helper_streams() : nullptr;
-  if (!pool) groups = 1;
-  // The pool's events are shared by all calls on the device; two host threads enqueuing at the same time
-  // must not interleave their record/wait pairs.
-  std::unique_lock<std::mutex> lock(g_pool_mutex, std::defer_lock);
-  if (groups > 1) {
-    lock.lock();
-    (void)hipEventRecord(pool->fork, st);
-    for (int g = 0; g < groups - 1; g++) (void)hipStreamWaitEvent(pool->s[g], pool->fork, 0);
-  }
+  hipStream_t streams[MAX_GROUPS];
+  groups = fork_streams(st, groups, streams);
   const int per = (pl.B + groups - 1) / groups;
   for (int g = 0; g < groups; g++) {
     const int img0 = g * per, nimg = pl.B - img0 < per ? pl.B - img0 : per;
     if (nimg <= 0) continue;
-    enqueue_group<T>(pl, G, U, R, offpart, state, img0, nimg, g == 0 ? st : pool->s[g - 1]);
+    enqueue_group<T>(pl, G, U, R, offpart, state, img0, nimg, streams[g]);
   }
-  if (groups > 1) {
-    for (int g = 0; g < groups - 1; g++) {
-      (void)hipEventRecord(pool->join[g], pool->s[g]);
-      (void)hipStreamWaitEvent(st, pool->join[g], 0);
-    }
-  }
+  join_streams(st, groups);
   return check_launch();
 }
 

@@ -92,6 +92,10 @@ int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, cons
                     double* sig, double* wgt, double* Cpart, float* Tf, float sv_rtol, bool vectors, float* C, float* C_out,
                     float* sigma_out, int32_t* info_out, hipStream_t st);
 int direct_eigenvalues(const Plan& pl, const tc_params* p, float* sigma, int32_t* info, void* ws, hipStream_t st);  // api.hip
+// helper streams of the library (jacobi.hip): up to 4 streams that run side by side and meet again
+int fork_streams(hipStream_t st, int groups, hipStream_t* streams);
+void stagger_streams(hipStream_t st, int g, int groups);
+void join_streams(hipStream_t st, int groups);
 int launch_topk(const Plan& pl, const float* E, int32_t* order, hipStream_t st);
 int launch_similarity(const Plan& pl, int dtype, const void* metric, const int32_t* order, float* rnorm, float* sim,
                       hipStream_t st);

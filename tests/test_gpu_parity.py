@@ -347,7 +347,8 @@ def test_results_do_not_depend_on_what_the_workspace_held_before(name, method):
             assert torch.equal(runs[0][k], r[k]), k
 
 
-def test_results_do_not_depend_on_the_number_of_stream_groups():
+@pytest.mark.parametrize("method", list(METHODS))
+def test_results_do_not_depend_on_the_number_of_stream_groups(method):
     # images are independent: cutting the batch into 1..4 groups on helper streams (and the launch shapes
     # that follow from the group size) must not change a single bit
     tc, gu, _, _, _ = _mods()
@@ -356,7 +357,7 @@ def test_results_do_not_depend_on_the_number_of_stream_groups():
     b = make_batch(w)
     runs = []
     for groups in (1, 2, 3, 4, 0):
-        p = tc.params_for(w, stream_groups=groups, eig_method=METHODS["jacobi"])
+        p = tc.params_for(w, stream_groups=groups, eig_method=METHODS[method])
         args = [gu.dev(b[k], p) for k in ("Q", "K", "V")] + [gu.dev(b["X"][:, w.n_sys:w.n_sys + w.n_vis], p)]
         runs.append(gu.compress(p, *args))
     for r in runs[1:]:
