@@ -83,12 +83,15 @@ def to_storage(a, dtype):
 # ----------------------------------------------------------------------------
 # Eq. 3-1, 3-2, 3-7: attention output and attention score of the visual tokens
 # ----------------------------------------------------------------------------
-def attn_output(Q, K, V, n_sys, n_vis, causal=True, scale=None):
+def attn_output(Q, K, V, n_sys, n_vis, causal=True, scale=None, n_prompt_q=0):
     """Q, K, V: [H, L, d_h].  Returns Z_visual [N, H*d_h] and S [N] (float64).
 
     Eq. 3-1: A = softmax(Q K^T / sqrt(d_k)) row-wise over the allowed keys.
     Eq. 3-2: Z = A V; its rows L_s .. L_s+L_v are Z_visual (Section 3.2.2).
     Eq. 3-7: S(x) = mean over heads and visual queries of A[:, :, x].
+    Text-guided variant of Eq. 3-7 (not in the paper, which keeps A^2 visual-by-visual): with
+    n_prompt_q = P > 0 the mean also runs over the P query rows that follow the visual block (the
+    first P prompt tokens), i.e. over the H * (L_v + P) entries of column x; P = 0 is Eq. 3-7.
     """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -96,20 +99,22 @@ def attn_output(Q, K, V, n_sys, n_vis, causal=True, scale=None):
     H, L, dh = Q.shape
     if scale is None:
         scale = 1.0 / np.sqrt(dh)
-    rows = np.arange(n_sys, n_sys + n_vis)
+    if n_prompt_q < 0 or n_sys + n_vis + n_prompt_q > L:
+        raise ValueError("n_prompt_q rows must lie inside the sequence, after the visual block")
+    rows = np.arange(n_sys, n_sys + n_vis + n_prompt_q)        # visual queries, then the prompt queries
     Z = np.zeros((n_vis, H * dh))
     S = np.zeros(n_vis)
     for h in range(H):
-        logits = (Q[h, rows] @ K[h].T) * scale                 # [N, L]
+        logits = (Q[h, rows] @ K[h].T) * scale                 # [N + P, L]
         if causal:
             allowed = np.arange(L)[None, :] <= rows[:, None]
             logits = np.where(allowed, logits, -np.inf)
         logits = logits - logits.max(axis=1, keepdims=True)
         A = np.exp(logits)
         A = A / A.sum(axis=1, keepdims=True)
-        Z[:, h * dh:(h + 1) * dh] = A @ V[h]
+        Z[:, h * dh:(h + 1) * dh] = A[:n_vis] @ V[h]
         S += A[:, n_sys:n_sys + n_vis].sum(axis=0)
-    S /= H * n_vis
+    S /= H * (n_vis + n_prompt_q)
     return Z, S
 
 
@@ -237,9 +242,9 @@ def average_rows(X, merge_dst, out_dtype=None):
 # whole path for one image
 # ----------------------------------------------------------------------------
 def compress(Q, K, V, X_vis, n_sys, n_vis, k_prune, k_final, lam=0.5, norm=NORM_MINMAX,
-             causal=True, dtype="bf16", sv_rtol=0.0, scale=None):
+             causal=True, dtype="bf16", sv_rtol=0.0, scale=None, n_prompt_q=0):
     """attention output -> stored O -> IPGS score -> prune -> merge, for one image."""
-    Z, S = attn_output(Q, K, V, n_sys, n_vis, causal, scale)
+    Z, S = attn_output(Q, K, V, n_sys, n_vis, causal, scale, n_prompt_q)
     O = to_storage(Z, dtype)
     E, C, sigma = ipgs_score(O, S, lam, norm, sv_rtol)
     order = select_topk(E, k_prune)

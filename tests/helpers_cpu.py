@@ -40,13 +40,14 @@ def hestenes_svd(M, tol=1e-15, max_sweeps=60):
     return J.T[:, order], sigma[order]          # J M = diag(sigma) W^T  =>  M = J^T diag(sigma) W^T
 
 
-def softmax_attention_loops(Q, K, V, n_sys, n_vis, causal, scale):
-    """Eq. 3-1/3-2/3-7 with scalar Python loops (tiny sizes only)."""
+def softmax_attention_loops(Q, K, V, n_sys, n_vis, causal, scale, n_prompt_q=0):
+    """Eq. 3-1/3-2/3-7 with scalar Python loops (tiny sizes only); n_prompt_q more query rows after the
+    visual block enter the column means (they produce no row of Z)."""
     H, L, dh = Q.shape
     Z = np.zeros((n_vis, H * dh))
     S = np.zeros(n_vis)
     for h in range(H):
-        for q in range(n_vis):
+        for q in range(n_vis + n_prompt_q):
             p = n_sys + q
             last = p if causal else L - 1
             logit = [sum(float(Q[h, p, e]) * float(K[h, k, e]) for e in range(dh)) * scale
@@ -56,11 +57,12 @@ def softmax_attention_loops(Q, K, V, n_sys, n_vis, causal, scale):
             tot = sum(w)
             for k, wk in enumerate(w):
                 a = wk / tot
-                for e in range(dh):
-                    Z[q, h * dh + e] += a * float(V[h, k, e])
+                if q < n_vis:
+                    for e in range(dh):
+                        Z[q, h * dh + e] += a * float(V[h, k, e])
                 if n_sys <= k < n_sys + n_vis:
                     S[k - n_sys] += a
-    return Z, S / (H * n_vis)
+    return Z, S / (H * (n_vis + n_prompt_q))
 
 
 def best_subset_by_sum(E, k):

@@ -78,6 +78,60 @@ def test_matches_scalar_loops_including_attention_score(rng):
         np.testing.assert_allclose(S, Sl, rtol=1e-12)
 
 
+# ---- text-guided variant of Eq. 3-7: the first P prompt rows join the visual query rows ----
+def test_prompt_rows_uniform_attention_closed_form(rng):
+    # Q = 0, causal: a query at position p spreads 1/(p+1) over keys 0..p; every prompt row sees every
+    # visual key, so S(x) = [sum_{q >= x} 1/(L_s+q+1) + sum_{t < P} 1/(L_s+N+t+1)] / (N + P).
+    H, L, dh, Ls, N, P = 2, 30, 4, 8, 11, 6
+    _, K, V = _rand(rng, H, L, dh)
+    Z, S = orc.attn_output(np.zeros((H, L, dh)), K, V, Ls, N, causal=True, n_prompt_q=P)
+    tail = sum(1.0 / (Ls + N + t + 1) for t in range(P))
+    S_expect = np.array([(sum(1.0 / (Ls + q + 1) for q in range(x, N)) + tail) / (N + P) for x in range(N)])
+    np.testing.assert_allclose(S, S_expect, rtol=1e-13)
+    Z0, _ = orc.attn_output(np.zeros((H, L, dh)), K, V, Ls, N, causal=True)
+    np.testing.assert_array_equal(Z, Z0)              # the attention output does not depend on P
+
+
+def test_prompt_rows_match_scalar_loops_and_reduce_to_eq_3_7(rng):
+    H, L, dh, Ls, N = 2, 18, 4, 5, 7
+    Q, K, V = _rand(rng, H, L, dh)
+    for causal in (True, False):
+        for P in (0, 1, 5, L - Ls - N):
+            Z, S = orc.attn_output(Q, K, V, Ls, N, causal=causal, scale=0.41, n_prompt_q=P)
+            Zl, Sl = softmax_attention_loops(Q, K, V, Ls, N, causal, 0.41, P)
+            np.testing.assert_allclose(Z, Zl, rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(S, Sl, rtol=1e-12)
+        Z, S = orc.attn_output(Q, K, V, Ls, N, causal=causal, scale=0.41, n_prompt_q=0)
+        Z0, S0 = orc.attn_output(Q, K, V, Ls, N, causal=causal, scale=0.41)
+        np.testing.assert_array_equal(S, S0)
+        np.testing.assert_array_equal(Z, Z0)
+
+
+def test_prompt_rows_are_a_weighted_mix_of_two_visual_style_means(rng):
+    # the mean over N + P rows is the row-count-weighted mean of the visual-row mean (Eq. 3-7) and of the
+    # mean over the P prompt rows alone, which is Eq. 3-7 of a sequence whose "visual" queries are the
+    # prompt rows: computed here from the full softmax of torch's attention with a one-hot value matrix
+    H, L, dh, Ls, N, P = 3, 28, 8, 8, 10, 7
+    Q, K, V = _rand(rng, H, L, dh)
+    _, S = orc.attn_output(Q, K, V, Ls, N, causal=True, n_prompt_q=P)
+    _, S_vis = orc.attn_output(Q, K, V, Ls, N, causal=True)
+    tq, tk = (torch.from_numpy(np.ascontiguousarray(a)) for a in (Q, K))
+    eye = torch.eye(L, dtype=torch.float64).expand(H, L, L)      # values = identity: the output IS the matrix A
+    A = torch.nn.functional.scaled_dot_product_attention(tq, tk, eye, is_causal=True).numpy()
+    S_prompt = A[:, Ls + N:Ls + N + P, Ls:Ls + N].mean(axis=(0, 1))
+    np.testing.assert_allclose(S, (N * S_vis + P * S_prompt) / (N + P), rtol=1e-12)
+
+
+def test_prompt_rows_out_of_range_is_an_error(rng):
+    import pytest
+    H, L, dh, Ls, N = 1, 10, 4, 2, 5
+    Q, K, V = _rand(rng, H, L, dh)
+    with pytest.raises(ValueError):
+        orc.attn_output(Q, K, V, Ls, N, n_prompt_q=L - Ls - N + 1)
+    with pytest.raises(ValueError):
+        orc.attn_output(Q, K, V, Ls, N, n_prompt_q=-1)
+
+
 def test_attention_score_mass_balance(rng):
     # full (non-causal) softmax: the visual columns of each row hold 1 - (mass on text keys);
     # with no text tokens at all the scores sum to exactly 1.

@@ -41,8 +41,17 @@ def _rng():
 def _mutant_attn(kind):
     real = orc.attn_output
 
-    def f(Q, K, V, n_sys, n_vis, causal=True, scale=None):
-        Z, S = real(Q, K, V, n_sys, n_vis, causal, scale)
+    def f(Q, K, V, n_sys, n_vis, causal=True, scale=None, n_prompt_q=0):
+        Z, S = real(Q, K, V, n_sys, n_vis, causal, scale, n_prompt_q)
+        if kind == "prompt_rows_divided_by_visual_count":
+            return Z, S * (n_vis + n_prompt_q) / n_vis
+        if kind == "prompt_rows_ignored":
+            return real(Q, K, V, n_sys, n_vis, causal, scale, 0)
+        if kind == "prompt_rows_taken_before_the_visual_block":
+            if n_prompt_q == 0 or n_sys < n_prompt_q:
+                return Z, S
+            _, S_shift = real(Q, K, V, n_sys - n_prompt_q, n_vis + n_prompt_q, causal, scale, 0)
+            return Z, S_shift[n_prompt_q:]
         if kind == "score_not_averaged_over_heads":
             return Z, S * np.asarray(Q).shape[0]
         if kind == "score_of_rows_instead_of_columns":
@@ -80,6 +89,22 @@ def test_attention_mutants_are_caught(monkeypatch, kind):
         except AssertionError:
             failed += 1
     assert failed >= 1, "mutant %s slipped through the attention pins" % kind
+
+
+@pytest.mark.parametrize("kind", ["prompt_rows_divided_by_visual_count", "prompt_rows_ignored",
+                                  "prompt_rows_taken_before_the_visual_block"])
+def test_prompt_row_mutants_are_caught(monkeypatch, kind):
+    monkeypatch.setattr(orc, "attn_output", _mutant_attn(kind))
+    pins = [t_attn.test_prompt_rows_uniform_attention_closed_form,
+            t_attn.test_prompt_rows_match_scalar_loops_and_reduce_to_eq_3_7,
+            t_attn.test_prompt_rows_are_a_weighted_mix_of_two_visual_style_means]
+    failed = 0
+    for pin in pins:
+        try:
+            pin(_rng())
+        except AssertionError:
+            failed += 1
+    assert failed >= 2, "mutant %s slipped through the prompt-row pins" % kind
 
 
 def _mutant_ics(kind):
