@@ -98,6 +98,10 @@ typedef struct {
                             too) runs on helper streams and overlaps: 0 = the library chooses (Jacobi: 1, 2 or 4 by
                             the amount of work; tridiagonal: 2 from 16 images on), 1 = everything on `stream`,
                             2..4 = that many groups.  Results do not depend on it.                      */
+  int32_t n_prompt_queries; /* P, text-guided variant of Eq. 3-7: the P query rows after the visual block (positions
+                            vis_start + n_vis .. + P - 1) join the visual query rows in the column mean, which
+                            then runs over H * (n_vis + P) entries; 0 <= P <= seq_len - vis_start - n_vis.
+                            0 = Eq. 3-7 as printed.  The attention output O is that of the visual rows either way. */
 } tc_params;
 
 /* Bytes of scratch that any entry point may need for `p` (0 if p is invalid). */

@@ -41,16 +41,17 @@ class tc_params(ctypes.Structure):
         ("softmax_scale", ctypes.c_float), ("lambda_", ctypes.c_float), ("norm_mode", ctypes.c_int32),
         ("sv_rtol", ctypes.c_float), ("k_prune", ctypes.c_int32), ("k_final", ctypes.c_int32),
         ("jacobi_max_sweeps", ctypes.c_int32), ("jacobi_tol", ctypes.c_float), ("eig_dtype", ctypes.c_int32),
-        ("eig_method", ctypes.c_int32), ("stream_groups", ctypes.c_int32),
+        ("eig_method", ctypes.c_int32), ("stream_groups", ctypes.c_int32), ("n_prompt_queries", ctypes.c_int32),
     ]
 
 
 def make_params(batch, seq_len, vis_start, n_vis, n_heads, head_dim, hidden_dim, dtype, k_prune, k_final,
                 lam=0.5, causal=1, norm_mode=TC_NORM_MINMAX, sv_rtol=0.0, softmax_scale=0.0,
-                jacobi_max_sweeps=0, jacobi_tol=0.0, eig_dtype=TC_EIG_F64, stream_groups=0, eig_method=0):
+                jacobi_max_sweeps=0, jacobi_tol=0.0, eig_dtype=TC_EIG_F64, stream_groups=0, eig_method=0,
+                n_prompt_queries=0):
     return tc_params(batch, seq_len, vis_start, n_vis, n_heads, head_dim, hidden_dim, dtype, causal,
                      softmax_scale, lam, norm_mode, sv_rtol, k_prune, k_final, jacobi_max_sweeps, jacobi_tol,
-                     eig_dtype, eig_method, stream_groups)
+                     eig_dtype, eig_method, stream_groups, n_prompt_queries)
 
 
 def params_for(w, batch=None, **overrides):

@@ -19,7 +19,8 @@ int make_plan(const tc_params* p, Plan* pl) {
       !(p->sv_rtol >= 0.f && p->sv_rtol < 1.f) || (p->causal != 0 && p->causal != 1) || !(p->softmax_scale >= 0.f) ||
       !std::isfinite(p->softmax_scale) || p->jacobi_max_sweeps < 0 || p->jacobi_max_sweeps > 1000 ||
       !(p->jacobi_tol >= 0.f) || !(p->jacobi_tol < 1.f) || p->stream_groups < 0 || p->stream_groups > 4 ||
-      p->eig_method < TC_EIG_AUTO || p->eig_method > TC_EIG_TRIDIAGONAL)
+      p->eig_method < TC_EIG_AUTO || p->eig_method > TC_EIG_TRIDIAGONAL || p->n_prompt_queries < 0 ||
+      (int64_t)p->vis_start + p->n_vis + p->n_prompt_queries > p->seq_len)
     return TC_ERR_PARAM;
   // the tridiagonal route works in float64 and keeps its panels in the LDS of one compute unit
   const bool direct_ok = p->eig_dtype == TC_EIG_F64 && p->n_vis <= 1024 && tridiag_panel_width(p->n_vis) >= 4;
@@ -33,7 +34,8 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.D = q.H * q.dh; q.hidden = p->hidden_dim; q.kp = p->k_prune; q.kf = p->k_final; q.m = q.kp - q.kf;
   q.nA = nA; q.nB = nB;
   q.Np = round_up(q.N, JT); q.nblk = q.Np / JB; q.P = q.nblk / 2; q.steps = q.nblk - 1;
-  q.q_tile = 128; q.n_qtiles = (q.N + q.q_tile - 1) / q.q_tile;
+  q.Nq = q.N + p->n_prompt_queries;
+  q.q_tile = 128; q.n_qtiles = (q.Nq + q.q_tile - 1) / q.q_tile;
   q.esize = p->dtype == TC_F32 ? 4 : 2;
   q.tsize = p->eig_dtype == TC_EIG_F64 ? 8 : 4;
   q.groups = p->stream_groups;
@@ -50,7 +52,9 @@ int make_plan(const tc_params* p, Plan* pl) {
   const size_t B = (size_t)q.B, N = (size_t)q.N, Np = (size_t)q.Np;
   q.off_O = take(B * N * q.D * q.esize);
   q.off_S = take(B * N * 4);
-  q.off_Spart = take(B * q.H * (size_t)(q.n_qtiles > 2 ? q.n_qtiles : 2) * N * 4);  // also holds the float path's (max, sum) pairs
+  // per (head, query tile) column sums; the float path keeps a (max, sum) pair per (head, query row) there instead
+  q.spart_stride = (size_t)q.H * ((size_t)q.n_qtiles * N > 2 * (size_t)q.Nq ? (size_t)q.n_qtiles * N : 2 * (size_t)q.Nq);
+  q.off_Spart = take(B * q.spart_stride * 4);
   q.off_G = take(B * Np * Np * q.tsize);
   q.off_U = take(B * Np * Np * 4);  // eigenvectors are kept in float32
   q.off_R = take(B * q.P * JT * JT * q.tsize);
@@ -148,7 +152,7 @@ static int front_chain(const Plan& pl, const tc_params* p, const void* Q, const 
       const size_t qoff = i0 * pl.H * pl.L * pl.dh * es;
       rc = launch_attention(sub, p->dtype, p->causal, static_cast<const char*>(Q) + qoff, static_cast<const char*>(K) + qoff,
                             static_cast<const char*>(V) + qoff, Og, Sg,
-                            at<float>(ws, pl.off_Spart) + i0 * pl.H * (size_t)(pl.n_qtiles > 2 ? pl.n_qtiles : 2) * N, streams[g]);
+                            at<float>(ws, pl.off_Spart) + i0 * pl.spart_stride, streams[g]);
       if (rc != TC_OK) break;
     }
     rc = launch_gram(sub, p->dtype, p->eig_dtype, Og, at<double>(ws, pl.off_G) + i0 * pl.Np * pl.Np, streams[g]);

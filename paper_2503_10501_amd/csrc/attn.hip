@@ -125,8 +125,8 @@ __device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const typename
 template <int DH, bool F16>
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
                                                         const uint16_t* __restrict__ V, uint16_t* __restrict__ O,
-                                                        float* __restrict__ Spart, int L, int Ls, int N, int H,
-                                                        int causal, float scale_log2e, int n_qtiles, int B) {
+                                                        float* __restrict__ Spart, int L, int Ls, int N, int Nq, int H,
+                                                        int causal, float scale_log2e, int n_qtiles, int B, size_t stride) {
   typedef AttnSmem<DH> SM;
   typedef typename Elem16<F16>::vec8 vec8;
   typedef typename Elem16<F16>::elem elem;
@@ -144,14 +144,16 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   const uint16_t* Kh = K + head_off;
   const uint16_t* Vh = V + head_off;
   const int q = qt * AQ + wave * 32 + (lane & 31);
-  const bool qvalid = q < N;
-  const int p = Ls + (qvalid ? q : N - 1);            // sequence position of this lane's query
+  // query rows 0 .. N-1 are the visual tokens; rows N .. Nq-1 (prompt tokens) only add to the column sums
+  const bool qvalid = q < Nq;
+  const int p = Ls + (qvalid ? q : Nq - 1);           // sequence position of this lane's query
   const int kend_q = causal ? p + 1 : L;              // keys [0, kend_q) are visible to it
-  const int q_last = min(N, (qt + 1) * AQ) - 1;
+  const int q_last = min(Nq, (qt + 1) * AQ) - 1;
   const int kend = causal ? min(L, Ls + q_last + 1) : L;
   const int n_tiles = (kend + AK - 1) / AK;
   // keys [0, kvis_all) are visible to every query of this wavefront (its first query sees the fewest)
-  const int kvis_all = causal ? min(L, Ls + min(qt * AQ + wave * 32, N - 1) + 1) : L;
+  const int kvis_all = causal ? min(L, Ls + min(qt * AQ + wave * 32, Nq - 1) + 1) : L;
+  const bool want_o = qt * AQ + wave * 32 < N;  // this wavefront holds visual rows: their output is wanted
 
   vec8 qf[DH / 16];
 #pragma unroll
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
     l_run = l_run * fast_exp2(m_run - M) + l_o * fast_exp2(m_o - M);
     m_run = M;
   }
-  // p = 2^(s - m) / l = 2^(s - (m + log2 l)); rows past N contribute nothing (2^-inf = 0)
+  // p = 2^(s - m) / l = 2^(s - (m + log2 l)); rows past Nq contribute nothing (2^-inf = 0)
   const float m_fold = qvalid ? m_run + log2f(l_run) : INFINITY;
 
   // ---------------- pass 2: probabilities, O^T accumulation, column sums ----------------
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   for (int mt = 0; mt < DH / 32; mt++)
 #pragma unroll
     for (int i = 0; i < 16; i++) oacc[mt][i] = 0.f;
-  float* sp_row = Spart + (((size_t)b * H + h) * n_qtiles + qt) * N;
+  float* sp_row = Spart + (size_t)b * stride + ((size_t)h * n_qtiles + qt) * N;
   load_v_tile<DH>(Vh, 0, L, vr);
   for (int t = 0; t < n_tiles; t++) {
     const int k0 = t * AK;
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
       // O^T += V^T P^T.  Matrix-core k-slot (half, i) of product u is key
       // sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
 #pragma unroll
-      for (int u = 0; u < 2; u++) {
+      for (int u = 0; u < 2 && want_o; u++) {
         // probabilities enter the matrix cores as a 16-bit head plus a 16-bit remainder (16 or more
         // significant bits), so O is accurate to its own final rounding
         vec8 pb, pl;
@@ -326,15 +328,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   }
 }
 
-// S[b][x] = (1 / (H N)) sum_h sum_tiles partial column sums, in a fixed order.
+// S[b][x] = (1 / (H Nq)) sum_h sum_tiles partial column sums, in a fixed order.
 __global__ __launch_bounds__(256) void attn_score_reduce(const float* __restrict__ Spart, float* __restrict__ S, int N,
-                                                         int H, int n_qtiles) {
+                                                         int Nq, int H, int n_qtiles, size_t stride) {
   const int b = blockIdx.y, x = blockIdx.x * 256 + threadIdx.x;
   if (x >= N) return;
-  const float* sp = Spart + (size_t)b * H * n_qtiles * N + x;
+  const float* sp = Spart + (size_t)b * stride + x;
   double acc = 0.0;
   for (int i = 0; i < H * n_qtiles; i++) acc += (double)sp[(size_t)i * N];
-  S[(size_t)b * N + x] = (float)(acc / ((double)H * (double)N));
+  S[(size_t)b * N + x] = (float)(acc / ((double)H * (double)Nq));
 }
 
 // ---------------- float32 storage: plain-ALU correctness path ----------------
@@ -342,8 +344,8 @@ __global__ __launch_bounds__(256) void attn_score_reduce(const float* __restrict
 template <int DH>
 __global__ __launch_bounds__(64) void attn_f32_rows(const float* __restrict__ Q, const float* __restrict__ K,
                                                     const float* __restrict__ V, float* __restrict__ O,
-                                                    float* __restrict__ stats, int L, int Ls, int N, int H, int causal,
-                                                    float scale) {
+                                                    float* __restrict__ stats, int L, int Ls, int N, int Nq, int H,
+                                                    int causal, float scale, size_t stride) {
   __shared__ float qs[DH];
   const int q = blockIdx.x, h = blockIdx.y, b = blockIdx.z, lane = threadIdx.x;
   const size_t head_off = ((size_t)b * H + h) * (size_t)L * DH;
@@ -377,35 +379,37 @@ __global__ __launch_bounds__(64) void attn_f32_rows(const float* __restrict__ Q,
 #pragma unroll
     for (int d = 0; d < DH; d++) acc[d] += pk * vr[d];
   }
-  float* out = O + ((size_t)b * N + q) * ((size_t)H * DH) + (size_t)h * DH;
+  if (q < N) {  // prompt rows (q >= N) only leave their softmax statistics
+    float* out = O + ((size_t)b * N + q) * ((size_t)H * DH) + (size_t)h * DH;
 #pragma unroll
-  for (int d = 0; d < DH; d++) {
-    const float v = wave_sum(acc[d]);
-    if (lane == (d & 63)) out[d] = v;
+    for (int d = 0; d < DH; d++) {
+      const float v = wave_sum(acc[d]);
+      if (lane == (d & 63)) out[d] = v;
+    }
   }
   if (lane == 0) {
-    stats[(((size_t)b * H + h) * N + q) * 2] = M;
-    stats[(((size_t)b * H + h) * N + q) * 2 + 1] = l;
+    stats[(size_t)b * stride + ((size_t)h * Nq + q) * 2] = M;
+    stats[(size_t)b * stride + ((size_t)h * Nq + q) * 2 + 1] = l;
   }
 }
 
-// One workgroup per (image, visual key x): S[b][x] = mean over heads and visual queries of A[.., q, x].
+// One workgroup per (image, visual key x): S[b][x] = mean over heads and the Nq query rows of A[.., q, x].
 template <int DH>
 __global__ __launch_bounds__(256) void attn_f32_cols(const float* __restrict__ Q, const float* __restrict__ K,
                                                      const float* __restrict__ stats, float* __restrict__ S, int L,
-                                                     int Ls, int N, int H, int causal, float scale) {
+                                                     int Ls, int N, int Nq, int H, int causal, float scale, size_t stride) {
   __shared__ double red[256];
   const int x = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   double acc = 0.0;
-  for (int idx = tid; idx < H * N; idx += 256) {
-    const int h = idx / N, q = idx % N;
+  for (int idx = tid; idx < H * Nq; idx += 256) {
+    const int h = idx / Nq, q = idx % Nq;
     if (causal && x > q) continue;
     const size_t head_off = ((size_t)b * H + h) * (size_t)L * DH;
     const float* qr = Q + head_off + (size_t)(Ls + q) * DH;
     const float* kr = K + head_off + (size_t)(Ls + x) * DH;
     float s = 0.f;
     for (int d = 0; d < DH; d++) s += qr[d] * kr[d];
-    const float M = stats[(((size_t)b * H + h) * N + q) * 2], l = stats[(((size_t)b * H + h) * N + q) * 2 + 1];
+    const float M = stats[(size_t)b * stride + ((size_t)h * Nq + q) * 2], l = stats[(size_t)b * stride + ((size_t)h * Nq + q) * 2 + 1];
     acc += (double)(expf(s * scale - M) / l);
   }
   red[tid] = acc;
@@ -414,7 +418,7 @@ __global__ __launch_bounds__(256) void attn_f32_cols(const float* __restrict__ Q
     if (tid < o) red[tid] += red[tid + o];
     __syncthreads();
   }
-  if (tid == 0) S[(size_t)b * N + x] = (float)(red[0] / ((double)H * (double)N));
+  if (tid == 0) S[(size_t)b * N + x] = (float)(red[0] / ((double)H * (double)Nq));
 }
 
 int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const void* K, const void* V, void* O,
@@ -425,26 +429,26 @@ int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const
     const uint16_t *q = (const uint16_t*)Q, *k = (const uint16_t*)K, *v = (const uint16_t*)V;
     uint16_t* o = (uint16_t*)O;
 #define TC_ATTN16(DH_, F16_) \
-  TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<DH_, F16_><<<grid, 256, 0, st>>>(q, k, v, o, Spart, pl.L, pl.Ls, pl.N, pl.H, causal, sl2, pl.n_qtiles, pl.B)))
+  TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<DH_, F16_><<<grid, 256, 0, st>>>(q, k, v, o, Spart, pl.L, pl.Ls, pl.N, pl.Nq, pl.H, causal, sl2, pl.n_qtiles, pl.B, pl.spart_stride)))
     if (pl.dh == 128) {
       if (dtype == TC_F16) TC_ATTN16(128, true); else TC_ATTN16(128, false);
     } else {
       if (dtype == TC_F16) TC_ATTN16(64, true); else TC_ATTN16(64, false);
     }
 #undef TC_ATTN16
-    if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.H, pl.n_qtiles)));
+    if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.Nq, pl.H, pl.n_qtiles, pl.spart_stride)));
   } else {
-    const dim3 grid(pl.N, pl.H, pl.B);
+    const dim3 grid(pl.Nq, pl.H, pl.B);
     if (pl.dh == 128) {
       TC_TIMED(PK_ATTN, 0, st, (attn_f32_rows<128><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart,
-                                              pl.L, pl.Ls, pl.N, pl.H, causal, pl.scale)));
+                                              pl.L, pl.Ls, pl.N, pl.Nq, pl.H, causal, pl.scale, pl.spart_stride)));
       if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_f32_cols<128><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
-                                                                   pl.Ls, pl.N, pl.H, causal, pl.scale)));
+                                                                   pl.Ls, pl.N, pl.Nq, pl.H, causal, pl.scale, pl.spart_stride)));
     } else {
       TC_TIMED(PK_ATTN, 0, st, (attn_f32_rows<64><<<grid, 64, 0, st>>>((const float*)Q, (const float*)K, (const float*)V, (float*)O, Spart, pl.L,
-                                             pl.Ls, pl.N, pl.H, causal, pl.scale)));
+                                             pl.Ls, pl.N, pl.Nq, pl.H, causal, pl.scale, pl.spart_stride)));
       if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_f32_cols<64><<<dim3(pl.N, pl.B), 256, 0, st>>>((const float*)Q, (const float*)K, Spart, S, pl.L,
-                                                                  pl.Ls, pl.N, pl.H, causal, pl.scale)));
+                                                                  pl.Ls, pl.N, pl.Nq, pl.H, causal, pl.scale, pl.spart_stride)));
     }
   }
   return check_launch();

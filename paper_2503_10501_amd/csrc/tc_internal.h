@@ -44,6 +44,8 @@ struct Plan {
   int steps;     // nblk - 1 steps per sweep
   int q_tile;    // query rows per attention workgroup
   int n_qtiles;
+  int Nq;                // query rows whose probabilities enter the attention score: N + prompt rows
+  size_t spart_stride;   // floats of the partial-score region per image
   int esize;     // bytes of one stored element (2 or 4)
   int tsize;     // bytes of one eigensolver element (4 or 8)
   int max_sweeps;

@@ -31,7 +31,7 @@ def ulp_bound(ref, dtype, rms):
 
 def oracle_attention(p, w, batch, i):
     return orc.attn_output(batch["Q"][i], batch["K"][i], batch["V"][i], w.n_sys, w.n_vis, bool(p.causal),
-                           p.softmax_scale or None)
+                           p.softmax_scale or None, p.n_prompt_queries)
 
 
 def check_attention(p, w, batch, images, O_dev, S_dev, report, ora=None):
@@ -270,7 +270,7 @@ def run_all_stages(w, images=None, eig=tc.TC_EIG_F64, oracle_images=None, tight=
         if n == 0:
             whole_or = orc.compress(batch["Q"][i], batch["K"][i], batch["V"][i], Xv[i], w.n_sys, w.n_vis, p.k_prune,
                                     p.k_final, lam=p.lambda_, norm=p.norm_mode, causal=bool(p.causal), dtype=sn,
-                                    sv_rtol=p.sv_rtol, scale=p.softmax_scale or None)
+                                    sv_rtol=p.sv_rtol, scale=p.softmax_scale or None, n_prompt_q=p.n_prompt_queries)
             assert np.array_equal(whole_or["kept_idx"], full["kept_idx"]) and np.array_equal(whole_or["X_out"], full["X_out"])
         a, b = set(kept_h[i].tolist()), set(full["kept_idx"].tolist())
         rep["jaccard"] = len(a & b) / len(a | b)

@@ -56,6 +56,7 @@ def test_workspace_size_and_status_strings():
     ("n_vis", 0, -2), ("n_vis", 5000, -2), ("head_dim", 96, -2), ("hidden_dim", 100, -2), ("vis_start", 600, -2),
     ("dtype", 7, -3), ("eig_dtype", 3, -3), ("lambda_", 1.5, -4), ("lambda_", -0.1, -4), ("k_final", 0, -4),
     ("k_prune", 9999, -4), ("k_final", 1, -4), ("norm_mode", 9, -4), ("causal", 2, -4), ("sv_rtol", 1.0, -4), ("stream_groups", 5, -4),
+    ("n_prompt_queries", -1, -4), ("n_prompt_queries", 9, -4),     # the tiny workload has 8 prompt tokens
 ])
 def test_invalid_params_are_rejected_on_the_host(field, value, status):
     tc = _binding()

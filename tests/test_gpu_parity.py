@@ -97,6 +97,29 @@ def test_sv_rtol_and_custom_scale():
     parity.run_all_stages(_small("f32_ragged"), softmax_scale=0.2)
 
 
+@pytest.mark.parametrize("name,prompt_rows", [("bf16_ragged", 1), ("bf16_ragged", 4), ("bf16_dh64_odd", 3),
+                                              ("f16_ragged", 2), ("f32_ragged", 1), ("f32_ragged", 2)])
+@pytest.mark.parametrize("causal", [1, 0])
+def test_prompt_query_rows_in_the_attention_score(name, prompt_rows, causal):
+    # text-guided variant of Eq. 3-7: the first P prompt rows join the visual rows of the column mean;
+    # every stage downstream sees the changed score
+    tc, gu, parity, _, _ = _mods()
+    parity.run_all_stages(_small(name).with_(causal=causal), n_prompt_queries=prompt_rows)
+
+
+def test_prompt_query_rows_at_the_llava7b_shape_change_only_the_attention_score():
+    # all prompt rows after the 576 visual rows: one more query tile, mostly empty; O must not move
+    tc, gu, parity, CONFIGS, _ = _mods()
+    from workloads import make_batch
+    w = CONFIGS["llava7b_b1"]
+    parity.run_all_stages(w, n_prompt_queries=w.seq_len - w.n_sys - w.n_vis)
+    b = make_batch(w)
+    O0, S0 = gu.attn_output(tc.params_for(w), b["Q"], b["K"], b["V"])
+    O1, S1 = gu.attn_output(tc.params_for(w, n_prompt_queries=(w.seq_len - w.n_sys - w.n_vis) // 2), b["Q"], b["K"], b["V"])
+    assert torch.equal(O0, O1)
+    assert not torch.equal(S0, S1)
+
+
 @pytest.mark.parametrize("method", list(METHODS))
 def test_llava7b_batch1_full_size(method):
     tc, gu, parity, CONFIGS, _ = _mods()
