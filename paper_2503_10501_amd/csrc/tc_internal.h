@@ -90,7 +90,7 @@ int launch_combine(const Plan& pl, const float* C_ws, const float* S, float lamb
 int tridiag_panel_width(int N);
 int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, hipStream_t st);
 int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, const float* tauv, const float* Vc,
-                    double* lam, int2* blk, double* tnorm, double* DP, double* UM, float* W, double* rn, int32_t* bad,
+                    double* lam, int2* blk, double* tnorm, double* DP, double* DM, float* W, double* rn, int32_t* bad,
                     double* sig, double* wgt, double* Cpart, float* Tf, float sv_rtol, bool vectors, float* C, float* C_out,
                     float* sigma_out, int32_t* info_out, hipStream_t st);
 int direct_eigenvalues(const Plan& pl, const tc_params* p, float* sigma, int32_t* info, void* ws, hipStream_t st);  // api.hip

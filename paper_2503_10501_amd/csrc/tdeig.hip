@@ -31,25 +31,23 @@ constexpr double TD_EPS = 2.220446049250313e-16;
 // on it, and with one eigenvalue per lane there is nothing to hide that latency behind: measured 3.4 ms
 // per batch against 0.2.  T is scaled by a power of two to ||T|| <= 1 so that the minors change by at most a
 // factor 3 per step, and they are brought back into range every eight steps.
-__global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict__ dvec, const double* __restrict__ evec,
-                                                        double* __restrict__ lam, int2* __restrict__ blk,
-                                                        double* __restrict__ tnorm, int32_t* __restrict__ bad, int N,
-                                                        int Np) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char tb_smem[];
-  double* ds = reinterpret_cast<double*>(tb_smem);  // [N], scaled
-  double* es = ds + N;                               // [N]: es[i] = |coupling of rows i-1 and i|, es[0] = 0, scaled
-  double* e2 = es + N;                               // [N]: its square, 0 where T is split
+typedef double tb_pair __attribute__((ext_vector_type(2)));
+
+// Scaled copy of T for the bisection, one workgroup per image: prep [B][prep_stride] doubles holds
+// (d_i, e_i^2) pairs for rows 0 .. N-1 (e_i = |coupling of rows i-1 and i|, e_0 = 0; the square is 0 where T
+// is split), sixteen zero pairs behind them, then the N scaled |e_i|.  Also tnorm [B] = ||T||_inf, and bad[b]
+// is cleared.
+__global__ __launch_bounds__(256) void td_prepare_kernel(const double* __restrict__ dvec, const double* __restrict__ evec,
+                                                         double* __restrict__ prep, size_t prep_stride,
+                                                         double* __restrict__ tnorm, int32_t* __restrict__ bad, int N,
+                                                         int Np) {
   __shared__ double wmax[4];
-  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const double* db = dvec + (size_t)b * Np;
   const double* eb = evec + (size_t)b * Np;
-  for (int i = tid; i < N; i += 256) {
-    ds[i] = db[i];
-    es[i] = i > 0 ? fabs(eb[i - 1]) : 0.0;
-  }
-  __syncthreads();
   double rowmax = 0.0;
-  for (int i = tid; i < N; i += 256) rowmax = fmax(rowmax, fabs(ds[i]) + es[i] + (i + 1 < N ? es[i + 1] : 0.0));
+  for (int i = tid; i < N; i += 256)
+    rowmax = fmax(rowmax, fabs(db[i]) + (i > 0 ? fabs(eb[i - 1]) : 0.0) + (i + 1 < N ? fabs(eb[i]) : 0.0));
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) rowmax = fmax(rowmax, __shfl_xor(rowmax, o, 64));
   if (lane == 0) wmax[wave] = rowmax;
@@ -59,16 +57,45 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
   // power of two that brings ||T|| into (1/2, 1] (exact); a zero or non-finite norm leaves T as it is
   int ex = 0;
   if (tn > 0.0 && tn < DBL_MAX) (void)frexp(tn, &ex);
-  const double down = ldexp(1.0, -ex), up = ldexp(1.0, ex);
-  __syncthreads();  // every thread has read the unscaled values it needs
-  for (int i = tid; i < N; i += 256) {
-    const double e = es[i];
-    ds[i] *= down;
-    es[i] = e * down;
-    e2[i] = e > split ? (e * down) * (e * down) : 0.0;
+  const double down = ldexp(1.0, -ex);
+  tb_pair* pr = reinterpret_cast<tb_pair*>(prep + (size_t)b * prep_stride);
+  double* esc = reinterpret_cast<double*>(pr + N + 16);
+  for (int i = tid; i < N + 16; i += 256) {
+    const double e = i > 0 && i < N ? fabs(eb[i - 1]) : 0.0;
+    pr[i] = i < N ? tb_pair{db[i] * down, e > split ? (e * down) * (e * down) : 0.0} : tb_pair{0.0, 0.0};
+    if (i < N) esc[i] = e * down;
   }
+  if (tid == 0) { tnorm[b] = tn; bad[b] = 0; }
+}
+
+// One lane per eigenvalue; blockIdx.y = image.  The usual case, T not split anywhere (or every lane of the
+// wavefront in the same block), reads the rows through the scalar unit: the coefficients are the same for all
+// lanes, and fetched per lane from LDS the sixteen bytes per row and lane made the LDS the limit of the kernel.
+__global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict__ prep, size_t prep_stride,
+                                                        const double* __restrict__ tnorm, double* __restrict__ lam,
+                                                        int2* __restrict__ blk, int N, int Np) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char tb_smem[];
+  double* ds = reinterpret_cast<double*>(tb_smem);  // [N], scaled
+  double* es = ds + N;                               // [N]: es[i] = |coupling of rows i-1 and i|, es[0] = 0, scaled
+  double* e2 = es + N;                               // [N]: its square, 0 where T is split
+  tb_pair* de = reinterpret_cast<tb_pair*>(e2 + N);  // [N + 16]: (ds[i], e2[i]) side by side, one 16-byte read per row; zero padding
+  const int b = blockIdx.y, tid = threadIdx.x;
+  const tb_pair* __restrict__ pr = reinterpret_cast<const tb_pair*>(prep + (size_t)b * prep_stride);
+  const double* __restrict__ esc = reinterpret_cast<const double*>(pr + N + 16);
+  for (int i = tid; i < N + 16; i += 256) {
+    const tb_pair v = pr[i];
+    de[i] = v;
+    if (i < N) {
+      ds[i] = v.x;
+      e2[i] = v.y;
+      es[i] = esc[i];
+    }
+  }
+  const double tn = tnorm[b];
+  int ex = 0;
+  if (tn > 0.0 && tn < DBL_MAX) (void)frexp(tn, &ex);
+  const double up = ldexp(1.0, ex);
   __syncthreads();
-  if (blockIdx.x == 0 && tid == 0) { tnorm[b] = tn; bad[b] = 0; }
   const int k = blockIdx.x * 256 + tid;
   if (k >= N) return;
   int s = k, t = k + 1;
@@ -86,51 +113,112 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
   lo -= widen;
   hi += widen;
   const double BIG = 0x1p256, SMALL = 0x1p-256;
+  const double d_s = ds[s];
+  const int s0 = __builtin_amdgcn_readfirstlane(s), t0 = __builtin_amdgcn_readfirstlane(t);
+  const bool uniform = __all(s == s0 && t == t0);
   for (int it = 0; it < 128; it++) {
     const double mid = 0.5 * (lo + hi);
     if (!(mid > lo && mid < hi)) break;     // the interval cannot be halved any more
     if (hi - lo <= 0.25 * TD_EPS) break;    // the entries of T carry errors of eps ||T|| themselves; same count for every lane
-    double pp = 1.0, p = ds[s] - mid;       // p_{i-2}, p_{i-1}
-    int cnt = __double2hiint(p) < 0 ? 1 : 0; // p_0 = 1 is positive
-    // Sign changes are counted on the sign bits: (bits of p_i xor bits of p_{i-1}) >> 63.  An exact zero needs
-    // no special case: its successor is -e^2 times its predecessor, so the three minors around it contain one
-    // sign change whichever sign the zero is given.  Eight rows at a time: their coefficients are fetched
-    // from LDS together (sixteen independent reads in flight; read one by one inside the chain each would
-    // cost its full latency), rows past the block's end are replaced by the identity step p_i = p_{i-1};
-    // then the pair of minors is brought back into range (a common factor does not change any sign).
-    auto chunk = [&](int i0, bool whole) {
-      double a[8], c[8];
+    double pp = 1.0, p = d_s - mid;         // p_{i-2}, p_{i-1}
+    // Sign changes are counted on the sign bits.  The signs of the minors are shifted into one register, a bit
+    // per row (bit 0 = the newest); after eight rows the changes among them and against the minor before them
+    // are the set bits of (signs xor signs >> 1) in its low byte.  An exact zero needs no special case: its
+    // successor is -e^2 times its predecessor, so the three minors around it contain one sign change whichever
+    // sign the zero is given.  Eight rows at a time: their coefficients are fetched from LDS together and one
+    // chunk ahead (read one by one inside the chain, each read would cost its full latency); rows past the
+    // block's end are replaced by the identity step p_i = p_{i-1}, which changes no sign; then the pair of
+    // minors is brought back into range (a common factor does not change any sign).
+    unsigned signs = (unsigned)__double2hiint(p) >> 31;  // p_0 = 1 is positive: bit 1 = 0
+    int cnt = (int)signs;
+    if (uniform) {
+      // every lane of the wavefront walks over the same block: the row index is a scalar, the coefficients come
+      // through the scalar unit (loaded one chunk ahead), and no row needs a select.  (Two recurrences per
+      // lane, at one third and two thirds of the interval, were measured too: no gain, the kernel is bound by
+      // the rate at which one wavefront issues float64 operations, not by their latency.)
+      int i0 = s0 + 1;
+      tb_pair ca[8], cb[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) ca[u] = pr[i0 + u];
+#define TB_UCHUNK(CUR, NXT)                                                                    \
+  {                                                                                            \
+    _Pragma("unroll") for (int u = 0; u < 8; u++) NXT[u] = pr[i0 + 8 + u];                     \
+    _Pragma("unroll") for (int u = 0; u < 8; u++) {                                            \
+      const double pn = fma(CUR[u].x - mid, p, -(CUR[u].y * pp));                              \
+      signs = __builtin_amdgcn_alignbit(signs, (unsigned)__double2hiint(pn), 31);              \
+      pp = p;                                                                                  \
+      p = pn;                                                                                  \
+    }                                                                                          \
+    cnt += __popc((signs ^ (signs >> 1)) & 0xffu);                                             \
+    const double mag = fmax(fabs(p), fabs(pp));                                                \
+    const double f = mag > BIG ? SMALL : (mag < SMALL && mag > 0.0 ? BIG : 1.0);               \
+    p *= f;                                                                                    \
+    pp *= f;                                                                                   \
+    i0 += 8;                                                                                   \
+  }
+      while (i0 + 8 <= t0) {
+        TB_UCHUNK(ca, cb)
+        if (i0 + 8 > t0) {
+#pragma unroll
+          for (int u = 0; u < 8; u++) ca[u] = cb[u];
+          break;
+        }
+        TB_UCHUNK(cb, ca)
+      }
+#undef TB_UCHUNK
+      // the last, shorter chunk (ca holds rows i0 .. i0 + 7)
 #pragma unroll
       for (int u = 0; u < 8; u++) {
-        const int ii = whole ? i0 + u : min(i0 + u, t - 1);
-        a[u] = ds[ii];
-        c[u] = e2[ii];
+        if (i0 + u < t0) {
+          const double pn = fma(ca[u].x - mid, p, -(ca[u].y * pp));
+          cnt += (int)((unsigned)(__double2hiint(pn) ^ __double2hiint(p)) >> 31);
+          pp = p;
+          p = pn;
+        }
       }
-      // all sixteen reads are issued before any is used, and none conditionally (the optimiser would put each
-      // behind a branch with a wait of its own)
-      asm volatile("" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7]),
-                        "+v"(c[0]), "+v"(c[1]), "+v"(c[2]), "+v"(c[3]), "+v"(c[4]), "+v"(c[5]), "+v"(c[6]), "+v"(c[7]));
-#pragma unroll
-      for (int u = 0; u < 8; u++) {
-        const bool in = whole || i0 + u < t;
-        a[u] = in ? a[u] - mid : 1.0;
-        c[u] = in ? c[u] : 0.0;
-      }
-#pragma unroll
-      for (int u = 0; u < 8; u++) {
-        const double pn = fma(a[u], p, -(c[u] * pp));
-        cnt += (int)((unsigned)(__double2hiint(pn) ^ __double2hiint(p)) >> 31);
-        pp = p;
-        p = pn;
-      }
-      const double mag = fmax(fabs(p), fabs(pp));
-      const double f = mag > BIG ? SMALL : (mag < SMALL && mag > 0.0 ? BIG : 1.0);
-      p *= f;
-      pp *= f;
-    };
+    } else {
+    // (two chunk buffers that trade places: no register copies)
+    tb_pair ca[8], cb[8];
     int i0 = s + 1;
-    for (; i0 + 8 <= t; i0 += 8) chunk(i0, true);   // whole chunks: no selects
-    if (i0 < t) chunk(i0, false);                   // the last, shorter one
+#pragma unroll
+    for (int u = 0; u < 8; u++) ca[u] = de[i0 + u];
+#define TB_CHUNK(CUR, NXT)                                                                                                \
+  {                                                                                                                       \
+    _Pragma("unroll") for (int u = 0; u < 8; u++) NXT[u] = de[i0 + 8 + u];                                                \
+    /* the eight reads of this chunk have arrived; those of the next stay in flight */                                   \
+    asm volatile("" : "+v"(CUR[0].x), "+v"(CUR[1].x), "+v"(CUR[2].x), "+v"(CUR[3].x), "+v"(CUR[4].x), "+v"(CUR[5].x),     \
+                      "+v"(CUR[6].x), "+v"(CUR[7].x), "+v"(CUR[0].y), "+v"(CUR[1].y), "+v"(CUR[2].y), "+v"(CUR[3].y),     \
+                      "+v"(CUR[4].y), "+v"(CUR[5].y), "+v"(CUR[6].y), "+v"(CUR[7].y));                                    \
+    if (i0 + 8 <= t) { /* a whole chunk: no selects */                                                                    \
+      _Pragma("unroll") for (int u = 0; u < 8; u++) {                                                                     \
+        const double pn = fma(CUR[u].x - mid, p, -(CUR[u].y * pp));                                                       \
+        signs = __builtin_amdgcn_alignbit(signs, (unsigned)__double2hiint(pn), 31);                                       \
+        pp = p;                                                                                                           \
+        p = pn;                                                                                                           \
+      }                                                                                                                   \
+    } else {                                                                                                              \
+      _Pragma("unroll") for (int u = 0; u < 8; u++) {                                                                     \
+        const bool in = i0 + u < t;                                                                                       \
+        const double pn = fma(in ? CUR[u].x - mid : 1.0, p, -((in ? CUR[u].y : 0.0) * pp));                               \
+        signs = __builtin_amdgcn_alignbit(signs, (unsigned)__double2hiint(pn), 31);                                       \
+        pp = p;                                                                                                           \
+        p = pn;                                                                                                           \
+      }                                                                                                                   \
+    }                                                                                                                     \
+    cnt += __popc((signs ^ (signs >> 1)) & 0xffu);                                                                        \
+    const double mag = fmax(fabs(p), fabs(pp));                                                                           \
+    const double f = mag > BIG ? SMALL : (mag < SMALL && mag > 0.0 ? BIG : 1.0);                                          \
+    p *= f;                                                                                                               \
+    pp *= f;                                                                                                              \
+    i0 += 8;                                                                                                              \
+  }
+    while (i0 < t) {
+      TB_CHUNK(ca, cb)
+      if (i0 >= t) break;
+      TB_CHUNK(cb, ca)
+    }
+#undef TB_CHUNK
+    }
     if (cnt > m) hi = mid; else lo = mid;
   }
   lam[(size_t)b * Np + k] = 0.5 * (lo + hi) * up;
@@ -138,14 +226,21 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
 }
 
 // ---- 2b -----------------------------------------------------------------------------------------------
-// One lane per eigenvector.  DP and UM are scratch [B][Np][Np] doubles addressed [row][slot] (contiguous
-// across the lanes of a wavefront).  W [B][Np][Np] float receives the unnormalised vector of slot k in
-// column k (rows outside its block are zero); rn [B][Np] its reciprocal norm (0 if the vector is not
-// finite, which also raises bad[b]).
+// One lane per eigenvector.  DP and DM are scratch [B][Np][Np] doubles addressed [row][slot] (contiguous
+// across the lanes of a wavefront): the pivots of the two factorisations.  W [B][Np][Np] float receives the
+// unnormalised vector of slot k in column k (rows outside its block are zero); rn [B][Np] its reciprocal
+// norm (0 if the vector is not finite, which also raises bad[b]).
+//
+// All lanes of a wavefront walk over the same row at the same time, whatever block their eigenvalue belongs
+// to and wherever its twist index lies (a lane ignores the rows that are not its own): every access to the
+// scratch arrays and to W is one contiguous run per row.  With per-lane rows (each lane starting at its own
+// twist index) a wavefront touched up to 64 rows per instruction and the kernel took six times as long.
+// The two factorisations are independent chains with a division per row: they run in one loop, side by side.
+// So do the two halves of the vector.  Loads from the scratch arrays are issued one chunk of eight rows ahead.
 __global__ __launch_bounds__(64) void td_twisted_kernel(const double* __restrict__ dvec, const double* __restrict__ evec,
                                                         const double* __restrict__ lam, const int2* __restrict__ blk,
                                                         const double* __restrict__ tnorm, double* __restrict__ DP,
-                                                        double* __restrict__ UM, float* __restrict__ W,
+                                                        double* __restrict__ DM, float* __restrict__ W,
                                                         double* __restrict__ rn, int32_t* __restrict__ bad, int N,
                                                         int Np) {
   extern __shared__ __attribute__((aligned(16))) unsigned char tw_smem[];
@@ -155,7 +250,6 @@ __global__ __launch_bounds__(64) void td_twisted_kernel(const double* __restrict
   const double* db = dvec + (size_t)b * Np;
   const double* eb = evec + (size_t)b * Np;
   const double split = TD_EPS * tnorm[b];
-  double e2max = 0.0;
   for (int i = tid; i < N; i += 64) {
     ds[i] = db[i];
     const double e = i + 1 < N ? eb[i] : 0.0;
@@ -163,52 +257,125 @@ __global__ __launch_bounds__(64) void td_twisted_kernel(const double* __restrict
   }
   __syncthreads();
   const int k = blockIdx.x * 64 + tid;
-  if (k >= N) return;
+  if (k >= N) return;  // (no barrier below)
   const int2 st = blk[(size_t)b * Np + k];
   const int s = st.x, t = st.y;
+  double e2max = 0.0;
   for (int i = s; i + 1 < t; i++) e2max = fmax(e2max, es[i] * es[i]);
   const double pivmin = DBL_MIN * fmax(1.0, e2max);
   const double l = lam[(size_t)b * Np + k];
   double* dp = DP + (size_t)b * Np * Np + k;
-  double* um = UM + (size_t)b * Np * Np + k;
+  double* dmv = DM + (size_t)b * Np * Np + k;
   float* w = W + (size_t)b * Np * Np + k;
-  // forward: T - l I = L D+ L^T, pivots dp[i]
-  double p = ds[s] - l;
-  for (int i = s; i < t; i++) {
-    if (fabs(p) < pivmin) p = -pivmin;
-    dp[(size_t)i * Np] = p;
-    if (i + 1 < t) p = (ds[i + 1] - l) - (es[i] / p) * es[i];
+
+  // forward, rows ascending:   T - l I = L D+ L^T, pivots dp[i] (the chain starts anew at row s);
+  // backward, rows descending: T - l I = U D- U^T, pivots dm[j] (the chain starts anew at row t - 1)
+  {
+    double p = 1.0, dm = 1.0;
+    auto row = [&](int i) {
+      const int j = N - 1 - i;
+      const double a = ds[i] - l, ep = i > 0 ? es[i - 1] : 0.0;
+      double pn = a - (ep / p) * ep;
+      pn = i == s ? a : pn;
+      if (fabs(pn) < pivmin) pn = -pivmin;
+      p = pn;
+      if (i >= s && i < t) dp[(size_t)i * Np] = p;
+      const double aj = ds[j] - l, ej = es[j];
+      double dn = aj - (ej / dm) * ej;
+      dn = j == t - 1 ? aj : dn;
+      if (fabs(dn) < pivmin) dn = -pivmin;
+      dm = dn;
+      if (j >= s && j < t) dmv[(size_t)j * Np] = dm;
+    };
+    int i0 = 0;
+    for (; i0 + 8 <= N; i0 += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; u++) row(i0 + u);
+    }
+    for (; i0 < N; i0++) row(i0);
   }
-  // backward: T - l I = U D- U^T, pivots dm; gamma_i = dp[i] + dm[i] - (d_i - l); keep the smallest |gamma|
-  double dm = ds[t - 1] - l;
+
+#define TD_ARRIVED8(f) \
+  asm volatile("" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]));
+  // twist index: gamma_i = dp[i] + dm[i] - (d_i - l), the row with the smallest |gamma| (rows descending, the
+  // first of equal ones wins).  Rows outside the block hold whatever the scratch memory held: not looked at.
   double gbest = DBL_MAX;
   int r = t - 1;
-  for (int i = t - 1; i >= s; i--) {
-    if (fabs(dm) < pivmin) dm = -pivmin;
-    const double g = fabs(dp[(size_t)i * Np] + dm - (ds[i] - l));
-    if (g < gbest || !(gbest == gbest)) { gbest = g; r = i; }
-    if (i > s) {
-      const double u = es[i - 1] / dm;
-      um[(size_t)(i - 1) * Np] = u;
-      dm = (ds[i - 1] - l) - u * es[i - 1];
+  {
+    double f[8], h[8], fn[8], hn[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+      const size_t row = (size_t)max(N - 1 - u, 0) * Np;
+      f[u] = dp[row];
+      h[u] = dmv[row];
+    }
+    for (int hi = N - 1; hi >= 0; hi -= 8) {
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const size_t row = (size_t)max(hi - 8 - u, 0) * Np;
+        fn[u] = dp[row];
+        hn[u] = dmv[row];
+      }
+      TD_ARRIVED8(f)
+      TD_ARRIVED8(h)
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int i = hi - u;
+        const double g = fabs(f[u] + h[u] - (ds[max(i, 0)] - l));
+        const bool take = i >= s && i < t && (g < gbest || !(gbest == gbest));
+        gbest = take ? g : gbest;
+        r = take ? i : r;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) { f[u] = fn[u]; h[u] = hn[u]; }
     }
   }
-  // the vector: z_r = 1, upwards with the multipliers of L, downwards with those of U
-  for (int i = 0; i < s; i++) w[(size_t)i * Np] = 0.f;
-  for (int i = t; i < N; i++) w[(size_t)i * Np] = 0.f;
-  double z = 1.0, nrm = 1.0;
-  w[(size_t)r * Np] = 1.f;
-  for (int i = r - 1; i >= s; i--) {
-    z = -(es[i] / dp[(size_t)i * Np]) * z;
-    w[(size_t)i * Np] = (float)z;
-    nrm += z * z;
+
+  // the vector: z_r = 1; upwards from r with the multipliers e_i / dp[i] of L (rows descending), downwards with
+  // the multipliers e_{i-1} / dm[i] of U (rows ascending); zero outside the block
+  double zu = 1.0, zd = 1.0, nrm = 1.0;
+  {
+    double f[8], h[8], fn[8], hn[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) {
+      f[u] = dp[(size_t)max(N - 1 - u, 0) * Np];
+      h[u] = dmv[(size_t)min(u, N - 1) * Np];
+    }
+    for (int c0 = 0; c0 < N; c0 += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        fn[u] = dp[(size_t)max(N - 1 - c0 - 8 - u, 0) * Np];
+        hn[u] = dmv[(size_t)min(c0 + 8 + u, N - 1) * Np];
+      }
+      TD_ARRIVED8(f)
+      TD_ARRIVED8(h)
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        const int c = c0 + u;
+        const bool in = c < N;
+        const int iu = max(N - 1 - c, 0), id = min(c, N - 1);
+        {  // rows iu <= r
+          const double q = es[iu] / f[u];
+          const bool act = in && iu >= s && iu < r;
+          const double zn = -q * zu;
+          zu = act ? zn : zu;
+          nrm += act ? zn * zn : 0.0;
+          if (in && iu <= r) w[(size_t)iu * Np] = iu < s ? 0.f : (iu == r ? 1.f : (float)zu);
+        }
+        {  // rows id > r
+          const double q = es[max(id - 1, 0)] / h[u];
+          const bool act = in && id > r && id < t;
+          const double zn = -q * zd;
+          zd = act ? zn : zd;
+          nrm += act ? zn * zn : 0.0;
+          if (in && id > r) w[(size_t)id * Np] = id >= t ? 0.f : (float)zd;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) { f[u] = fn[u]; h[u] = hn[u]; }
+    }
   }
-  z = 1.0;
-  for (int i = r; i + 1 < t; i++) {
-    z = -um[(size_t)i * Np] * z;
-    w[(size_t)(i + 1) * Np] = (float)z;
-    nrm += z * z;
-  }
+#undef TD_ARRIVED8
   const bool fin = nrm == nrm && nrm < DBL_MAX && nrm < 1e60;  // float storage of z holds |z| < 3e38 relative to z_r = 1
   rn[(size_t)b * Np + k] = fin ? 1.0 / sqrt(nrm) : 0.0;
   if (!fin) atomicOr(&bad[b], 1);
@@ -533,11 +700,14 @@ __global__ __launch_bounds__(256) void td_ics_finish_kernel(const double* __rest
 }
 
 int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, const float* tauv, const float* Vc,
-                    double* lam, int2* blk, double* tnorm, double* DP, double* UM, float* W, double* rn, int32_t* bad,
+                    double* lam, int2* blk, double* tnorm, double* DP, double* DM, float* W, double* rn, int32_t* bad,
                     double* sig, double* wgt, double* Cpart, float* Tf, float sv_rtol, bool vectors, float* C, float* C_out,
                     float* sigma_out, int32_t* info_out, hipStream_t st) {
   const int N = pl.N, Np = pl.Np, B = pl.B;
-  TC_TIMED(PK_BISECT, 0, st, (td_bisect_kernel<<<dim3((N + 255) / 256, B), 256, (size_t)3 * N * 8, st>>>(dvec, evec, lam, blk, tnorm, bad, N, Np)));
+  // (the scaled copy of T lives at the start of each image's region of DP until the factorisations overwrite it)
+  const size_t prep_stride = (size_t)Np * Np;
+  TC_TIMED(PK_BISECT, 0, st, (td_prepare_kernel<<<B, 256, 0, st>>>(dvec, evec, DP, prep_stride, tnorm, bad, N, Np)));
+  TC_TIMED(PK_BISECT, 0, st, (td_bisect_kernel<<<dim3((N + 255) / 256, B), 256, (size_t)5 * N * 8 + 256, st>>>(DP, prep_stride, tnorm, lam, blk, N, Np)));
   int n2 = 1;
   while (n2 < N) n2 <<= 1;
   const size_t shm_sig = sigma_out ? (size_t)n2 * sizeof(float) : 0;
@@ -545,7 +715,7 @@ int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, cons
     TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, nullptr, tnorm, bad, 0.f, sig, nullptr, sigma_out, info_out, N, Np)));
     return check_launch();
   }
-  TC_TIMED(PK_TWISTED, 0, st, (td_twisted_kernel<<<dim3((N + 63) / 64, B), 64, (size_t)2 * N * 8, st>>>(dvec, evec, lam, blk, tnorm, DP, UM, W, rn, bad, N, Np)));
+  TC_TIMED(PK_TWISTED, 0, st, (td_twisted_kernel<<<dim3((N + 63) / 64, B), 64, (size_t)2 * N * 8, st>>>(dvec, evec, lam, blk, tnorm, DP, DM, W, rn, bad, N, Np)));
   TC_TIMED(PK_TWISTED, 1, st, (td_cluster_kernel<<<B, 256, 0, st>>>(lam, blk, tnorm, W, rn, bad, N, Np)));
   TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, rn, tnorm, bad, sv_rtol, sig, wgt, sigma_out, info_out, N, Np)));
   const int nstrip = (N + 63) / 64, npanel = (N + BT_K - 1) / BT_K;
