@@ -69,7 +69,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   q.off_mlist = take(B * (size_t)(q.m > 0 ? q.m : 1) * 8);
   q.off_info = take(B * 4);
   if (q.method == TC_EIG_TRIDIAGONAL) {
-    const size_t nstrip = (N + 63) / 64;
+    const size_t nstrip = (N + 15) / 16;   // strips of the back-transformation are 16 to 64 eigenvectors wide
     q.off_td_d = take(B * Np * 8);
     q.off_td_e = take(B * Np * 8);
     q.off_td_tau = take(B * Np * 4);
@@ -93,7 +93,7 @@ int make_plan(const tc_params* p, Plan* pl) {
 // workspace region is addressed per image, so groups of images can run side by side on different streams.
 static int direct_chain(const Plan& pl, const Plan& sub, int img0, const tc_params* p, bool vectors, float* C_ws,
                         float* ics, float* sigma, int32_t* info, void* ws, hipStream_t st) {
-  const size_t Np = pl.Np, i0 = img0, nstrip = (pl.N + 63) / 64, npanel = (pl.N + 15) / 16;
+  const size_t Np = pl.Np, i0 = img0, nstrip = (pl.N + 15) / 16, npanel = (pl.N + 15) / 16;
   double* G = at<double>(ws, pl.off_G) + i0 * Np * Np;
   double* dvec = at<double>(ws, pl.off_td_d) + i0 * Np;
   double* evec = at<double>(ws, pl.off_td_e) + i0 * Np;

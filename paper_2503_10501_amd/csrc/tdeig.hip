@@ -513,26 +513,33 @@ __global__ __launch_bounds__(256) void td_weights_kernel(const double* __restric
 typedef __attribute__((ext_vector_type(4))) float f4;
 constexpr int BT_K = 16;  // reflectors per block
 
-// T of every block of 16 reflectors: one workgroup per (block, image).
+// T of every block of 16 reflectors: one workgroup per (block, image).  The block goes through LDS once
+// (16-byte accesses); thread (a, c) then forms v_a^T v_c from there.
 __global__ __launch_bounds__(256) void td_tfactor_kernel(const float* __restrict__ Vc, const float* __restrict__ tauv,
                                                          float* __restrict__ Tf, int N, int Np, int npanel) {
+  constexpr int VP = BT_K + 1;
+  extern __shared__ __attribute__((aligned(16))) float tf_smem[];  // [N - j0][VP]
   __shared__ float S[BT_K][BT_K];   // S[a][c] = v_a^T v_c, a < c
   __shared__ float T[BT_K][BT_K];
   const int p = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int j0 = BT_K * p;
-  const float* Vb = Vc + (size_t)b * Np * Np;
-  for (int pair = wave; pair < BT_K * BT_K; pair += 4) {
-    const int a = pair / BT_K, c = pair % BT_K;
-    if (a >= c) continue;  // uniform over the wavefront
-    float dot = 0.f;
-    if (j0 + c <= N - 2) {  // reflectors past the last one are zero; v_c is zero up to row j0 + c
-      const float* vp = Vb + (size_t)p * Np * BT_K;  // [row][16]
-      for (int i = j0 + c + 1 + lane; i < N; i += 64) dot += vp[(size_t)i * BT_K + a] * vp[(size_t)i * BT_K + c];
-    }
-    dot = wave_sum(dot);
-    if (lane == 0) S[a][c] = dot;
+  const int j0 = BT_K * p, rows = N - j0;
+  const f4* src = reinterpret_cast<const f4*>(Vc + (size_t)b * Np * Np + (size_t)p * Np * BT_K + (size_t)j0 * BT_K);
+  for (int e = tid; e < rows * 4; e += 256) {
+    const int i = e >> 2, m = 4 * (e & 3);
+    const f4 v = src[e];
+    float* d = &tf_smem[i * VP + m];
+#pragma unroll
+    for (int u = 0; u < 4; u++) d[u] = j0 + m + u <= N - 2 ? v[u] : 0.f;  // reflectors past N-2 do not exist: their slots were never written
   }
-  T[tid / BT_K][tid % BT_K] = 0.f;
+  __syncthreads();
+  {
+    const int a = tid / BT_K, c = tid % BT_K;
+    float dot = 0.f;
+    if (a < c)  // v_c is zero up to row j0 + c
+      for (int i = c + 1; i < rows; i++) dot += tf_smem[i * VP + a] * tf_smem[i * VP + c];
+    S[a][c] = dot;
+    T[a][c] = 0.f;
+  }
   __syncthreads();
   if (wave == 0) {  // column by column; lane a owns row a
     for (int c = 0; c < BT_K; c++) {
@@ -551,9 +558,9 @@ __global__ __launch_bounds__(256) void td_tfactor_kernel(const float* __restrict
   Tf[((size_t)b * npanel + p) * (BT_K * BT_K) + tid] = T[tid / BT_K][tid % BT_K];
 }
 
-// The strip of 64 eigenvectors (columns k0 .. k0+63 of W) lives in the accumulator registers of the four
+// A strip of 16 CT eigenvectors (columns k0 .. k0 + 16 CT - 1 of W) lives in the accumulator registers of the four
 // wavefronts of a workgroup for the whole kernel: wavefront w owns the row tiles rt = 4 t + w (16 rows each),
-// as four 16x16 column tiles; element j of a lane is (row 4 (lane / 16) + j, column lane % 16) of its tile.
+// as CT 16x16 column tiles; element j of a lane is (row 4 (lane / 16) + j, column lane % 16) of its tile.
 // Per block of reflectors, last block first:
 //   Z  = V^T U     contraction over rows; the B operand of matrix-core step j is accumulator element j itself
 //                  (rows j, 4 + j, 8 + j, 12 + j of the tile), the A operand the matching rows of V;
@@ -562,8 +569,9 @@ __global__ __launch_bounds__(256) void td_tfactor_kernel(const float* __restrict
 //   U -= V Z2      likewise on the accumulator of Z2.
 // V of the block goes through LDS, transposed to [row][reflector].  Only row tiles that the block reaches
 // (rows > j0) take part.  At the end the strip's share of Eq. 3-6, Cpart[strip][x] = sum_k |U[x][k]| wgt[k],
-// is reduced across the 16 lanes of a row and written; U itself is not.
-template <int TPW>
+// is reduced across the 16 lanes of a row and written; U itself is not.  CT is chosen by the launcher so that
+// the workgroups fill the chip in whole rounds and the accumulators fit the register file.
+template <int TPW, int CT>
 __global__ __launch_bounds__(256) void td_backtransform_kernel(const float* __restrict__ W, const float* __restrict__ Vc,
                                                                const float* __restrict__ Tf,
                                                                const double* __restrict__ wgt,
@@ -573,54 +581,61 @@ __global__ __launch_bounds__(256) void td_backtransform_kernel(const float* __re
   constexpr int ROWS = 64 * TPW;     // rows covered by the workgroup (>= Np)
   extern __shared__ __attribute__((aligned(16))) float bt_smem[];
   float* vt = bt_smem;                         // [ROWS][VP]
-  float* zbuf = vt + ROWS * VP;                // [4][16][64] the wavefronts' parts of Z
-  float* tl = zbuf + 4 * BT_K * 64;            // [16][16]
+  constexpr int SW = 16 * CT;                  // width of the strip
+  float* zbuf = vt + ROWS * VP;                // [4][16][SW] the wavefronts' parts of Z
+  float* tl = zbuf + 4 * BT_K * SW;            // [16][16]
   const int b = blockIdx.y, strip = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l15 = lane & 15, q4 = lane >> 4;
-  const int k0 = strip * 64;
+  const int k0 = strip * SW;
   const float* Wb = W + (size_t)b * Np * Np;
   const float* Vb = Vc + (size_t)b * Np * Np;
-  f4 acc[TPW][4];
+  f4 acc[TPW][CT];
 #pragma unroll
   for (int t = 0; t < TPW; t++)
 #pragma unroll
-    for (int ct = 0; ct < 4; ct++)
+    for (int ct = 0; ct < CT; ct++)
 #pragma unroll
       for (int j = 0; j < 4; j++) {
         const int row = 16 * (4 * t + wave) + 4 * q4 + j, col = k0 + 16 * ct + l15;
         acc[t][ct][j] = (row < N && col < N) ? Wb[(size_t)row * Np + col] : 0.f;
       }
+  // The block's reflectors [row][16] are a straight copy, 16 bytes per access; the copy of the next block is
+  // in flight (in registers) while the matrix cores work on this one.
+  constexpr int PER = ROWS * 4 / 256;  // 16-byte pieces per thread when the block covers every row
+  f4 piece[PER];
+  float t_next;
+  auto fetch = [&](int p) {
+    const f4* src = reinterpret_cast<const f4*>(Vb + (size_t)p * Np * BT_K);
+#pragma unroll
+    for (int u = 0; u < PER; u++) {
+      const int e = tid + 256 * u, i = e >> 2;      // row i, quarter e & 3
+      piece[u] = (i >= BT_K * p && i < N) ? src[e] : f4{0.f, 0.f, 0.f, 0.f};
+    }
+    t_next = Tf[((size_t)b * npanel + p) * (BT_K * BT_K) + tid];
+  };
+  fetch(npanel - 1);
   for (int p = npanel - 1; p >= 0; p--) {
     const int j0 = BT_K * p;
     __syncthreads();  // the previous block no longer reads vt, tl, zbuf
-    {  // the block's reflectors [row][16]: a straight copy, 16 bytes per access, every load issued before the first store
-      const f4* src = reinterpret_cast<const f4*>(Vb + (size_t)p * Np * BT_K);
-      constexpr int PER = ROWS * 4 / 256;  // 16-byte pieces per thread when the block covers every row
-      f4 piece[PER];
 #pragma unroll
-      for (int u = 0; u < PER; u++) {
-        const int e = tid + 256 * u, i = e >> 2;      // row i, quarter e & 3
-        piece[u] = (i >= j0 && i < N) ? src[e] : f4{0.f, 0.f, 0.f, 0.f};
-      }
-#pragma unroll
-      for (int u = 0; u < PER; u++) {
-        const int e = tid + 256 * u, i = e >> 2, m = 4 * (e & 3);
-        if (i >= j0) {
-          const bool last = j0 + m + 3 > N - 2;  // reflectors past N-2 do not exist: their slots were never written
-          float* d = &vt[i * VP + m];
-          d[0] = (!last || j0 + m <= N - 2) ? piece[u][0] : 0.f;
-          d[1] = (!last || j0 + m + 1 <= N - 2) ? piece[u][1] : 0.f;
-          d[2] = (!last || j0 + m + 2 <= N - 2) ? piece[u][2] : 0.f;
-          d[3] = (!last || j0 + m + 3 <= N - 2) ? piece[u][3] : 0.f;
-        }
+    for (int u = 0; u < PER; u++) {
+      const int e = tid + 256 * u, i = e >> 2, m = 4 * (e & 3);
+      if (i >= j0) {
+        const bool last = j0 + m + 3 > N - 2;  // reflectors past N-2 do not exist: their slots were never written
+        float* d = &vt[i * VP + m];
+        d[0] = (!last || j0 + m <= N - 2) ? piece[u][0] : 0.f;
+        d[1] = (!last || j0 + m + 1 <= N - 2) ? piece[u][1] : 0.f;
+        d[2] = (!last || j0 + m + 2 <= N - 2) ? piece[u][2] : 0.f;
+        d[3] = (!last || j0 + m + 3 <= N - 2) ? piece[u][3] : 0.f;
       }
     }
-    tl[tid] = Tf[((size_t)b * npanel + p) * (BT_K * BT_K) + tid];
+    tl[tid] = t_next;
+    if (p > 0) fetch(p - 1);
     __syncthreads();
-    f4 z[4];
+    f4 z[CT];
 #pragma unroll
-    for (int ct = 0; ct < 4; ct++) z[ct] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int ct = 0; ct < CT; ct++) z[ct] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int t = 0; t < TPW; t++) {
       const int rt = 4 * t + wave;
@@ -629,30 +644,30 @@ __global__ __launch_bounds__(256) void td_backtransform_kernel(const float* __re
         for (int j = 0; j < 4; j++) {
           const float a = vt[(16 * rt + 4 * q4 + j) * VP + l15];
 #pragma unroll
-          for (int ct = 0; ct < 4; ct++) z[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, acc[t][ct][j], z[ct], 0, 0, 0);
+          for (int ct = 0; ct < CT; ct++) z[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, acc[t][ct][j], z[ct], 0, 0, 0);
         }
       }
     }
 #pragma unroll
-    for (int ct = 0; ct < 4; ct++)
+    for (int ct = 0; ct < CT; ct++)
 #pragma unroll
-      for (int j = 0; j < 4; j++) zbuf[(wave * BT_K + 4 * q4 + j) * 64 + 16 * ct + l15] = z[ct][j];
+      for (int j = 0; j < 4; j++) zbuf[(wave * BT_K + 4 * q4 + j) * SW + 16 * ct + l15] = z[ct][j];
     __syncthreads();
 #pragma unroll
-    for (int ct = 0; ct < 4; ct++)
+    for (int ct = 0; ct < CT; ct++)
 #pragma unroll
       for (int j = 0; j < 4; j++) {
-        const int o = (4 * q4 + j) * 64 + 16 * ct + l15;
-        z[ct][j] = (zbuf[o] + zbuf[BT_K * 64 + o]) + (zbuf[2 * BT_K * 64 + o] + zbuf[3 * BT_K * 64 + o]);
+        const int o = (4 * q4 + j) * SW + 16 * ct + l15;
+        z[ct][j] = (zbuf[o] + zbuf[BT_K * SW + o]) + (zbuf[2 * BT_K * SW + o] + zbuf[3 * BT_K * SW + o]);
       }
-    f4 z2[4];
+    f4 z2[CT];
 #pragma unroll
-    for (int ct = 0; ct < 4; ct++) z2[ct] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int ct = 0; ct < CT; ct++) z2[ct] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 4; j++) {
       const float a = tl[l15 * BT_K + 4 * q4 + j];
 #pragma unroll
-      for (int ct = 0; ct < 4; ct++) z2[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, z[ct][j], z2[ct], 0, 0, 0);
+      for (int ct = 0; ct < CT; ct++) z2[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, z[ct][j], z2[ct], 0, 0, 0);
     }
 #pragma unroll
     for (int t = 0; t < TPW; t++) {
@@ -662,15 +677,15 @@ __global__ __launch_bounds__(256) void td_backtransform_kernel(const float* __re
         for (int j = 0; j < 4; j++) {
           const float a = -vt[(16 * rt + l15) * VP + 4 * q4 + j];
 #pragma unroll
-          for (int ct = 0; ct < 4; ct++) acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, z2[ct][j], acc[t][ct], 0, 0, 0);
+          for (int ct = 0; ct < CT; ct++) acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, z2[ct][j], acc[t][ct], 0, 0, 0);
         }
       }
     }
   }
   // Eq. 3-6, this strip's share
-  double wk[4];
+  double wk[CT];
 #pragma unroll
-  for (int ct = 0; ct < 4; ct++) {
+  for (int ct = 0; ct < CT; ct++) {
     const int col = k0 + 16 * ct + l15;
     wk[ct] = col < N ? wgt[(size_t)b * Np + col] : 0.0;
   }
@@ -681,7 +696,7 @@ __global__ __launch_bounds__(256) void td_backtransform_kernel(const float* __re
     for (int j = 0; j < 4; j++) {
       double term = 0.0;
 #pragma unroll
-      for (int ct = 0; ct < 4; ct++) term += fabs((double)acc[t][ct][j]) * wk[ct];
+      for (int ct = 0; ct < CT; ct++) term += fabs((double)acc[t][ct][j]) * wk[ct];
       term = row16_sum_dpp(term);
       const int row = 16 * (4 * t + wave) + 4 * q4 + j;
       if (l15 == 0 && row < N) Cp[row] = term;
@@ -718,25 +733,53 @@ int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, cons
   TC_TIMED(PK_TWISTED, 0, st, (td_twisted_kernel<<<dim3((N + 63) / 64, B), 64, (size_t)2 * N * 8, st>>>(dvec, evec, lam, blk, tnorm, DP, DM, W, rn, bad, N, Np)));
   TC_TIMED(PK_TWISTED, 1, st, (td_cluster_kernel<<<B, 256, 0, st>>>(lam, blk, tnorm, W, rn, bad, N, Np)));
   TC_TIMED(PK_BISECT, 1, st, (td_weights_kernel<<<B, 256, shm_sig, st>>>(lam, rn, tnorm, bad, sv_rtol, sig, wgt, sigma_out, info_out, N, Np)));
-  const int nstrip = (N + 63) / 64, npanel = (N + BT_K - 1) / BT_K;
+  const int npanel = (N + BT_K - 1) / BT_K;
+  {
+    const size_t shm = (size_t)N * (BT_K + 1) * sizeof(float);
+    if (shm > 64 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(td_tfactor_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)
+      return TC_ERR_HIP;
+    TC_TIMED(PK_BACKTF, 0, st, (td_tfactor_kernel<<<dim3(npanel, B), 256, shm, st>>>(Vc, tauv, Tf, N, Np, npanel)));
+  }
+  // Width of the strips (16 CT eigenvectors per workgroup, one workgroup per compute unit at a time): the one
+  // with the least (rounds over the chip) x (work of a workgroup: CT column tiles plus a fixed part of about
+  // one); above 576 rows at most two column tiles fit the registers next to the row tiles.
+  int ct_best = 1;
+  {
+    long best = -1;
+    for (int ct = Np > 576 ? 2 : 4; ct >= 1; ct--) {
+      const long wgs = (long)((N + 16 * ct - 1) / (16 * ct)) * B, rounds = (wgs + 255) / 256;
+      const long cost = rounds * (ct + 1);
+      if (best < 0 || cost < best) { best = cost; ct_best = ct; }
+    }
+  }
+  const int nstrip = (N + 16 * ct_best - 1) / (16 * ct_best);
   const dim3 gb(nstrip, B);
-  TC_TIMED(PK_BACKTF, 0, st, (td_tfactor_kernel<<<dim3(npanel, B), 256, 0, st>>>(Vc, tauv, Tf, N, Np, npanel)));
-#define TC_BACKTF(TPW_)                                                                                                     \
+#define TC_BACKTF2(TPW_, CT_)                                                                                               \
   {                                                                                                                         \
-    const size_t shm = ((size_t)64 * TPW_ * (BT_K + 1) + 4 * BT_K * 64 + BT_K * BT_K) * sizeof(float);                      \
+    const size_t shm = ((size_t)64 * TPW_ * (BT_K + 1) + 4 * BT_K * 16 * CT_ + BT_K * BT_K) * sizeof(float);                \
     if (shm > 64 * 1024 &&                                                                                                  \
-        hipFuncSetAttribute(reinterpret_cast<const void*>(td_backtransform_kernel<TPW_>),                                   \
+        hipFuncSetAttribute(reinterpret_cast<const void*>(td_backtransform_kernel<TPW_, CT_>),                              \
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm) != hipSuccess)                            \
       return TC_ERR_HIP;                                                                                                    \
-    TC_TIMED(PK_BACKTF, 1, st, (td_backtransform_kernel<TPW_><<<gb, 256, shm, st>>>(W, Vc, Tf, wgt, Cpart, N, Np, nstrip, npanel))); \
+    TC_TIMED(PK_BACKTF, 1, st, (td_backtransform_kernel<TPW_, CT_><<<gb, 256, shm, st>>>(W, Vc, Tf, wgt, Cpart, N, Np, nstrip, npanel))); \
+  }
+#define TC_BACKTF(TPW_)                                    \
+  {                                                        \
+    if (ct_best == 4) TC_BACKTF2(TPW_, 4)                  \
+    else if (ct_best == 3) TC_BACKTF2(TPW_, 3)             \
+    else if (ct_best == 2) TC_BACKTF2(TPW_, 2)             \
+    else TC_BACKTF2(TPW_, 1)                               \
   }
   if (Np <= 64) TC_BACKTF(1)
   else if (Np <= 128) TC_BACKTF(2)
   else if (Np <= 256) TC_BACKTF(4)
   else if (Np <= 576) TC_BACKTF(9)
-  else if (Np <= 1024) TC_BACKTF(16)
-  else return TC_ERR_SHAPE;
+  else if (Np <= 1024) {
+    if (ct_best == 2) TC_BACKTF2(16, 2) else TC_BACKTF2(16, 1)
+  } else return TC_ERR_SHAPE;
 #undef TC_BACKTF
+#undef TC_BACKTF2
   TC_TIMED(PK_ICS, 0, st, (td_ics_finish_kernel<<<dim3((N + 255) / 256, B), 256, 0, st>>>(Cpart, C, C_out, N, Np, nstrip)));
   return check_launch();
 }
