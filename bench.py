@@ -19,7 +19,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm_gbps": 8000.0, "mfma_bf16": 2500.0, "mfma_f64": 78.6, "mfma_f32": 157.3, "vec_f64": 78.6, "vec_f32": 157.3}
-FULL_EVERY = 6   # Jacobi method: one rotation launch in six sweeps all 64 indices of its pair (csrc/jacobi.hip)
 
 
 # ---- algorithmic work per batch (what the method must move or compute; derivations in the design doc) -------------
@@ -55,16 +54,6 @@ def work_model(w):
         # Jacobi method (when it runs): Eq. 3-6 reads U once
         "ics_bytes": B * 4 * N * N,
     }
-
-
-def jacobi_solve_flops_per_image_sweep(n_vis):
-    """Rotation kernel of the Jacobi method: one step of a pair's 64x64 subproblem applies 32 plane rotations from
-    both sides to the symmetric S (528 2x2 blocks, 24 flops each) and from the right to R (4096 entries, 3 flops)."""
-    np_ = (n_vis + 63) // 64 * 64
-    P, steps = np_ // 64, np_ // 32 - 1
-    per_step = 528 * 24 + 4096 * 3
-    full = len(range(0, steps, FULL_EVERY))
-    return P * per_step * (full * 63 + (steps - full) * 32)
 
 
 def main():
