@@ -45,7 +45,9 @@ size_t tridiag_lds_bytes(int N, int nb) {
   return (size_t)(2 * nb + 2) * Nr * 8 + TD_RED * 8 + 1024;
 }
 
-// Sum over the workgroup in a fixed order: lanes as above, wavefronts left to right.
+// Sum over the workgroup in a fixed order: lanes as above, wavefronts left to right.  One barrier: the caller
+// must not use the same scratch array for its next sum unless another barrier lies in between (the two sums of
+// a column step use two arrays).
 __device__ inline double td_block_sum(double x, double* scratch, int wave, int lane) {
   x = wave_sum_dpp(x);
   if (lane == 0) scratch[wave] = x;
@@ -53,7 +55,6 @@ __device__ inline double td_block_sum(double x, double* scratch, int wave, int l
   double s = 0.0;
 #pragma unroll
   for (int k = 0; k < TD_WAVES; k++) s += scratch[k];
-  __syncthreads();
   return s;
 }
 
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
   double* as = vs + Nr;                              // [Nr] current column
   double* red = as + Nr;                             // [nrg][128 ncg] partial column sums of the row groups, <= 2048 in all
   double* dots = red + TD_RED;                       // [64] W^T v and V^T v
-  double* wsum = dots + 64;                          // [16] wavefront partials of td_block_sum
+  double* wsum = dots + 64;                          // [2][16] wavefront partials of td_block_sum
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   double* A = G + (size_t)b * Np * Np;
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
         pc *= tau;
         vc = vs[c];
       }
-      const double pv = td_block_sum(pc * vc, wsum, wave, lane);
+      const double pv = td_block_sum(pc * vc, wsum + TD_WAVES, wave, lane);
       if (c < N) Wp[c * nb + jj] = pc - 0.5 * tau * pv * vc;
       __syncthreads();
     }
