@@ -22,6 +22,14 @@ PEAK = {"hbm_gbps": 8000.0, "mfma_bf16": 2500.0, "mfma_f64": 78.6, "mfma_f32": 1
 
 
 # ---- algorithmic work per batch (what the method must move or compute; derivations in the design doc) -------------
+def panel_ends(n_vis):
+    """Last column + 1 of every panel of the reduction to tridiagonal form: the panel width is what fits the 160 KB of
+    LDS of a compute unit next to two vectors and 16 KB of partial sums (the library's sizing rule, csrc/tridiag.hip)."""
+    nr = (n_vis + 15) // 16 * 16
+    nb = min(32, ((160 * 1024 - 1024 - 2048 * 8 - 2 * nr * 8) // (16 * nr)) & ~3)
+    return [min(j0 + nb, n_vis - 1) for j0 in range(0, n_vis - 1, max(nb, 1))]
+
+
 def work_model(w):
     B, N, D, H, dh, Ls = w.batch, w.n_vis, w.hidden, w.n_heads, w.head_dim, w.n_sys
     es = 4 if w.dtype == "f32" else 2
@@ -41,6 +49,8 @@ def work_model(w):
         # plus the rank-2 updates (read and write of the lower half once per column pair v, w): N^3/6 * 8 * (1 + 2/nb)
         "tridiag_bytes": B * 8 * sum((N - j - 1) * (N - j) // 2 for j in range(N - 1)),
         "tridiag_flops": B * 4 * N ** 3 // 3,
+        # rank-2nb update of the trailing matrix after every panel: its lower half read and written once
+        "tridiag_update_bytes": B * 16 * sum((N - je) * (N - je + 1) // 2 for je in panel_ends(N)),
         # twisted factorisations: pivots and multipliers written and read once (2 * 8 N^2 each way), vectors written (4 N^2)
         "twisted_bytes": B * N * N * (16 + 16 + 4),
         # back-transformation: 4 N^3 / 2 ... each reflector touches (N-j-1) rows of N columns, 4 flops each
@@ -186,6 +196,8 @@ def main():
     if kinds["tridiag"][1] > 0:   # the tridiagonal route ran
         per_row["a4_tridiagonal_reduction"] = entry("tridiag", "hbm", rate(wm["tridiag_bytes"], "tridiag", "G"), PEAK["hbm_gbps"],
                                                     "GB/s", ms=ms("tridiag"))
+        per_row["a4_trailing_update"] = entry("tridiag_update", "hbm", rate(wm["tridiag_update_bytes"], "tridiag_update", "G"),
+                                              PEAK["hbm_gbps"], "GB/s", ms=ms("tridiag_update"))
         per_row["a4_bisection"] = {"kernel": "bisect", "bound": "alu (float64 divisions, one lane per eigenvalue)", "ms": ms("bisect")}
         per_row["a4_twisted_factorisation"] = entry("twisted", "hbm", rate(wm["twisted_bytes"], "twisted", "G"), PEAK["hbm_gbps"],
                                                     "GB/s", ms=ms("twisted"))

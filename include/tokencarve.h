@@ -217,7 +217,7 @@ typedef enum {
   TC_PROF_ATTN = 0, TC_PROF_ATTN_REDUCE, TC_PROF_GRAM, TC_PROF_JACOBI_INIT, TC_PROF_JACOBI_SOLVE,
   TC_PROF_JACOBI_UPDATE, TC_PROF_JACOBI_UPDATE_U, TC_PROF_JACOBI_SWEEP_END, TC_PROF_SIGMA, TC_PROF_ICS, TC_PROF_COMBINE, TC_PROF_TOPK,
   TC_PROF_ROWNORM, TC_PROF_SIM, TC_PROF_ASSIGN, TC_PROF_AVERAGE, TC_PROF_TRIDIAG, TC_PROF_BISECT, TC_PROF_TWISTED,
-  TC_PROF_BACKTRANSFORM, TC_PROF_KINDS
+  TC_PROF_BACKTRANSFORM, TC_PROF_TRIDIAG_UPDATE, TC_PROF_KINDS
 } tc_prof_kind;
 TC_API int tc_profile_compress(const tc_params* p, const void* Q, const void* K, const void* V, const void* X,
                                void* X_out, int32_t* kept_idx, int32_t* merge_dst, int32_t* info, void* ws,

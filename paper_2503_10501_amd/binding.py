@@ -24,7 +24,7 @@ SYMBOLS = ("tc_workspace_bytes", "tc_status_string", "tc_attn_output", "tc_ipgs_
            "tc_assemble_sequence", "tc_kv_cache_fraction")
 PROF_KINDS = ("attn", "attn_reduce", "gram", "jacobi_init", "jacobi_solve", "jacobi_update", "jacobi_update_u", "jacobi_sweep_end",
               "sigma", "ics", "combine", "topk", "rownorm", "sim", "assign", "average", "tridiag", "bisect", "twisted",
-              "backtransform")
+              "backtransform", "tridiag_update")
 
 
 class TokenCarveError(RuntimeError):

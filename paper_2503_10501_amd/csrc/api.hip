@@ -30,7 +30,7 @@ int make_plan(const tc_params* p, Plan* pl) {
   if (p->k_prune - p->k_final > nB) return TC_ERR_PARAM;
 
   Plan& q = *pl;
-  q.B = p->batch; q.L = p->seq_len; q.Ls = p->vis_start; q.N = p->n_vis; q.H = p->n_heads; q.dh = p->head_dim;
+  q.B = p->batch; q.batch_call = p->batch; q.L = p->seq_len; q.Ls = p->vis_start; q.N = p->n_vis; q.H = p->n_heads; q.dh = p->head_dim;
   q.D = q.H * q.dh; q.hidden = p->hidden_dim; q.kp = p->k_prune; q.kf = p->k_final; q.m = q.kp - q.kf;
   q.nA = nA; q.nB = nB;
   q.Np = round_up(q.N, JT); q.nblk = q.Np / JB; q.P = q.nblk / 2; q.steps = q.nblk - 1;
@@ -99,9 +99,10 @@ static int direct_chain(const Plan& pl, const Plan& sub, int img0, const tc_para
   double* evec = at<double>(ws, pl.off_td_e) + i0 * Np;
   float* tauv = at<float>(ws, pl.off_td_tau) + i0 * Np;
   float* Vc = at<float>(ws, pl.off_U) + i0 * Np * Np;
-  int rc = launch_tridiag(sub, G, dvec, evec, tauv, Vc, st);
-  if (rc != TC_OK) return rc;
   double* tw = at<double>(ws, pl.off_td_tw);
+  // (the panels of the reduction pass through the start of the image's pivot scratch, which is idle until stage 2)
+  int rc = launch_tridiag(sub, G, dvec, evec, tauv, Vc, tw + i0 * Np * Np, Np * Np, st);
+  if (rc != TC_OK) return rc;
   return launch_td_eigen(sub, dvec, evec, tauv, Vc, at<double>(ws, pl.off_td_lam) + i0 * Np, at<int2>(ws, pl.off_td_blk) + i0 * Np,
                          at<double>(ws, pl.off_td_tnorm) + i0, tw + i0 * Np * Np, tw + ((size_t)pl.B + i0) * Np * Np,
                          at<float>(ws, pl.off_td_W) + i0 * Np * Np, at<double>(ws, pl.off_td_rn) + i0 * Np,

@@ -44,6 +44,7 @@ struct Plan {
   int steps;     // nblk - 1 steps per sweep
   int q_tile;    // query rows per attention workgroup
   int n_qtiles;
+  int batch_call;        // images of the whole call (B is the group's share when the batch is cut into stream groups)
   int Nq;                // query rows whose probabilities enter the attention score: N + prompt rows
   size_t spart_stride;   // floats of the partial-score region per image
   int esize;     // bytes of one stored element (2 or 4)
@@ -88,7 +89,8 @@ int launch_sigma(const Plan& pl, int eig_dtype, const void* G, const EigState* s
 int launch_combine(const Plan& pl, const float* C_ws, const float* S, float lambda, int norm_mode, float* E, hipStream_t st);
 // direct eigensolver (tridiag.hip, tdeig.hip)
 int tridiag_panel_width(int N);
-int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, hipStream_t st);
+int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, double* panels,
+                   size_t panels_stride, hipStream_t st);
 int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, const float* tauv, const float* Vc,
                     double* lam, int2* blk, double* tnorm, double* DP, double* DM, float* W, double* rn, int32_t* bad,
                     double* sig, double* wgt, double* Cpart, float* Tf, float sv_rtol, bool vectors, float* C, float* C_out,
@@ -107,7 +109,7 @@ int launch_merge(const Plan& pl, int dtype, const void* X, const void* metric, c
 // ---- optional per-kernel timing (only active inside tc_profile_compress) ----------------------
 enum ProfKind {
   PK_ATTN = 0, PK_ATTN_REDUCE, PK_GRAM, PK_JINIT, PK_JSOLVE, PK_JUPDATE, PK_JUPDATE_U, PK_JSWEEPEND, PK_SIGMA, PK_ICS, PK_COMBINE,
-  PK_TOPK, PK_ROWNORM, PK_SIM, PK_ASSIGN, PK_AVERAGE, PK_TRIDIAG, PK_BISECT, PK_TWISTED, PK_BACKTF, PK_COUNT
+  PK_TOPK, PK_ROWNORM, PK_SIM, PK_ASSIGN, PK_AVERAGE, PK_TRIDIAG, PK_BISECT, PK_TWISTED, PK_BACKTF, PK_TRIDIAG_UPDATE, PK_COUNT
 };
 static_assert((int)PK_COUNT == (int)TC_PROF_KINDS, "internal and public kernel kinds must match");
 void prof_begin(int kind, int tag, hipStream_t st);  // no-ops unless a profile run is active on this thread

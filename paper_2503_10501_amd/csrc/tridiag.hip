@@ -3,18 +3,20 @@
 // so that the singular vectors of Section 3.3.1 (Z = U Sigma V^T, Z Z^T = U Sigma^2 U^T) become
 // U = Q W with T W = W Sigma^2 (stages 2 and 3: tdeig.hip).
 //
-// One workgroup of 16 wavefronts reduces one image; nothing is exchanged between workgroups.  The
-// reduction is bound by memory: column j needs the product of the trailing (N-j-1)^2 matrix with v_j.
-// Measured on MI355X a single workgroup streams 150 GB/s out of its L2 and 64 of them together 6 TB/s,
-// which is what the fabric delivers to any number of compute units for a working set of this size, so
-// one compute unit per image is enough at batch 64.
+// The columns of an image are reduced by one workgroup of 16 wavefronts.  The reduction is bound by
+// memory: column j needs the product of the trailing (N-j-1)^2 matrix with v_j.  Measured on MI355X a
+// single workgroup streams 150 GB/s out of its L2 and 64 of them together 6 TB/s, which is what the
+// fabric delivers to any number of compute units for a working set of this size, so one compute unit per
+// image is enough for the products at batch 64.
 //
 // The trailing matrix is only rewritten once per panel of nb columns (the scheme of LAPACK's
 // dlatrd/dsytrd): inside a panel the reflectors v and the vectors w of the rank-2 updates
 // A <- A - v w^T - w v^T are kept in LDS (panels Vp, Wp) and applied on the fly to the column being
-// reduced and to the matrix-vector product; at the end of the panel the trailing matrix gets the
-// rank-2nb update on the matrix cores (computed for the lower triangle, stored to both: the matrix-vector
-// product reads whole rows).
+// reduced and to the matrix-vector product (tridiag_panel_kernel, one launch per panel).  The panels then
+// go to global memory and the trailing matrix gets the rank-2nb update on the matrix cores from a launch
+// of its own that spreads over the whole chip (tridiag_update_kernel: computed for the lower triangle,
+// stored to both, since the matrix-vector product reads whole rows): inside the panel kernel the update
+// ran on one compute unit per image, 2 of its 10.7 ms per batch of 64 and of its 9.3 ms for one image.
 // G is symmetric and stored in full, so the product p = A v is formed as column sums over rows,
 // p_c = sum_i A[i][c] v_i: a lane owns two neighbouring columns, loads are 16 bytes wide and contiguous
 // across the wavefront, and no cross-lane reduction is needed; 4 row groups x 4 column groups of
@@ -58,15 +60,73 @@ __device__ inline double td_block_sum(double x, double* scratch, int wave, int l
   return s;
 }
 
+// One task of the rank-2nb update: trailing matrix (rows and columns jend .. N-1) <- itself - Vp Wp^T - Wp Vp^T on
+// the matrix cores, for the strip of 16 rows x 64 columns (a, bch) counted from base = jend rounded down to 16;
+// product ks contracts over k = 4 ks + lane / 16 of the 2 kcols columns of [Vp | Wp] (rows) against [Wp | Vp]
+// (columns).  Only strips that reach the diagonal or lie below it are computed (64 bch <= 16 a + 15); a strip
+// strictly below the diagonal also writes its mirror image, which is a strip that is skipped.  Vp, Wp: [Nr][nb]
+// in LDS or in global memory.
+__device__ inline void td_update_strip(double* __restrict__ A, int N, int Np, int Nr, int nb, int jend, int kcols,
+                                       const double* Vp, const double* Wp, int a, int bch, int lane) {
+  const int l15 = lane & 15, q4 = lane >> 4;
+  const int base = jend & ~15;
+  const int rt = base + 16 * a, ct = base + 64 * bch;
+  const bool below = 64 * bch + 63 < 16 * a;
+  d4 acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; t++) {
+    const int cc = ct + 16 * t + l15;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      const int rr = rt + 4 * e + q4;
+      acc[t][e] = (rr < N && cc < N) ? A[(size_t)rr * Np + cc] : 0.0;
+    }
+  }
+  const int arow = min(rt + l15, Nr - 1);
+  const int ksteps = kcols >> 2;
+  for (int half = 0; half < 2; half++) {
+    const double* L = half == 0 ? Vp : Wp;   // row factor
+    const double* R = half == 0 ? Wp : Vp;   // column factor
+    for (int ks = 0; ks < ksteps; ks++) {
+      const int k = 4 * ks + q4;
+      const double av = -L[arow * nb + k];
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        const int crow = min(ct + 16 * t + l15, Nr - 1);
+        acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, R[crow * nb + k], acc[t], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 4; t++) {
+    const int cc = ct + 16 * t + l15;
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      const int rr = rt + 4 * e + q4;
+      if (rr >= jend && cc >= jend && rr < N && cc < N) {
+        A[(size_t)rr * Np + cc] = acc[t][e];
+        if (below) A[(size_t)cc * Np + rr] = acc[t][e];
+      }
+    }
+  }
+}
+
 // G      [B][Np][Np]  in: the Gram matrix, symmetric, stored in full; destroyed
 // dvec   [B][Np]      out: diagonal of T
 // evec   [B][Np]      out: evec[j] = T[j+1][j], j < N-1
 // tauv   [B][Np]      out: tau_j (0 for a reflector that is the identity)
 // Vc     [B][Np/16][Np][16] out, float: the reflectors in blocks of sixteen, Vc[j / 16][i][j % 16] = v_j[i] (zeros up to
 //                     i = j, 1 at j + 1) -- the layout stage 3 copies into LDS; reflectors j >= N-1 are not written
-__global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict__ G, int N, int Np, int nb,
-                                                             double* __restrict__ dvec, double* __restrict__ evec,
-                                                             float* __restrict__ tauv, float* __restrict__ Vc) {
+// panels [B][2][Nr][nb] out: the panel's Vp and Wp (zero beyond the panel's columns, up to kcols) for the update
+// One launch reduces the panels that start at j0, j0 + nb, ... below j0_stop.  fused != 0: the update after each
+// panel runs inside the kernel, on this image's compute unit (the whole reduction in one launch: better from about
+// a hundred images on, where the chip is full anyway); fused == 0: one panel per launch, the panels go to global
+// memory and tridiag_update_kernel follows.
+__global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __restrict__ G, int N, int Np, int nb, int j0_first,
+                                                                   int j0_stop, int fused,
+                                                                   double* __restrict__ dvec, double* __restrict__ evec,
+                                                                   float* __restrict__ tauv, float* __restrict__ Vc,
+                                                                   double* __restrict__ panels, size_t panels_stride) {
   extern __shared__ __attribute__((aligned(16))) unsigned char td_smem[];
   const int Nr = round_up(N, 16);
   double* Vp = reinterpret_cast<double*>(td_smem);  // [Nr][nb] reflectors of the panel
@@ -85,7 +145,7 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
   float* Vout = Vc + (size_t)b * Np * Np;
   const int l15 = lane & 15, q4 = lane >> 4;
 
-  for (int j0 = 0; j0 < N - 1; j0 += nb) {
+  for (int j0 = j0_first; j0 < j0_stop; j0 += nb) {
     const int jend = min(j0 + nb, N - 1);  // this panel reduces columns j0 .. jend-1
     for (int j = j0; j < jend; j++) {
       const int jj = j - j0;
@@ -193,83 +253,94 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_kernel(double* __restrict_
       }
     }
     __syncthreads();
-    // trailing matrix (rows and columns jend .. N-1) <- itself - Vp Wp^T - Wp Vp^T on the matrix cores.
-    // A task is a strip of 16 rows x 64 columns; product ks contracts over k = 4 ks + lane / 16 of the
-    // 2 kcols columns of [Vp | Wp] (rows) against [Wp | Vp] (columns).
-    {
+    if (fused) {  // strips are dealt to the wavefronts round-robin
       const int base = jend & ~15;
       const int nrt = (N - base + 15) >> 4, ncc = (N - base + 63) >> 6;
-      const int ksteps = kcols >> 2;
-#ifndef TD_PROBE_NO_SYR2K
-      // Only strips that reach the diagonal or lie below it are computed (column chunk b of row tile a with
-      // 64 b <= 16 a + 15); a strip strictly below the diagonal also writes its mirror image, which is a
-      // strip that is skipped.  Strips are dealt to the wavefronts round-robin in this order.
       int idx = 0;
       for (int a = 0; a < nrt; a++) {
-        const int nb_a = min(ncc, (a >> 2) + 1);
-        for (int bch = 0; bch < nb_a; bch++, idx++) {
-          if ((idx & (TD_WAVES - 1)) != wave) continue;  // uniform over the wavefront
-          const int rt = base + 16 * a, ct = base + 64 * bch;
-          const bool below = 64 * bch + 63 < 16 * a;
-          d4 acc[4];
-#pragma unroll
-          for (int t = 0; t < 4; t++) {
-            const int cc = ct + 16 * t + l15;
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-              const int rr = rt + 4 * e + q4;
-              acc[t][e] = (rr < N && cc < N) ? A[(size_t)rr * Np + cc] : 0.0;
-            }
-          }
-          const int arow = min(rt + l15, Nr - 1);
-          for (int half = 0; half < 2; half++) {
-            const double* L = half == 0 ? Vp : Wp;   // row factor
-            const double* R = half == 0 ? Wp : Vp;   // column factor
-            for (int ks = 0; ks < ksteps; ks++) {
-              const int k = 4 * ks + q4;
-              const double av = -L[arow * nb + k];
-#pragma unroll
-              for (int t = 0; t < 4; t++) {
-                const int crow = min(ct + 16 * t + l15, Nr - 1);
-                acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, R[crow * nb + k], acc[t], 0, 0, 0);
-              }
-            }
-          }
-#pragma unroll
-          for (int t = 0; t < 4; t++) {
-            const int cc = ct + 16 * t + l15;
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-              const int rr = rt + 4 * e + q4;
-              if (rr >= jend && cc >= jend && rr < N && cc < N) {
-                A[(size_t)rr * Np + cc] = acc[t][e];
-                if (below) A[(size_t)cc * Np + rr] = acc[t][e];
-              }
-            }
-          }
-        }
+        const int n_a = min(ncc, (a >> 2) + 1);
+        for (int bch = 0; bch < n_a; bch++, idx++)
+          if ((idx & (TD_WAVES - 1)) == wave) td_update_strip(A, N, Np, Nr, nb, jend, kcols, Vp, Wp, a, bch, lane);
       }
-#endif
+      __syncthreads();  // the rewritten matrix is visible to the whole workgroup
+    } else {
+      // the panels for the update of the trailing matrix (rows that the update does not store are written as zero)
+      double* Vg = panels + (size_t)b * panels_stride;
+      double* Wg = Vg + (size_t)Nr * nb;
+      for (int e = tid; e < Nr * kcols; e += TD_THREADS) {
+        const int i = e / kcols, k = e % kcols;
+        Vg[i * nb + k] = (i >= jend && i < N) ? Vp[i * nb + k] : 0.0;
+        Wg[i * nb + k] = (i >= jend && i < N) ? Wp[i * nb + k] : 0.0;
+      }
     }
-    __syncthreads();  // the rewritten matrix is visible to the whole workgroup
   }
-  if (tid == 0) {
+  if (fused && tid == 0) {
     dout[N - 1] = A[(size_t)(N - 1) * Np + (N - 1)];
     eout[N - 1] = 0.0;
     tout[N - 1] = 0.f;
   }
 }
 
-int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, hipStream_t st) {
-  const int nb = tridiag_panel_width(pl.N);
+// The update of the trailing matrix after a panel as a launch of its own: one wavefront per strip (td_update_strip),
+// panels read from global memory.
+__global__ __launch_bounds__(256) void tridiag_update_kernel(double* __restrict__ G, int N, int Np, int nb, int jend,
+                                                             int kcols, const double* __restrict__ panels,
+                                                             size_t panels_stride, int ntasks) {
+  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+  const int task = blockIdx.x * 4 + (tid >> 6);
+  if (task >= ntasks) return;  // uniform over the wavefront; no barrier in this kernel
+  const int Nr = round_up(N, 16);
+  const int base = jend & ~15;
+  const int ncc = (N - base + 63) >> 6;
+  int a = 0, rest = task;  // row tile a has min(ncc, a / 4 + 1) strips
+  for (;;) {
+    const int n_a = min(ncc, (a >> 2) + 1);
+    if (rest < n_a) break;
+    rest -= n_a;
+    a++;
+  }
+  const double* Vg = panels + (size_t)b * panels_stride;
+  td_update_strip(G + (size_t)b * Np * Np, N, Np, Nr, nb, jend, kcols, Vg, Vg + (size_t)Nr * nb, a, rest, lane);
+}
+
+// The last diagonal entry, after the last update.
+__global__ __launch_bounds__(64) void tridiag_last_kernel(const double* __restrict__ G, int N, int Np,
+                                                          double* __restrict__ dvec, double* __restrict__ evec,
+                                                          float* __restrict__ tauv) {
+  const int b = blockIdx.x;
+  if (threadIdx.x == 0) {
+    dvec[(size_t)b * Np + N - 1] = G[(size_t)b * Np * Np + (size_t)(N - 1) * Np + (N - 1)];
+    evec[(size_t)b * Np + N - 1] = 0.0;
+    tauv[(size_t)b * Np + N - 1] = 0.f;
+  }
+}
+
+int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, double* panels,
+                   size_t panels_stride, hipStream_t st) {
+  const int N = pl.N, nb = tridiag_panel_width(N);
   if (nb < 4) return TC_ERR_SHAPE;
-  const size_t lds = tridiag_lds_bytes(pl.N, nb);
+  if ((size_t)2 * round_up(N, 16) * nb > panels_stride) return TC_ERR_WORKSPACE;
+  const size_t lds = tridiag_lds_bytes(N, nb);
   // more than 64 KB of dynamic LDS has to be allowed per function (a cheap host call, repeated so that it
   // holds on whichever device is current)
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(tridiag_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(tridiag_panel_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           TD_LDS_BYTES) != hipSuccess)
     return TC_ERR_HIP;
-  TC_TIMED(PK_TRIDIAG, 0, st, (tridiag_kernel<<<pl.B, TD_THREADS, lds, st>>>(G, pl.N, pl.Np, nb, dvec, evec, tauv, Vc)));
+  if (pl.batch_call >= 96) {  // the chip is full of images: the whole reduction in one launch, updates on the image's own compute unit
+    TC_TIMED(PK_TRIDIAG, 0, st, (tridiag_panel_kernel<<<pl.B, TD_THREADS, lds, st>>>(G, N, pl.Np, nb, 0, N - 1, 1, dvec, evec, tauv, Vc, panels, panels_stride)));
+    return check_launch();
+  }
+  for (int j0 = 0; j0 < N - 1; j0 += nb) {
+    const int jend = j0 + nb < N - 1 ? j0 + nb : N - 1;
+    const int kcols = round_up(jend - j0, 4);
+    TC_TIMED(PK_TRIDIAG, 0, st, (tridiag_panel_kernel<<<pl.B, TD_THREADS, lds, st>>>(G, N, pl.Np, nb, j0, j0 + 1, 0, dvec, evec, tauv, Vc, panels, panels_stride)));
+    const int base = jend & ~15;
+    const int nrt = (N - base + 15) >> 4, ncc = (N - base + 63) >> 6;
+    int ntasks = 0;
+    for (int a = 0; a < nrt; a++) ntasks += ncc < (a >> 2) + 1 ? ncc : (a >> 2) + 1;
+    TC_TIMED(PK_TRIDIAG_UPDATE, 0, st, (tridiag_update_kernel<<<dim3((ntasks + 3) / 4, pl.B), 256, 0, st>>>(G, N, pl.Np, nb, jend, kcols, panels, panels_stride, ntasks)));
+  }
+  TC_TIMED(PK_TRIDIAG_UPDATE, 1, st, (tridiag_last_kernel<<<pl.B, 64, 0, st>>>(G, N, pl.Np, dvec, evec, tauv)));
   return check_launch();
 }
 
