@@ -399,11 +399,14 @@ __global__ __launch_bounds__(256) void td_cluster_kernel(const double* __restric
   double* rb = rn + (size_t)b * Np;
   float* Wb = W + (size_t)b * Np * Np;
   const double ctol = 1e-10 * tnorm[b];
+  // vectors of eigenvalues that count as zero (below the resolution of the reduction) get weight 0 in Eq. 3-6: they
+  // are left as they are, however many of them there are (the null space of a rank-deficient matrix)
+  const double floor0 = tnorm[b] > 0.0 ? 8.0 * TD_EPS * tnorm[b] : DBL_MAX;
   // quick exit: no close pair anywhere (the usual case)
   if (tid == 0) any = 0;
   __syncthreads();
   int mine = 0;
-  for (int k = 1 + tid; k < N; k += 256) mine |= (bb[k].x == bb[k - 1].x && lb[k] - lb[k - 1] <= ctol) ? 1 : 0;
+  for (int k = 1 + tid; k < N; k += 256) mine |= (bb[k].x == bb[k - 1].x && lb[k] - lb[k - 1] <= ctol && lb[k] > floor0) ? 1 : 0;
   if (mine) any = 1;  // every writer stores the same value
   __syncthreads();
   if (!any) return;
@@ -416,7 +419,7 @@ __global__ __launch_bounds__(256) void td_cluster_kernel(const double* __restric
   };
   int first = 0;  // first slot of the current cluster
   for (int k = 1; k < N; k++) {
-    const bool close = bb[k].x == bb[k - 1].x && lb[k] - lb[k - 1] <= ctol;  // uniform over the workgroup
+    const bool close = bb[k].x == bb[k - 1].x && lb[k] - lb[k - 1] <= ctol && lb[k] > floor0;  // uniform over the workgroup
     if (!close) { first = k; continue; }
     const int s = bb[k].x, t = bb[k].y;
     for (int j = first; j < k; j++) {

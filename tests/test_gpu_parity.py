@@ -213,6 +213,18 @@ def test_maximum_number_of_visual_tokens():
     assert max(rep["C_rel"]) < 1e-4
 
 
+@pytest.mark.parametrize("n_vis,heads", [(1024, 2), (700, 8), (577, 4)])
+def test_tridiagonal_route_up_to_its_largest_token_count(n_vis, heads):
+    # 577 .. 1024 tokens: narrower panels in the reduction, sixteen row tiles per wavefront and narrower strips in
+    # the back-transformation.  With two heads of 64 the Gram matrix of 1024 tokens has rank 128: the null space
+    # (896 eigenvalues below the resolution of the reduction) gets weight zero and must not be orthogonalised
+    tc, gu, parity, _, Workload = _mods()
+    w = Workload("direct_%d" % n_vis, 19, 2, n_vis, 5, 3, heads, 64, "bf16", n_vis // 4, n_vis // 8, 8, "powerlaw", 0.05, "proj")
+    rep = parity.run_all_stages(w, eig_method=METHODS["tridiagonal"])
+    print("direct", n_vis, rep)
+    assert max(rep["C_rel"]) < 1e-4
+
+
 @pytest.mark.parametrize("first", [0, 64])
 def test_llava13b_batch128_every_image(first, capsys):
     # the batch of 128 runs on the GPU as a whole both times; the oracle takes one half per test
