@@ -188,7 +188,6 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
       const int ncg = (ncols + 127) >> 7;        // <= 8 for N <= 1024
       const int nrg = TD_WAVES / ncg;            // >= 2
       const int pitch = ncg << 7;                // nrg * pitch <= 2048 partial sums
-#ifndef TD_PROBE_NO_MATVEC
       if (wave < ncg * nrg) {
         const int cg = wave % ncg, rg = wave / ncg;
         const int c = cbase + (cg << 7) + 2 * lane;
@@ -213,7 +212,6 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
           red[rg * pitch + (c - cbase) + 1] = acc.y;
         }
       }
-#endif
       // ---- W^T v and V^T v for the panel's earlier columns: one wavefront per dot product ------------------
       for (int id = wave; id < 2 * jj; id += TD_WAVES) {
         const double* P = id < jj ? Wp + id : Vp + (id - jj);
