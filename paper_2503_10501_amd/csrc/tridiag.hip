@@ -28,6 +28,9 @@ namespace tc {
 typedef __attribute__((ext_vector_type(2))) double d2;
 typedef __attribute__((ext_vector_type(4))) double d4;
 
+#ifndef TD_INFLIGHT
+#define TD_INFLIGHT 12
+#endif
 constexpr int TD_THREADS = 1024;
 constexpr int TD_WAVES = TD_THREADS / 64;
 constexpr int TD_LDS_BYTES = 160 * 1024;  // LDS of one compute unit, all of it for the one workgroup
@@ -180,8 +183,7 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
       // ---- p = A v over the trailing matrix (rows and columns j+1 .. N-1), as column sums -------------------
       // Wavefront (rg, cg): column group cg = 128 columns (a lane owns two neighbours, one 16-byte load per row),
       // row group rg = every nrg-th row.  As the trailing matrix shrinks there are fewer column groups and more
-      // row groups; sixteen rows are in flight per wavefront (16 KB), which is what it takes to keep a compute
-      // unit's share of the fabric busy at 2 us of latency.
+      // row groups; up to TD_INFLIGHT rows are in flight per wavefront.
       const int r0 = j + 1;
       const int cbase = r0 & ~1;                 // column pairs start at an even column
       const int ncols = N - cbase;
@@ -194,18 +196,31 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
         const bool ok = c < N;                   // (an odd N reads the zero padding column N as the pair's second half)
         const double* col = A + (ok ? c : cbase);
         d2 acc = d2{0.0, 0.0};
-        for (int ib = r0 + rg; ib < N; ib += 16 * nrg) {
-          d2 x[16];
+        // whole chunks of TD_INFLIGHT rows with all their loads in flight together, then chunks of 4, then single rows:
+        // no row is fetched that does not count (a chunk padded with repeated rows cost up to a tenth of the kernel)
+        int ib = r0 + rg;
+        for (; ib + (TD_INFLIGHT - 1) * nrg < N; ib += TD_INFLIGHT * nrg) {
+          d2 x[TD_INFLIGHT];
 #pragma unroll
-          for (int u = 0; u < 16; u++) {
-            const int i = ib + u * nrg;
-            x[u] = *reinterpret_cast<const d2*>(col + (size_t)(i < N ? i : r0) * Np);  // a row past the end: a valid one, weight 0
-          }
+          for (int u = 0; u < TD_INFLIGHT; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
 #pragma unroll
-          for (int u = 0; u < 16; u++) {
-            const int i = ib + u * nrg;
-            acc += x[u] * (i < N ? vs[i] : 0.0);
-          }
+          for (int u = 0; u < TD_INFLIGHT; u++) acc += x[u] * vs[ib + u * nrg];
+        }
+        for (; ib + 3 * nrg < N; ib += 4 * nrg) {
+          d2 x[4];
+#pragma unroll
+          for (int u = 0; u < 4; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
+#pragma unroll
+          for (int u = 0; u < 4; u++) acc += x[u] * vs[ib + u * nrg];
+        }
+        {
+          d2 x[3];
+#pragma unroll
+          for (int u = 0; u < 3; u++)
+            if (ib + u * nrg < N) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);  // uniform over the wavefront
+#pragma unroll
+          for (int u = 0; u < 3; u++)
+            if (ib + u * nrg < N) acc += x[u] * vs[ib + u * nrg];
         }
         if (ok) {
           red[rg * pitch + (c - cbase)] = acc.x;
