@@ -23,12 +23,31 @@ template <> struct Elem16<false> {
   typedef bf8 vec8;
   __device__ static inline f16v mma(vec8 a, vec8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
   __device__ static inline uint16_t bits(float f) { return float_to_bf16_bits(f); }
+  // a and b as packed 16-bit heads (a in the low half) and the packed heads of what the first rounding left
+  __device__ static inline void split2(float a, float b, uint32_t& head, uint32_t& rem) {
+    typedef __attribute__((ext_vector_type(2))) float f2;
+    typedef __attribute__((ext_vector_type(2))) __bf16 b2;
+    union { b2 v; uint32_t w; } h, r;
+    h.v = __builtin_convertvector(f2{a, b}, b2);
+    r.v = __builtin_convertvector(f2{a - __uint_as_float(h.w << 16), b - __uint_as_float(h.w & 0xffff0000u)}, b2);
+    head = h.w;
+    rem = r.w;
+  }
 };
 template <> struct Elem16<true> {
   typedef _Float16 elem;
   typedef h8 vec8;
   __device__ static inline f16v mma(vec8 a, vec8 b, f16v c) { return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0); }
   __device__ static inline uint16_t bits(float f) { return float_to_f16_bits(f); }
+  __device__ static inline void split2(float a, float b, uint32_t& head, uint32_t& rem) {
+    typedef __attribute__((ext_vector_type(2))) float f2;
+    typedef __attribute__((ext_vector_type(2))) _Float16 h2;
+    union { h2 v; uint32_t w; } h, r;
+    h.v = __builtin_convertvector(f2{a, b}, h2);
+    r.v = __builtin_convertvector(f2{a - (float)h.v[0], b - (float)h.v[1]}, h2);
+    head = h.w;
+    rem = r.w;
+  }
 };
 
 typedef __attribute__((ext_vector_type(2))) unsigned int u2v;
@@ -47,14 +66,19 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 constexpr int AQ = 128;  // queries per workgroup
 constexpr int AK = 64;   // keys per LDS tile
 
+// LDS: two stages of (K tile, transposed V tile), so that the next tile is written while this one is read
+// (one barrier per tile), and two sets of per-wavefront column sums.
 template <int DH>
 struct AttnSmem {
   static constexpr int KLD = DH + 8;  // bf16 elements per K row in LDS
   static constexpr int VLD = AK + 8;  // bf16 elements per V^T row in LDS
   static constexpr int K_BYTES = AK * KLD * 2;
   static constexpr int V_BYTES = DH * VLD * 2;
+  static constexpr int STAGE = K_BYTES + V_BYTES;
   static constexpr int O_BYTES = 4 * 32 * KLD * 2;
-  static constexpr int MAIN = (K_BYTES + V_BYTES) > O_BYTES ? (K_BYTES + V_BYTES) : O_BYTES;
+  static constexpr int MAIN = 2 * STAGE > O_BYTES ? 2 * STAGE : O_BYTES;
+  static constexpr int CS_BYTES = 2 * 4 * AK * 4;
+  static constexpr int TOTAL = MAIN + CS_BYTES;
 };
 
 template <int DH>
@@ -114,12 +138,167 @@ __device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const typename
 #pragma unroll
   for (int i = 0; i < 16; i++) acc[i] = 0.f;
   const uint16_t* row = Ks + (sub * 32 + (lane & 31)) * KLD + 8 * (lane >> 5);
+  vec8 a[DH / 16];  // all fragments first: the matrix-core chain then runs without waiting on LDS
 #pragma unroll
-  for (int ks = 0; ks < DH / 16; ks++) {
-    const vec8 a = *reinterpret_cast<const vec8*>(row + 16 * ks);
-    acc = Elem16<F16>::mma(a, qf[ks], acc);
-  }
+  for (int ks = 0; ks < DH / 16; ks++) a[ks] = *reinterpret_cast<const vec8*>(row + 16 * ks);
+#pragma unroll
+  for (int ks = 0; ks < DH / 16; ks++) acc = Elem16<F16>::mma(a[ks], qf[ks], acc);
   return acc;
+}
+
+// Pass 1 on one key tile: running row maximum and normaliser (log2 domain).  MASKED = the tile crosses the
+// causal edge of some query of the wavefront; the arithmetic on the visible keys is the same in both
+// forms, so a query's statistics do not depend on where the query tiles fall.
+template <int DH, bool F16, bool MASKED>
+__device__ inline void stats_tile(const uint16_t* Ks, const typename Elem16<F16>::vec8* qf, int k0, int kend_q,
+                                  float scale_log2e, float& m_run, float& l_run, int lane) {
+  const int half = lane >> 5;
+  f16v s[2];
+  s[0] = score_subtile<DH, F16>(Ks, 0, qf, lane);
+  s[1] = score_subtile<DH, F16>(Ks, 1, qf, lane);
+  float mx = -INFINITY;
+#pragma unroll
+  for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      if (!MASKED || key < kend_q) mx = fmaxf(mx, s[sub][r]);
+    }
+  if (!MASKED || mx > -INFINITY) {
+    const float m_new = fmaxf(m_run, mx * scale_log2e);  // the scale is positive
+    float sum = 0.f;
+#pragma unroll
+    for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const float e = fast_exp2(fmaf(s[sub][r], scale_log2e, -m_new));
+        sum += (!MASKED || key < kend_q) ? e : 0.f;
+      }
+    l_run = l_run * fast_exp2(m_run - m_new) + sum;
+    m_run = m_new;
+  }
+}
+
+// O^T += V^T P^T for one 32-key sub-tile.  Matrix-core k-slot (half, i) of product u is key
+// sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
+template <int DH, bool F16>
+__device__ inline void pv_subtile(const uint16_t* Vt, int sub, const float* pr, f16v* oacc, int lane) {
+  typedef typename Elem16<F16>::vec8 vec8;
+  constexpr int VLD = AttnSmem<DH>::VLD;
+  const int half = lane >> 5;
+#pragma unroll
+  for (int u = 0; u < 2; u++) {
+    // probabilities enter the matrix cores as a 16-bit head plus a 16-bit remainder (16 or more
+    // significant bits), so O is accurate to its own final rounding
+    union { uint32_t w[4]; vec8 v; } pb, pl;
+#pragma unroll
+    for (int i = 0; i < 4; i++) Elem16<F16>::split2(pr[8 * u + 2 * i], pr[8 * u + 2 * i + 1], pb.w[i], pl.w[i]);
+#pragma unroll
+    for (int mt = 0; mt < DH / 32; mt++) {
+      union { uint4 u4; vec8 v; } va;  // V^T row 32 mt + lane%32, the lane's eight keys (stored side by side)
+      va.u4 = *reinterpret_cast<const uint4*>(Vt + (32 * mt + (lane & 31)) * VLD + sub * 32 + 16 * u + 8 * half);
+      oacc[mt] = Elem16<F16>::mma(va.v, pb.v, oacc[mt]);
+      oacc[mt] = Elem16<F16>::mma(va.v, pl.v, oacc[mt]);
+    }
+  }
+}
+
+// Column sums of one sub-tile over this wavefront's 32 queries (the 32 lanes of each half): recursive
+// halving, 16 values -> 1 value per lane pair.  First the two 16-lane rows of a half trade eight values
+// with the row-swap instruction (after it, one register holds a value's two row parts in the even row and
+// the other the partner value's in the odd row), then lanes L and 15-L, L and 7-L, L and L^2 trade through
+// data-parallel lane permutations, and the two lanes of a pair are added.  pr is used up.
+__device__ inline void colsum_subtile(float* pr, float* cs_sub, int lane) {
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const u2v sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(pr[i]), __float_as_uint(pr[i + 8]), false, false);
+    pr[i] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  }
+  {
+    const bool up = (lane & 8) != 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++) pr[i] = (up ? pr[i + 4] : pr[i]) + lane_perm<0x140>(up ? pr[i] : pr[i + 4]);  // L <-> 15-L
+  }
+  {
+    const bool up = (lane & 4) != 0;
+#pragma unroll
+    for (int i = 0; i < 2; i++) pr[i] = (up ? pr[i + 2] : pr[i]) + lane_perm<0x141>(up ? pr[i] : pr[i + 2]);  // L <-> 7-L
+  }
+  {
+    const bool up = (lane & 2) != 0;
+    pr[0] = (up ? pr[1] : pr[0]) + lane_perm<0x4E>(up ? pr[0] : pr[1]);  // L <-> L^2
+  }
+  pr[0] += lane_perm<0xB1>(pr[0]);  // L <-> L^1
+  if ((lane & 1) == 0) {
+    const int r = (lane >> 1) & 15;  // accumulator element whose column sum this lane pair holds
+    cs_sub[8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)] = pr[0];
+  }
+}
+
+// Pass 2 on one key tile: exact probabilities, O^T accumulation (WANT_O), column sums.  The scores of both
+// sub-tiles come first so that the exponentials of one overlap the matrix-core work of the other.
+template <int DH, bool F16, bool MASKED, bool WANT_O>
+__device__ inline void probs_tile(const uint16_t* Ks, const uint16_t* Vt, const typename Elem16<F16>::vec8* qf, f16v* oacc,
+                                  float* cs_wave, int k0, int kend_q, float scale_log2e, float m_fold, int lane) {
+  const int half = lane >> 5;
+  f16v s[2];
+  s[0] = score_subtile<DH, F16>(Ks, 0, qf, lane);
+  s[1] = score_subtile<DH, F16>(Ks, 1, qf, lane);
+#pragma unroll
+  for (int sub = 0; sub < 2; sub++) {
+    float pr[16];
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+      const float e = fast_exp2(fmaf(s[sub][r], scale_log2e, -m_fold));
+      pr[r] = (!MASKED || key < kend_q) ? e : 0.f;
+    }
+    if (WANT_O) pv_subtile<DH, F16>(Vt, sub, pr, oacc, lane);
+    colsum_subtile(pr, cs_wave + sub * 32, lane);
+  }
+}
+
+template <int DH, bool F16, bool WANT_O>
+__device__ inline void probs_pass(unsigned char* smem, const uint16_t* __restrict__ Kh, const uint16_t* __restrict__ Vh,
+                                  const typename Elem16<F16>::vec8* qf, f16v* oacc, uint4* kr, uint4* vr, float* sp_row,
+                                  int n_tiles, int kvis_all, int kend_q, float scale_log2e, float m_fold, int L, int Ls,
+                                  int N) {
+  typedef AttnSmem<DH> SM;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float* cs = reinterpret_cast<float*>(smem + SM::MAIN);  // [2][4][AK]
+  store_k_tile<DH>(reinterpret_cast<uint16_t*>(smem), kr);
+  store_v_tile_transposed<DH>(reinterpret_cast<uint16_t*>(smem + SM::K_BYTES), vr);
+  __syncthreads();
+  if (n_tiles > 1) {
+    load_k_tile<DH>(Kh, AK, L, kr);
+    load_v_tile<DH>(Vh, AK, L, vr);
+  }
+  for (int t = 0; t < n_tiles; t++) {
+    const int k0 = t * AK;
+    unsigned char* stage = smem + (t & 1) * SM::STAGE;
+    unsigned char* other = smem + ((t + 1) & 1) * SM::STAGE;
+    const uint16_t* Ks = reinterpret_cast<const uint16_t*>(stage);
+    const uint16_t* Vt = reinterpret_cast<const uint16_t*>(stage + SM::K_BYTES);
+    float* cs_t = cs + (t & 1) * 4 * AK;
+    if (k0 + AK <= kvis_all)  // every key visible to every query of the wavefront: no masks
+      probs_tile<DH, F16, false, WANT_O>(Ks, Vt, qf, oacc, cs_t + wave * AK, k0, kend_q, scale_log2e, m_fold, lane);
+    else
+      probs_tile<DH, F16, true, WANT_O>(Ks, Vt, qf, oacc, cs_t + wave * AK, k0, kend_q, scale_log2e, m_fold, lane);
+    if (t + 1 < n_tiles) {  // the other stage was last read before the previous barrier
+      store_k_tile<DH>(reinterpret_cast<uint16_t*>(other), kr);
+      store_v_tile_transposed<DH>(reinterpret_cast<uint16_t*>(other + SM::K_BYTES), vr);
+    }
+    __syncthreads();
+    if (t + 2 < n_tiles) {
+      load_k_tile<DH>(Kh, k0 + 2 * AK, L, kr);
+      load_v_tile<DH>(Vh, k0 + 2 * AK, L, vr);
+    }
+    if (tid < AK) {  // this set of column sums is written again two tiles on, behind the next barrier
+      const int x = k0 + tid - Ls;
+      if (x >= 0 && x < N) sp_row[x] = (cs_t[tid] + cs_t[AK + tid]) + (cs_t[2 * AK + tid] + cs_t[3 * AK + tid]);
+    }
+  }
 }
 
 template <int DH, bool F16>
@@ -129,11 +308,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
                                                         int causal, float scale_log2e, int n_qtiles, int B, size_t stride) {
   typedef AttnSmem<DH> SM;
   typedef typename Elem16<F16>::vec8 vec8;
-  typedef typename Elem16<F16>::elem elem;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SM::MAIN];
-  __shared__ float cs[4][AK];
-  uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
-  uint16_t* Vt = reinterpret_cast<uint16_t*>(smem + SM::K_BYTES);
+  extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
+  unsigned char* smem = attn_smem;
   int bh, qt;  // the query tiles of one (image, head) share K and V: keep them on one XCD
   if (!group_on_xcd(blockIdx.x, n_qtiles, B * H, &bh, &qt)) return;
   qt = n_qtiles - 1 - qt;  // longest (latest) query tile first
@@ -143,17 +319,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   const uint16_t* Qh = Q + head_off;
   const uint16_t* Kh = K + head_off;
   const uint16_t* Vh = V + head_off;
-  const int q = qt * AQ + wave * 32 + (lane & 31);
+  // The tiles are laid so that the last one is full: a ragged query count leaves its empty rows in the first
+  // tile, the one with the fewest visible keys under the causal mask.
+  const int qbase = qt * AQ - (n_qtiles * AQ - Nq);
+  const int q = qbase + wave * 32 + (lane & 31);
   // query rows 0 .. N-1 are the visual tokens; rows N .. Nq-1 (prompt tokens) only add to the column sums
-  const bool qvalid = q < Nq;
-  const int p = Ls + (qvalid ? q : Nq - 1);           // sequence position of this lane's query
+  const bool qvalid = q >= 0;
+  const int p = Ls + (qvalid ? q : 0);                // sequence position of this lane's query
   const int kend_q = causal ? p + 1 : L;              // keys [0, kend_q) are visible to it
-  const int q_last = min(Nq, (qt + 1) * AQ) - 1;
-  const int kend = causal ? min(L, Ls + q_last + 1) : L;
+  const int kend = causal ? min(L, Ls + qbase + AQ) : L;  // the tile's last query sees the most
   const int n_tiles = (kend + AK - 1) / AK;
   // keys [0, kvis_all) are visible to every query of this wavefront (its first query sees the fewest)
-  const int kvis_all = causal ? min(L, Ls + min(qt * AQ + wave * 32, Nq - 1) + 1) : L;
-  const bool want_o = qt * AQ + wave * 32 < N;  // this wavefront holds visual rows: their output is wanted
+  const int kvis_all = causal ? min(L, Ls + max(qbase + wave * 32, 0) + 1) : L;
 
   vec8 qf[DH / 16];
 #pragma unroll
@@ -161,47 +338,25 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
     qf[ks] = *reinterpret_cast<const vec8*>(Qh + (size_t)p * DH + 16 * ks + 8 * half);
 
   // ---------------- pass 1: row maximum and normaliser (log2 domain) ----------------
-  // (both passes fetch the next key tile into registers while the matrix cores work on this one)
+  // Both passes keep the tile after the next in registers (fetched while the matrix cores work on this one)
+  // and write it into the LDS stage that is not being read; one barrier per tile.
   float m_run = -INFINITY, l_run = 0.f;
   uint4 kr[AK * (DH / 8) / 256], vr[DH / 32];
   load_k_tile<DH>(Kh, 0, L, kr);
+  store_k_tile<DH>(reinterpret_cast<uint16_t*>(smem), kr);
+  __syncthreads();
+  load_k_tile<DH>(Kh, n_tiles > 1 ? AK : 0, L, kr);  // after the last tile of this pass: tile 0 for pass 2
+  load_v_tile<DH>(Vh, 0, L, vr);
   for (int t = 0; t < n_tiles; t++) {
     const int k0 = t * AK;
+    const uint16_t* Ks = reinterpret_cast<const uint16_t*>(smem + (t & 1) * SM::STAGE);
+    if (k0 + AK <= kvis_all)
+      stats_tile<DH, F16, false>(Ks, qf, k0, kend_q, scale_log2e, m_run, l_run, lane);
+    else
+      stats_tile<DH, F16, true>(Ks, qf, k0, kend_q, scale_log2e, m_run, l_run, lane);
+    if (t + 1 < n_tiles) store_k_tile<DH>(reinterpret_cast<uint16_t*>(smem + ((t + 1) & 1) * SM::STAGE), kr);
     __syncthreads();
-    store_k_tile<DH>(Ks, kr);
-    __syncthreads();
-    load_k_tile<DH>(Kh, t + 1 < n_tiles ? k0 + AK : 0, L, kr);  // after the last tile: tile 0 for pass 2
-#pragma unroll
-    for (int sub = 0; sub < 2; sub++) {
-      const f16v acc = score_subtile<DH, F16>(Ks, sub, qf, lane);
-      if (k0 + sub * 32 + 32 <= kvis_all) {  // every key visible to every query of the wavefront: no masks
-        float mx = acc[0];
-#pragma unroll
-        for (int r = 1; r < 16; r++) mx = fmaxf(mx, acc[r]);
-        const float m_new = fmaxf(m_run, mx * scale_log2e);  // the scale is positive
-        float sum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; r++) sum += fast_exp2(fmaf(acc[r], scale_log2e, -m_new));
-        l_run = l_run * fast_exp2(m_run - m_new) + sum;
-        m_run = m_new;
-        continue;
-      }
-      float s2[16], mx = -INFINITY;
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        s2[r] = key < kend_q ? acc[r] * scale_log2e : -INFINITY;
-        mx = fmaxf(mx, s2[r]);
-      }
-      if (mx > -INFINITY) {
-        const float m_new = fmaxf(m_run, mx);
-        float sum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; r++) sum += fast_exp2(s2[r] - m_new);
-        l_run = l_run * fast_exp2(m_run - m_new) + sum;
-        m_run = m_new;
-      }
-    }
+    if (t + 1 < n_tiles) load_k_tile<DH>(Kh, t + 2 < n_tiles ? k0 + 2 * AK : 0, L, kr);
   }
   {
     const float m_o = __shfl_xor(m_run, 32, 64), l_o = __shfl_xor(l_run, 32, 64);
@@ -209,7 +364,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
     l_run = l_run * fast_exp2(m_run - M) + l_o * fast_exp2(m_o - M);
     m_run = M;
   }
-  // p = 2^(s - m) / l = 2^(s - (m + log2 l)); rows past Nq contribute nothing (2^-inf = 0)
+  // p = 2^(s - m) / l = 2^(s - (m + log2 l)); rows before the first query contribute nothing (2^-inf = 0)
   const float m_fold = qvalid ? m_run + log2f(l_run) : INFINITY;
 
   // ---------------- pass 2: probabilities, O^T accumulation, column sums ----------------
@@ -219,95 +374,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
 #pragma unroll
     for (int i = 0; i < 16; i++) oacc[mt][i] = 0.f;
   float* sp_row = Spart + (size_t)b * stride + ((size_t)h * n_qtiles + qt) * N;
-  load_v_tile<DH>(Vh, 0, L, vr);
-  for (int t = 0; t < n_tiles; t++) {
-    const int k0 = t * AK;
-    __syncthreads();
-    store_k_tile<DH>(Ks, kr);
-    store_v_tile_transposed<DH>(Vt, vr);
-    __syncthreads();
-    if (t + 1 < n_tiles) {
-      load_k_tile<DH>(Kh, k0 + AK, L, kr);
-      load_v_tile<DH>(Vh, k0 + AK, L, vr);
-    }
-    // one 32-key sub-tile at a time keeps the live register set small (two wavefronts per SIMD)
-#pragma unroll
-    for (int sub = 0; sub < 2; sub++) {
-      float pr[16];
-      {
-        const f16v acc = score_subtile<DH, F16>(Ks, sub, qf, lane);
-        if (k0 + sub * 32 + 32 <= kvis_all) {
-#pragma unroll
-          for (int r = 0; r < 16; r++) pr[r] = fast_exp2(fmaf(acc[r], scale_log2e, -m_fold));
-        } else {
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            const int key = k0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            pr[r] = key < kend_q ? fast_exp2(fmaf(acc[r], scale_log2e, -m_fold)) : 0.f;
-          }
-        }
-      }
-      // O^T += V^T P^T.  Matrix-core k-slot (half, i) of product u is key
-      // sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
-#pragma unroll
-      for (int u = 0; u < 2 && want_o; u++) {
-        // probabilities enter the matrix cores as a 16-bit head plus a 16-bit remainder (16 or more
-        // significant bits), so O is accurate to its own final rounding
-        vec8 pb, pl;
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-          const float pv = pr[8 * u + i];
-          pb[i] = (elem)pv;
-          pl[i] = (elem)(pv - (float)pb[i]);
-        }
-#pragma unroll
-        for (int mt = 0; mt < DH / 32; mt++) {
-          union { uint4 u4; vec8 v; } va;  // V^T row 32 mt + lane%32, the lane's eight keys (stored side by side)
-          va.u4 = *reinterpret_cast<const uint4*>(Vt + (32 * mt + (lane & 31)) * SM::VLD + sub * 32 + 16 * u + 8 * half);
-          oacc[mt] = Elem16<F16>::mma(va.v, pb, oacc[mt]);
-          oacc[mt] = Elem16<F16>::mma(va.v, pl, oacc[mt]);
-        }
-      }
-      // column sums over this wavefront's 32 queries (the 32 lanes of each half): recursive halving,
-      // 16 values -> 1 value per lane pair.  First the two 16-lane rows of a half trade eight values
-      // with the row-swap instruction (after it, one register holds a value's two row parts in the even
-      // row and the other the partner value's in the odd row), then lanes L and 15-L, L and 7-L,
-      // L and L^2 trade through data-parallel lane permutations, and the two lanes of a pair are added.
-#pragma unroll
-      for (int i = 0; i < 8; i++) {
-        const u2v sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(pr[i]), __float_as_uint(pr[i + 8]), false, false);
-        pr[i] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-      }
-      {
-        const bool up = (lane & 8) != 0;
-#pragma unroll
-        for (int i = 0; i < 4; i++) pr[i] = (up ? pr[i + 4] : pr[i]) + lane_perm<0x140>(up ? pr[i] : pr[i + 4]);  // L <-> 15-L
-      }
-      {
-        const bool up = (lane & 4) != 0;
-#pragma unroll
-        for (int i = 0; i < 2; i++) pr[i] = (up ? pr[i + 2] : pr[i]) + lane_perm<0x141>(up ? pr[i] : pr[i + 2]);  // L <-> 7-L
-      }
-      {
-        const bool up = (lane & 2) != 0;
-        pr[0] = (up ? pr[1] : pr[0]) + lane_perm<0x4E>(up ? pr[0] : pr[1]);  // L <-> L^2
-      }
-      pr[0] += lane_perm<0xB1>(pr[0]);  // L <-> L^1
-      if ((lane & 1) == 0) {
-        const int r = (lane >> 1) & 15;  // accumulator element whose column sum this lane pair holds
-        cs[wave][sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3)] = pr[0];
-      }
-    }
-    __syncthreads();
-    if (tid < AK) {
-      const int x = k0 + tid - Ls;
-      if (x >= 0 && x < N) sp_row[x] = (cs[0][tid] + cs[1][tid]) + (cs[2][tid] + cs[3][tid]);
-    }
-  }
+  if (qbase < N)  // the tile holds visual rows: their output is wanted
+    probs_pass<DH, F16, true>(smem, Kh, Vh, qf, oacc, kr, vr, sp_row, n_tiles, kvis_all, kend_q, scale_log2e, m_fold, L, Ls, N);
+  else
+    probs_pass<DH, F16, false>(smem, Kh, Vh, qf, oacc, kr, vr, sp_row, n_tiles, kvis_all, kend_q, scale_log2e, m_fold, L, Ls, N);
   // visual tokens behind the last key tile received no attention from this query tile
   for (int x = max(0, n_tiles * AK - Ls) + tid; x < N; x += 256) sp_row[x] = 0.f;
 
   // ---------------- write O: transpose through LDS, 16-byte rows stores ----------------
+  if (qbase >= N) return;
   __syncthreads();
   uint16_t* Os = reinterpret_cast<uint16_t*>(smem) + wave * 32 * SM::KLD;
 #pragma unroll
@@ -321,8 +396,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   constexpr int CH = DH / 8;
   for (int idx = lane; idx < 32 * CH; idx += 64) {
     const int ql = idx / CH, ch = idx % CH;
-    const int qq = qt * AQ + wave * 32 + ql;
-    if (qq < N)
+    const int qq = qbase + wave * 32 + ql;
+    if (qq >= 0 && qq < N)
       *reinterpret_cast<uint4*>(O + ((size_t)b * N + qq) * ((size_t)H * DH) + (size_t)h * DH + ch * 8) =
           *reinterpret_cast<const uint4*>(Os + ql * SM::KLD + ch * 8);
   }
@@ -429,7 +504,13 @@ int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const
     const uint16_t *q = (const uint16_t*)Q, *k = (const uint16_t*)K, *v = (const uint16_t*)V;
     uint16_t* o = (uint16_t*)O;
 #define TC_ATTN16(DH_, F16_) \
-  TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<DH_, F16_><<<grid, 256, 0, st>>>(q, k, v, o, Spart, pl.L, pl.Ls, pl.N, pl.Nq, pl.H, causal, sl2, pl.n_qtiles, pl.B, pl.spart_stride)))
+  do {                                                                                                                  \
+    constexpr int shm = AttnSmem<DH_>::TOTAL;                                                                             \
+    if (shm > 64 * 1024 && hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel<DH_, F16_>),                \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, shm) != hipSuccess)            \
+      return TC_ERR_HIP;                                                                                                  \
+    TC_TIMED(PK_ATTN, 0, st, (attn_bf16_kernel<DH_, F16_><<<grid, 256, shm, st>>>(q, k, v, o, Spart, pl.L, pl.Ls, pl.N, pl.Nq, pl.H, causal, sl2, pl.n_qtiles, pl.B, pl.spart_stride))); \
+  } while (0)
     if (pl.dh == 128) {
       if (dtype == TC_F16) TC_ATTN16(128, true); else TC_ATTN16(128, false);
     } else {
