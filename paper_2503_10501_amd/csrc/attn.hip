@@ -51,6 +51,7 @@ template <> struct Elem16<true> {
 };
 
 typedef __attribute__((ext_vector_type(2))) unsigned int u2v;
+typedef __attribute__((ext_vector_type(4))) unsigned int u4v;  // 16 bytes in registers (a native vector: no struct copies)
 
 // v of the lane that a data-parallel permutation control pairs this lane with (0x140: 15-L within a
 // row of 16 lanes, 0x141: 7-L within 8, 0x4E: L^2, 0xB1: L^1).  All lanes of the wavefront must be active.
@@ -81,36 +82,38 @@ struct AttnSmem {
   static constexpr int TOTAL = MAIN + CS_BYTES;
 };
 
+// Keys past the end of the sequence are read as the last key (no branch around a load, so that the compiler
+// counts the loads in flight exactly); they are masked out of every result.
 template <int DH>
-__device__ inline void load_k_tile(const uint16_t* __restrict__ Kh, int k0, int L, uint4* regs) {
+__device__ inline void load_k_tile(const uint16_t* __restrict__ Kh, int k0, int L, u4v* regs) {
   constexpr int CH = DH / 8, ITER = AK * CH / 256;
 #pragma unroll
   for (int it = 0; it < ITER; it++) {
     const int idx = threadIdx.x + 256 * it, key = idx / CH, ch = idx % CH;
-    regs[it] = (k0 + key < L) ? *reinterpret_cast<const uint4*>(Kh + (size_t)(k0 + key) * DH + ch * 8) : uint4{0, 0, 0, 0};
+    regs[it] = *reinterpret_cast<const u4v*>(Kh + (size_t)min(k0 + key, L - 1) * DH + ch * 8);
   }
 }
 template <int DH>
-__device__ inline void store_k_tile(uint16_t* Ks, const uint4* regs) {
+__device__ inline void store_k_tile(uint16_t* Ks, const u4v* regs) {
   constexpr int CH = DH / 8, ITER = AK * CH / 256, KLD = AttnSmem<DH>::KLD;
 #pragma unroll
   for (int it = 0; it < ITER; it++) {
     const int idx = threadIdx.x + 256 * it, key = idx / CH, ch = idx % CH;
-    *reinterpret_cast<uint4*>(Ks + key * KLD + ch * 8) = regs[it];
+    *reinterpret_cast<u4v*>(Ks + key * KLD + ch * 8) = regs[it];
   }
 }
 template <int DH>
-__device__ inline void load_v_tile(const uint16_t* __restrict__ Vh, int k0, int L, uint4* regs) {
+__device__ inline void load_v_tile(const uint16_t* __restrict__ Vh, int k0, int L, u4v* regs) {
   constexpr int ITER = DH / 32;
   const int key = threadIdx.x & 63;
 #pragma unroll
   for (int it = 0; it < ITER; it++) {
     const int ch = (threadIdx.x >> 6) + 4 * it;
-    regs[it] = (k0 + key < L) ? *reinterpret_cast<const uint4*>(Vh + (size_t)(k0 + key) * DH + ch * 8) : uint4{0, 0, 0, 0};
+    regs[it] = *reinterpret_cast<const u4v*>(Vh + (size_t)min(k0 + key, L - 1) * DH + ch * 8);
   }
 }
 template <int DH>
-__device__ inline void store_v_tile_transposed(uint16_t* Vt, const uint4* regs) {
+__device__ inline void store_v_tile_transposed(uint16_t* Vt, const u4v* regs) {
   constexpr int ITER = DH / 32, VLD = AttnSmem<DH>::VLD;
   const int key = threadIdx.x & 63;
   // Within a row the keys are stored with bits 2 and 3 swapped: the eight keys that one lane feeds
@@ -128,22 +131,37 @@ __device__ inline void store_v_tile_transposed(uint16_t* Vt, const uint4* regs) 
   }
 }
 
-// S^T sub-tile: 32 keys (rows) x 32 queries (columns); accumulator element r of a lane is
-// key 8*(r/4) + 4*(lane/32) + r%4, query lane%32.
+// One word of every 128-byte line of a K tile (threads 0 .. 127) and of a V tile (threads 128 .. 255), so that
+// the lines are on their way into the L2 well before the tile itself is fetched (a first read comes from HBM
+// and takes longer than the work on one tile).  Keys are clamped to [0, kcap): a touch past the end repeats a line.
+template <int DH>
+__device__ inline uint32_t touch_lines(const uint16_t* __restrict__ Kh, const uint16_t* __restrict__ Vh, int k_key0,
+                                       int v_key0, int kcap) {
+  constexpr int LPR = DH * 2 / 128;  // lines per row
+  const int i = min((int)(threadIdx.x & 127), AK * LPR - 1);
+  const bool is_v = threadIdx.x >= 128;
+  const int key = min(max(is_v ? v_key0 : k_key0, 0) + i / LPR, kcap - 1);
+  return *reinterpret_cast<const uint32_t*>((is_v ? Vh : Kh) + (size_t)key * DH + (i % LPR) * 64);
+}
+
+// The two S^T sub-tiles of a key tile, each 32 keys (rows) x 32 queries (columns); accumulator element r of a
+// lane is key 8*(r/4) + 4*(lane/32) + r%4, query lane%32.  The two chains of dependent matrix-core products
+// alternate, so that one runs while the other waits for its accumulator.
 template <int DH, bool F16>
-__device__ inline f16v score_subtile(const uint16_t* Ks, int sub, const typename Elem16<F16>::vec8* qf, int lane) {
+__device__ inline void score_pair(const uint16_t* Ks, const typename Elem16<F16>::vec8* qf, int lane, f16v& s0, f16v& s1) {
   typedef typename Elem16<F16>::vec8 vec8;
   constexpr int KLD = AttnSmem<DH>::KLD;
-  f16v acc;
 #pragma unroll
-  for (int i = 0; i < 16; i++) acc[i] = 0.f;
-  const uint16_t* row = Ks + (sub * 32 + (lane & 31)) * KLD + 8 * (lane >> 5);
-  vec8 a[DH / 16];  // all fragments first: the matrix-core chain then runs without waiting on LDS
+  for (int i = 0; i < 16; i++) s0[i] = s1[i] = 0.f;
+  const uint16_t* row0 = Ks + (lane & 31) * KLD + 8 * (lane >> 5);
+  const uint16_t* row1 = row0 + 32 * KLD;
 #pragma unroll
-  for (int ks = 0; ks < DH / 16; ks++) a[ks] = *reinterpret_cast<const vec8*>(row + 16 * ks);
-#pragma unroll
-  for (int ks = 0; ks < DH / 16; ks++) acc = Elem16<F16>::mma(a[ks], qf[ks], acc);
-  return acc;
+  for (int ks = 0; ks < DH / 16; ks++) {
+    const vec8 a0 = *reinterpret_cast<const vec8*>(row0 + 16 * ks);
+    const vec8 a1 = *reinterpret_cast<const vec8*>(row1 + 16 * ks);
+    s0 = Elem16<F16>::mma(a0, qf[ks], s0);
+    s1 = Elem16<F16>::mma(a1, qf[ks], s1);
+  }
 }
 
 // Pass 1 on one key tile: running row maximum and normaliser (log2 domain).  MASKED = the tile crosses the
@@ -154,8 +172,7 @@ __device__ inline void stats_tile(const uint16_t* Ks, const typename Elem16<F16>
                                   float scale_log2e, float& m_run, float& l_run, int lane) {
   const int half = lane >> 5;
   f16v s[2];
-  s[0] = score_subtile<DH, F16>(Ks, 0, qf, lane);
-  s[1] = score_subtile<DH, F16>(Ks, 1, qf, lane);
+  score_pair<DH, F16>(Ks, qf, lane, s[0], s[1]);
   float mx = -INFINITY;
 #pragma unroll
   for (int sub = 0; sub < 2; sub++)
@@ -180,6 +197,30 @@ __device__ inline void stats_tile(const uint16_t* Ks, const typename Elem16<F16>
   }
 }
 
+// One tile of pass 1 with its data movement: statistics from this stage, the next tile into the other stage,
+// one barrier, then the fetch of the tile after the next and a touch of lines further ahead (K four tiles on,
+// V one tile on for pass 2).  `touch` is the touch issued two tiles ago: it is waited for here, behind the
+// fetch that was issued after it.
+template <int DH, bool F16>
+__device__ __forceinline__ void stats_step(unsigned char* smem, const uint16_t* __restrict__ Kh, const uint16_t* __restrict__ Vh,
+                                           const typename Elem16<F16>::vec8* qf, u4v (&kr)[AK * (DH / 8) / 256],
+                                           uint32_t& touch, int t, int n_tiles, int kvis_all, int kend_q, int kcap, int L,
+                                           float scale_log2e, float& m_run, float& l_run) {
+  typedef AttnSmem<DH> SM;
+  const int k0 = t * AK, lane = threadIdx.x & 63;
+  const uint16_t* Ks = reinterpret_cast<const uint16_t*>(smem + (t & 1) * SM::STAGE);
+  if (k0 + AK <= kvis_all)
+    stats_tile<DH, F16, false>(Ks, qf, k0, kend_q, scale_log2e, m_run, l_run, lane);
+  else
+    stats_tile<DH, F16, true>(Ks, qf, k0, kend_q, scale_log2e, m_run, l_run, lane);
+  // (no branches in this part: behind the last tile the other stage takes a tile that nobody reads)
+  store_k_tile<DH>(reinterpret_cast<uint16_t*>(smem + ((t + 1) & 1) * SM::STAGE), kr);
+  asm volatile("" ::"v"(touch));
+  __syncthreads();
+  load_k_tile<DH>(Kh, t + 2 < n_tiles ? k0 + 2 * AK : 0, L, kr);
+  touch = touch_lines<DH>(Kh, Vh, k0 + 4 * AK, k0 + AK, kcap);
+}
+
 // O^T += V^T P^T for one 32-key sub-tile.  Matrix-core k-slot (half, i) of product u is key
 // sub*32 + 16u + 8*(i/4) + 4*half + i%4, which is accumulator element 8u+i of the score sub-tile.
 template <int DH, bool F16>
@@ -196,8 +237,8 @@ __device__ inline void pv_subtile(const uint16_t* Vt, int sub, const float* pr, 
     for (int i = 0; i < 4; i++) Elem16<F16>::split2(pr[8 * u + 2 * i], pr[8 * u + 2 * i + 1], pb.w[i], pl.w[i]);
 #pragma unroll
     for (int mt = 0; mt < DH / 32; mt++) {
-      union { uint4 u4; vec8 v; } va;  // V^T row 32 mt + lane%32, the lane's eight keys (stored side by side)
-      va.u4 = *reinterpret_cast<const uint4*>(Vt + (32 * mt + (lane & 31)) * VLD + sub * 32 + 16 * u + 8 * half);
+      union { u4v u4; vec8 v; } va;  // V^T row 32 mt + lane%32, the lane's eight keys (stored side by side)
+      va.u4 = *reinterpret_cast<const u4v*>(Vt + (32 * mt + (lane & 31)) * VLD + sub * 32 + 16 * u + 8 * half);
       oacc[mt] = Elem16<F16>::mma(va.v, pb.v, oacc[mt]);
       oacc[mt] = Elem16<F16>::mma(va.v, pl.v, oacc[mt]);
     }
@@ -243,8 +284,7 @@ __device__ inline void probs_tile(const uint16_t* Ks, const uint16_t* Vt, const 
                                   float* cs_wave, int k0, int kend_q, float scale_log2e, float m_fold, int lane) {
   const int half = lane >> 5;
   f16v s[2];
-  s[0] = score_subtile<DH, F16>(Ks, 0, qf, lane);
-  s[1] = score_subtile<DH, F16>(Ks, 1, qf, lane);
+  score_pair<DH, F16>(Ks, qf, lane, s[0], s[1]);
 #pragma unroll
   for (int sub = 0; sub < 2; sub++) {
     float pr[16];
@@ -261,7 +301,7 @@ __device__ inline void probs_tile(const uint16_t* Ks, const uint16_t* Vt, const 
 
 template <int DH, bool F16, bool WANT_O>
 __device__ inline void probs_pass(unsigned char* smem, const uint16_t* __restrict__ Kh, const uint16_t* __restrict__ Vh,
-                                  const typename Elem16<F16>::vec8* qf, f16v* oacc, uint4* kr, uint4* vr, float* sp_row,
+                                  const typename Elem16<F16>::vec8* qf, f16v* oacc, u4v* kr, u4v* vr, float* sp_row,
                                   int n_tiles, int kvis_all, int kend_q, float scale_log2e, float m_fold, int L, int Ls,
                                   int N) {
   typedef AttnSmem<DH> SM;
@@ -341,23 +381,22 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   // Both passes keep the tile after the next in registers (fetched while the matrix cores work on this one)
   // and write it into the LDS stage that is not being read; one barrier per tile.
   float m_run = -INFINITY, l_run = 0.f;
-  uint4 kr[AK * (DH / 8) / 256], vr[DH / 32];
+  u4v kr[AK * (DH / 8) / 256], vr[DH / 32];
   load_k_tile<DH>(Kh, 0, L, kr);
   store_k_tile<DH>(reinterpret_cast<uint16_t*>(smem), kr);
   __syncthreads();
   load_k_tile<DH>(Kh, n_tiles > 1 ? AK : 0, L, kr);  // after the last tile of this pass: tile 0 for pass 2
-  load_v_tile<DH>(Vh, 0, L, vr);
-  for (int t = 0; t < n_tiles; t++) {
-    const int k0 = t * AK;
-    const uint16_t* Ks = reinterpret_cast<const uint16_t*>(smem + (t & 1) * SM::STAGE);
-    if (k0 + AK <= kvis_all)
-      stats_tile<DH, F16, false>(Ks, qf, k0, kend_q, scale_log2e, m_run, l_run, lane);
-    else
-      stats_tile<DH, F16, true>(Ks, qf, k0, kend_q, scale_log2e, m_run, l_run, lane);
-    if (t + 1 < n_tiles) store_k_tile<DH>(reinterpret_cast<uint16_t*>(smem + ((t + 1) & 1) * SM::STAGE), kr);
-    __syncthreads();
-    if (t + 1 < n_tiles) load_k_tile<DH>(Kh, t + 2 < n_tiles ? k0 + 2 * AK : 0, L, kr);
+  // Lines of K four tiles ahead and of V (for pass 2) are touched while this pass runs; a touch is waited
+  // for two tiles later, behind the tile fetch that was issued after it.
+  const int kcap = min(L, n_tiles * AK);
+  uint32_t touch_a = touch_lines<DH>(Kh, Vh, 2 * AK, 0, kcap), touch_b = touch_lines<DH>(Kh, Vh, 3 * AK, 0, kcap);
+  for (int t = 0; t < n_tiles; t += 2) {
+    stats_step<DH, F16>(smem, Kh, Vh, qf, kr, touch_a, t, n_tiles, kvis_all, kend_q, kcap, L, scale_log2e, m_run, l_run);
+    if (t + 1 < n_tiles)
+      stats_step<DH, F16>(smem, Kh, Vh, qf, kr, touch_b, t + 1, n_tiles, kvis_all, kend_q, kcap, L, scale_log2e, m_run, l_run);
   }
+  asm volatile("" ::"v"(touch_a), "v"(touch_b));
+  load_v_tile<DH>(Vh, 0, L, vr);
   {
     const float m_o = __shfl_xor(m_run, 32, 64), l_o = __shfl_xor(l_run, 32, 64);
     const float M = fmaxf(m_run, m_o);  // finite: key 0 is visible to every query
@@ -398,8 +437,8 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
     const int ql = idx / CH, ch = idx % CH;
     const int qq = qbase + wave * 32 + ql;
     if (qq >= 0 && qq < N)
-      *reinterpret_cast<uint4*>(O + ((size_t)b * N + qq) * ((size_t)H * DH) + (size_t)h * DH + ch * 8) =
-          *reinterpret_cast<const uint4*>(Os + ql * SM::KLD + ch * 8);
+      *reinterpret_cast<u4v*>(O + ((size_t)b * N + qq) * ((size_t)H * DH) + (size_t)h * DH + ch * 8) =
+          *reinterpret_cast<const u4v*>(Os + ql * SM::KLD + ch * 8);
   }
 }
 
