@@ -83,6 +83,7 @@ int make_plan(const tc_params* p, Plan* pl) {
     q.off_td_tw = take(B * Np * Np * 16);      // pivots and multipliers of the twisted factorisations
     q.off_td_Cpart = take(B * nstrip * Np * 8);
     q.off_td_Tf = take(B * ((N + 15) / 16) * 256 * 4);   // T factors of the blocks of 16 reflectors
+    q.off_td_tab = take(B * Np * 24 * 4);                // wavefront assignments of the reduction, one table per image slot
   }
   q.total = off > 0 ? off : 256;
   return TC_OK;
@@ -101,7 +102,7 @@ static int direct_chain(const Plan& pl, const Plan& sub, int img0, const tc_para
   float* Vc = at<float>(ws, pl.off_U) + i0 * Np * Np;
   double* tw = at<double>(ws, pl.off_td_tw);
   // (the panels of the reduction pass through the start of the image's pivot scratch, which is idle until stage 2)
-  int rc = launch_tridiag(sub, G, dvec, evec, tauv, Vc, tw + i0 * Np * Np, Np * Np, st);
+  int rc = launch_tridiag(sub, G, dvec, evec, tauv, Vc, tw + i0 * Np * Np, Np * Np, at<int>(ws, pl.off_td_tab) + i0 * Np * 24, st);
   if (rc != TC_OK) return rc;
   return launch_td_eigen(sub, dvec, evec, tauv, Vc, at<double>(ws, pl.off_td_lam) + i0 * Np, at<int2>(ws, pl.off_td_blk) + i0 * Np,
                          at<double>(ws, pl.off_td_tnorm) + i0, tw + i0 * Np * Np, tw + ((size_t)pl.B + i0) * Np * Np,

@@ -57,7 +57,7 @@ struct Plan {
   size_t off_O, off_S, off_Spart, off_G, off_U, off_R, off_offpart, off_state, off_sig, off_C, off_E, off_order,
       off_rnorm, off_sim, off_mlist, off_info;
   size_t off_td_d, off_td_e, off_td_tau, off_td_lam, off_td_blk, off_td_tnorm, off_td_rn, off_td_bad, off_td_wgt,
-      off_td_W, off_td_tw, off_td_Cpart, off_td_Tf;  // direct eigensolver only
+      off_td_W, off_td_tw, off_td_Cpart, off_td_Tf, off_td_tab;  // direct eigensolver only
   size_t total;
 };
 
@@ -90,7 +90,7 @@ int launch_combine(const Plan& pl, const float* C_ws, const float* S, float lamb
 // direct eigensolver (tridiag.hip, tdeig.hip)
 int tridiag_panel_width(int N);
 int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, double* panels,
-                   size_t panels_stride, hipStream_t st);
+                   size_t panels_stride, int* tab, hipStream_t st);
 int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, const float* tauv, const float* Vc,
                     double* lam, int2* blk, double* tnorm, double* DP, double* DM, float* W, double* rn, int32_t* bad,
                     double* sig, double* wgt, double* Cpart, float* Tf, float sv_rtol, bool vectors, float* C, float* C_out,

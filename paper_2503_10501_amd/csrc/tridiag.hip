@@ -36,18 +36,27 @@ constexpr int TD_WAVES = TD_THREADS / 64;
 constexpr int TD_LDS_BYTES = 160 * 1024;  // LDS of one compute unit, all of it for the one workgroup
 
 constexpr int TD_RED = 2048;              // partial column sums of the matrix-vector product
+constexpr int TD_TAB = 24;                // ints per column in the table of wavefront assignments
+
+// Row sums of the matrix-vector product (the part of a row left of its diagonal block): one double per row and
+// column group, at most sum_k max(0, Nr - 128 k), k >= 1.
+__host__ __device__ inline int tridiag_rowsum_len(int Nr) {
+  int n = 0;
+  for (int k = 128; k < Nr; k += 128) n += Nr - k;
+  return n;
+}
 
 // Panel width that fits the LDS next to the current reflector and column (2 vectors of Nr doubles), the
-// partial sums, the two panels (2 nb Nr doubles) and 1 KB of small scratch.
+// partial sums of the matrix-vector product (columns and rows), the two panels (2 nb Nr doubles) and 1 KB of small scratch.
 int tridiag_panel_width(int N) {
   const int Nr = round_up(N, 16);
-  long nb = ((long)TD_LDS_BYTES - 1024 - TD_RED * 8 - 2L * Nr * 8) / (16L * Nr);
+  long nb = ((long)TD_LDS_BYTES - 1024 - TD_RED * 8 - 2L * Nr * 8 - 8L * tridiag_rowsum_len(Nr)) / (16L * Nr);
   nb &= ~3L;
   return nb > 32 ? 32 : (int)nb;
 }
 size_t tridiag_lds_bytes(int N, int nb) {
   const int Nr = round_up(N, 16);
-  return (size_t)(2 * nb + 2) * Nr * 8 + TD_RED * 8 + 1024;
+  return (size_t)(2 * nb + 2) * Nr * 8 + TD_RED * 8 + (size_t)tridiag_rowsum_len(Nr) * 8 + 1024;
 }
 
 // Sum over the workgroup in a fixed order: lanes as above, wavefronts left to right.  One barrier: the caller
@@ -61,6 +70,60 @@ __device__ inline double td_block_sum(double x, double* scratch, int wave, int l
 #pragma unroll
   for (int k = 0; k < TD_WAVES; k++) s += scratch[k];
   return s;
+}
+
+// Totals over the 64 lanes of eight values at once (recursive halving, fixed order): lane L returns the total of
+// part[L / 8].  The halves of the wavefront and the rows of 16 lanes trade registers with the swap instructions,
+// lanes L and L^8 through a rotation of the row, the last eight lanes through quad and half-row permutations.
+__device__ inline double td_sum8(const double* part, int lane) {
+  typedef __attribute__((ext_vector_type(2))) unsigned int u2;
+  double q[4], s[2];
+#pragma unroll
+  for (int u = 0; u < 4; u++) {  // lanes < 32: part[u] of L and L+32; lanes >= 32: part[u + 4]
+    const u2 lo = __builtin_amdgcn_permlane32_swap((unsigned)__double2loint(part[u]), (unsigned)__double2loint(part[u + 4]), false, false);
+    const u2 hi = __builtin_amdgcn_permlane32_swap((unsigned)__double2hiint(part[u]), (unsigned)__double2hiint(part[u + 4]), false, false);
+    q[u] = __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+  }
+#pragma unroll
+  for (int u = 0; u < 2; u++) {  // even rows of 16 lanes: q[u] of L and L+16; odd rows: q[u + 2]
+    const u2 lo = __builtin_amdgcn_permlane16_swap((unsigned)__double2loint(q[u]), (unsigned)__double2loint(q[u + 2]), false, false);
+    const u2 hi = __builtin_amdgcn_permlane16_swap((unsigned)__double2hiint(q[u]), (unsigned)__double2hiint(q[u + 2]), false, false);
+    s[u] = __hiloint2double((int)hi[0], (int)lo[0]) + __hiloint2double((int)hi[1], (int)lo[1]);
+  }
+  const bool up = (lane & 8) != 0;
+  double t = (up ? s[1] : s[0]) + dpp_f64<0x128>(up ? s[0] : s[1]);  // row_ror:8, L <-> L^8
+  t += dpp_f64<0xB1>(t);   // quad_perm [1,0,3,2]
+  t += dpp_f64<0x4E>(t);   // quad_perm [2,3,0,1]
+  t += dpp_f64<0x141>(t);  // row_half_mirror
+  return t;
+}
+
+// Which wavefront works on which part of the matrix-vector product of column j: column group g (128 columns from
+// cbase + 128 g) takes the rows from its diagonal block down, R_g of them, and the 16 wavefronts are dealt so that
+// the largest R_g / n_g is as small as it can be.  tab[j][w] = g | rg << 4 | n_g << 12 for wavefront w (row group
+// rg of n_g), tab[j][16 + g] = first wavefront of g | n_g << 8.
+__global__ __launch_bounds__(256) void tridiag_table_kernel(int N, int* __restrict__ tab) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= N - 1) return;
+  const int r0 = j + 1, cbase = r0 & ~1;
+  const int ncg = (N - cbase + 127) >> 7;
+  int R[8], n[8];
+  for (int g = 0; g < 8; g++) {
+    R[g] = g < ncg ? N - max(cbase + 128 * g, r0) : 0;
+    n[g] = g < ncg ? 1 : 0;
+  }
+  for (int k = ncg; k < TD_WAVES; k++) {
+    int best = 0;
+    for (int g = 1; g < ncg; g++)
+      if (R[g] * n[best] > R[best] * n[g]) best = g;
+    n[best]++;
+  }
+  int* row = tab + (size_t)j * TD_TAB;
+  int w = 0;
+  for (int g = 0; g < 8; g++) {
+    row[16 + g] = w | (n[g] << 8);
+    for (int rg = 0; rg < n[g]; rg++) row[w++] = g | (rg << 4) | (n[g] << 12);
+  }
 }
 
 // One task of the rank-2nb update: trailing matrix (rows and columns jend .. N-1) <- itself - Vp Wp^T - Wp Vp^T on
@@ -129,15 +192,17 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
                                                                    int j0_stop, int fused,
                                                                    double* __restrict__ dvec, double* __restrict__ evec,
                                                                    float* __restrict__ tauv, float* __restrict__ Vc,
-                                                                   double* __restrict__ panels, size_t panels_stride) {
+                                                                   double* __restrict__ panels, size_t panels_stride,
+                                                                   const int* __restrict__ tab) {
   extern __shared__ __attribute__((aligned(16))) unsigned char td_smem[];
   const int Nr = round_up(N, 16);
   double* Vp = reinterpret_cast<double*>(td_smem);  // [Nr][nb] reflectors of the panel
   double* Wp = Vp + (size_t)Nr * nb;                 // [Nr][nb] their update vectors
   double* vs = Wp + (size_t)Nr * nb;                 // [Nr] current reflector
   double* as = vs + Nr;                              // [Nr] current column
-  double* red = as + Nr;                             // [nrg][128 ncg] partial column sums of the row groups, <= 2048 in all
-  double* dots = red + TD_RED;                       // [64] W^T v and V^T v
+  double* red = as + Nr;                             // [16][128] partial column sums, one set per wavefront
+  double* yrow = red + TD_RED;                       // row sums left of the diagonal blocks, per column group
+  double* dots = yrow + tridiag_rowsum_len(Nr);      // [64] W^T v and V^T v
   double* wsum = dots + 64;                          // [2][16] wavefront partials of td_block_sum
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -152,6 +217,12 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
     const int jend = min(j0 + nb, N - 1);  // this panel reduces columns j0 .. jend-1
     for (int j = j0; j < jend; j++) {
       const int jj = j - j0;
+      // this column's table entries, asked for early: the wavefront's task and, for the thread's own element of p,
+      // the wavefronts of its column group
+      const int* trow = tab + (size_t)j * TD_TAB;
+      const int ent = trow[wave];
+      const int cbase = (j + 1) & ~1;            // column pairs start at an even column
+      const int ent_c = (j + 1 + tid < N) ? trow[16 + ((j + 1 + tid - cbase) >> 7)] : 0;
       // ---- column j of the matrix as it would be with the panel's updates applied (row j, by symmetry) ----
       const int i1 = j + tid;
       double x = 0.0;
@@ -180,33 +251,36 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
         tout[j] = (float)tau;
       }
       __syncthreads();
-      // ---- p = A v over the trailing matrix (rows and columns j+1 .. N-1), as column sums -------------------
-      // Wavefront (rg, cg): column group cg = 128 columns (a lane owns two neighbours, one 16-byte load per row),
-      // row group rg = every nrg-th row.  As the trailing matrix shrinks there are fewer column groups and more
-      // row groups; up to TD_INFLIGHT rows are in flight per wavefront.
+      // ---- p = A v over the trailing matrix (rows and columns j+1 .. N-1) -----------------------------------
+      // The matrix is symmetric and stored in full; an element below the diagonal blocks is fetched once and used
+      // twice.  Column group g = 128 columns from cbase + 128 g (a lane owns two neighbours, one 16-byte load per
+      // row).  Its rows run from the top of its diagonal block down: inside the block (128 rows, both triangles)
+      // a row only adds to the column sums p_c += A[r][c] v_r; a row r below the block also gives the part of p_r
+      // that lies in these columns, sum_c A[r][c] v_c, summed over the lanes eight rows at a time.  The rows of a
+      // group are dealt to its wavefronts in turn (table: more wavefronts for the groups with more rows).
       const int r0 = j + 1;
-      const int cbase = r0 & ~1;                 // column pairs start at an even column
-      const int ncols = N - cbase;
-      const int ncg = (ncols + 127) >> 7;        // <= 8 for N <= 1024
-      const int nrg = TD_WAVES / ncg;            // >= 2
-      const int pitch = ncg << 7;                // nrg * pitch <= 2048 partial sums
-      if (wave < ncg * nrg) {
-        const int cg = wave % ncg, rg = wave / ncg;
-        const int c = cbase + (cg << 7) + 2 * lane;
+      {
+        const int cg = ent & 15, rg = (ent >> 4) & 255, nrg = ent >> 12;
+        const int C0 = cbase + (cg << 7);
+        const int c = C0 + 2 * lane;
         const bool ok = c < N;                   // (an odd N reads the zero padding column N as the pair's second half)
         const double* col = A + (ok ? c : cbase);
+        const double vc0 = (ok && c >= r0) ? vs[c] : 0.0, vc1 = (c + 1 < N) ? vs[c + 1] : 0.0;
+        const int dend = min(C0 + 128, N);       // rows below dend lie under the diagonal block
+        int yoff = 0;                            // where this group's row sums start
+        for (int g = 0; g < cg; g++) yoff += N - (cbase + 128 * g + 128);
         d2 acc = d2{0.0, 0.0};
         // whole chunks of TD_INFLIGHT rows with all their loads in flight together, then chunks of 4, then single rows:
-        // no row is fetched that does not count (a chunk padded with repeated rows cost up to a tenth of the kernel)
-        int ib = r0 + rg;
-        for (; ib + (TD_INFLIGHT - 1) * nrg < N; ib += TD_INFLIGHT * nrg) {
+        // no row is fetched that does not count
+        int ib = max(C0, r0) + rg;
+        for (; ib + (TD_INFLIGHT - 1) * nrg < dend; ib += TD_INFLIGHT * nrg) {
           d2 x[TD_INFLIGHT];
 #pragma unroll
           for (int u = 0; u < TD_INFLIGHT; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
 #pragma unroll
           for (int u = 0; u < TD_INFLIGHT; u++) acc += x[u] * vs[ib + u * nrg];
         }
-        for (; ib + 3 * nrg < N; ib += 4 * nrg) {
+        for (; ib + 3 * nrg < dend; ib += 4 * nrg) {
           d2 x[4];
 #pragma unroll
           for (int u = 0; u < 4; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
@@ -215,17 +289,56 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
         }
         {
           d2 x[3];
+          int cnt = 0;
 #pragma unroll
           for (int u = 0; u < 3; u++)
-            if (ib + u * nrg < N) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);  // uniform over the wavefront
+            if (ib + u * nrg < dend) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);  // uniform over the wavefront
 #pragma unroll
           for (int u = 0; u < 3; u++)
-            if (ib + u * nrg < N) acc += x[u] * vs[ib + u * nrg];
+            if (ib + u * nrg < dend) {
+              acc += x[u] * vs[ib + u * nrg];
+              cnt++;
+            }
+          ib += cnt * nrg;
         }
-        if (ok) {
-          red[rg * pitch + (c - cbase)] = acc.x;
-          red[rg * pitch + (c - cbase) + 1] = acc.y;
+        // rows under the diagonal block, eight at a time
+        double* yg = yrow + yoff - (C0 + 128);
+        for (; ib + 7 * nrg < N; ib += 8 * nrg) {
+          d2 x[8];
+          double part[8];
+#pragma unroll
+          for (int u = 0; u < 8; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
+#pragma unroll
+          for (int u = 0; u < 8; u++) {
+            acc += x[u] * vs[ib + u * nrg];
+            part[u] = x[u].x * vc0 + x[u].y * vc1;
+          }
+          const double tot = td_sum8(part, lane);
+          if ((lane & 7) == 0) yg[ib + (lane >> 3) * nrg] = tot;
         }
+        if (ib < N) {  // a last chunk of fewer than eight rows, fetched four at a time
+          double part[8];
+#pragma unroll
+          for (int h = 0; h < 2; h++) {
+            d2 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+              if (ib + (4 * h + u) * nrg < N) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + (4 * h + u) * nrg) * Np);  // uniform over the wavefront
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+              part[4 * h + u] = 0.0;
+              if (ib + (4 * h + u) * nrg < N) {
+                acc += x[u] * vs[ib + (4 * h + u) * nrg];
+                part[4 * h + u] = x[u].x * vc0 + x[u].y * vc1;
+              }
+            }
+          }
+          const double tot = td_sum8(part, lane);
+          const int r = ib + (lane >> 3) * nrg;
+          if ((lane & 7) == 0 && r < N) yg[r] = tot;
+        }
+        red[(wave << 7) + 2 * lane] = acc.x;
+        red[(wave << 7) + 2 * lane + 1] = acc.y;
       }
       // ---- W^T v and V^T v for the panel's earlier columns: one wavefront per dot product ------------------
       for (int id = wave; id < 2 * jj; id += TD_WAVES) {
@@ -240,7 +353,15 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
       const int c = r0 + tid;
       double pc = 0.0, vc = 0.0;
       if (c < N) {
-        for (int g = 0; g < nrg; g++) pc += red[g * pitch + (c - cbase)];  // fixed order
+        const int cgc = (c - cbase) >> 7;
+        const int w0 = ent_c & 255, w1 = w0 + (ent_c >> 8), cl = c - cbase - (cgc << 7);
+        for (int w = w0; w < w1; w++) pc += red[(w << 7) + cl];  // fixed order: the wavefronts of the column's group,
+        int yoff = 0;                                            // then the row sums of the groups to its left
+        for (int g = 0; g < cgc; g++) {
+          const int top = cbase + 128 * g + 128;
+          pc += yrow[yoff + (c - top)];
+          yoff += N - top;
+        }
         for (int k = 0; k < jj; k++) pc -= Vp[c * nb + k] * dots[k] + Wp[c * nb + k] * dots[jj + k];
         pc *= tau;
         vc = vs[c];
@@ -329,7 +450,7 @@ __global__ __launch_bounds__(64) void tridiag_last_kernel(const double* __restri
 }
 
 int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float* tauv, float* Vc, double* panels,
-                   size_t panels_stride, hipStream_t st) {
+                   size_t panels_stride, int* tab, hipStream_t st) {
   const int N = pl.N, nb = tridiag_panel_width(N);
   if (nb < 4) return TC_ERR_SHAPE;
   if ((size_t)2 * round_up(N, 16) * nb > panels_stride) return TC_ERR_WORKSPACE;
@@ -339,14 +460,15 @@ int launch_tridiag(const Plan& pl, double* G, double* dvec, double* evec, float*
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(tridiag_panel_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           TD_LDS_BYTES) != hipSuccess)
     return TC_ERR_HIP;
+  TC_TIMED(PK_TRIDIAG_UPDATE, 2, st, (tridiag_table_kernel<<<(N + 255) / 256, 256, 0, st>>>(N, tab)));
   if (pl.batch_call >= 96) {  // the chip is full of images: the whole reduction in one launch, updates on the image's own compute unit
-    TC_TIMED(PK_TRIDIAG, 0, st, (tridiag_panel_kernel<<<pl.B, TD_THREADS, lds, st>>>(G, N, pl.Np, nb, 0, N - 1, 1, dvec, evec, tauv, Vc, panels, panels_stride)));
+    TC_TIMED(PK_TRIDIAG, 0, st, (tridiag_panel_kernel<<<pl.B, TD_THREADS, lds, st>>>(G, N, pl.Np, nb, 0, N - 1, 1, dvec, evec, tauv, Vc, panels, panels_stride, tab)));
     return check_launch();
   }
   for (int j0 = 0; j0 < N - 1; j0 += nb) {
     const int jend = j0 + nb < N - 1 ? j0 + nb : N - 1;
     const int kcols = round_up(jend - j0, 4);
-    TC_TIMED(PK_TRIDIAG, 0, st, (tridiag_panel_kernel<<<pl.B, TD_THREADS, lds, st>>>(G, N, pl.Np, nb, j0, j0 + 1, 0, dvec, evec, tauv, Vc, panels, panels_stride)));
+    TC_TIMED(PK_TRIDIAG, 0, st, (tridiag_panel_kernel<<<pl.B, TD_THREADS, lds, st>>>(G, N, pl.Np, nb, j0, j0 + 1, 0, dvec, evec, tauv, Vc, panels, panels_stride, tab)));
     const int base = jend & ~15;
     const int nrt = (N - base + 15) >> 4, ncc = (N - base + 63) >> 6;
     int ntasks = 0;
