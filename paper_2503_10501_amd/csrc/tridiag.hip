@@ -270,53 +270,27 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
         int yoff = 0;                            // where this group's row sums start
         for (int g = 0; g < cg; g++) yoff += N - (cbase + 128 * g + 128);
         d2 acc = d2{0.0, 0.0};
-        // whole chunks of TD_INFLIGHT rows with all their loads in flight together, then chunks of 4, then single rows:
-        // no row is fetched that does not count
-        int ib = max(C0, r0) + rg;
-        for (; ib + (TD_INFLIGHT - 1) * nrg < dend; ib += TD_INFLIGHT * nrg) {
-          d2 x[TD_INFLIGHT];
-#pragma unroll
-          for (int u = 0; u < TD_INFLIGHT; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
-#pragma unroll
-          for (int u = 0; u < TD_INFLIGHT; u++) acc += x[u] * vs[ib + u * nrg];
-        }
-        for (; ib + 3 * nrg < dend; ib += 4 * nrg) {
-          d2 x[4];
-#pragma unroll
-          for (int u = 0; u < 4; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
-#pragma unroll
-          for (int u = 0; u < 4; u++) acc += x[u] * vs[ib + u * nrg];
-        }
-        {
-          d2 x[3];
-          int cnt = 0;
-#pragma unroll
-          for (int u = 0; u < 3; u++)
-            if (ib + u * nrg < dend) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);  // uniform over the wavefront
-#pragma unroll
-          for (int u = 0; u < 3; u++)
-            if (ib + u * nrg < dend) {
-              acc += x[u] * vs[ib + u * nrg];
-              cnt++;
-            }
-          ib += cnt * nrg;
-        }
-        // rows under the diagonal block, eight at a time
+        // Chunks of eight rows with all their loads in flight together, then a last chunk of fewer rows fetched four
+        // at a time: no row is fetched that does not count.  A chunk that reaches below the diagonal block also
+        // forms the row sums of its rows there.
         double* yg = yrow + yoff - (C0 + 128);
+        int ib = max(C0, r0) + rg;
         for (; ib + 7 * nrg < N; ib += 8 * nrg) {
           d2 x[8];
-          double part[8];
 #pragma unroll
           for (int u = 0; u < 8; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
 #pragma unroll
-          for (int u = 0; u < 8; u++) {
-            acc += x[u] * vs[ib + u * nrg];
-            part[u] = x[u].x * vc0 + x[u].y * vc1;
+          for (int u = 0; u < 8; u++) acc += x[u] * vs[ib + u * nrg];
+          if (ib + 7 * nrg >= dend) {  // uniform over the wavefront
+            double part[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) part[u] = ib + u * nrg >= dend ? x[u].x * vc0 + x[u].y * vc1 : 0.0;
+            const double tot = td_sum8(part, lane);
+            const int r = ib + (lane >> 3) * nrg;
+            if ((lane & 7) == 0 && r >= dend) yg[r] = tot;
           }
-          const double tot = td_sum8(part, lane);
-          if ((lane & 7) == 0) yg[ib + (lane >> 3) * nrg] = tot;
         }
-        if (ib < N) {  // a last chunk of fewer than eight rows, fetched four at a time
+        if (ib < N) {
           double part[8];
 #pragma unroll
           for (int h = 0; h < 2; h++) {
@@ -326,16 +300,17 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
               if (ib + (4 * h + u) * nrg < N) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + (4 * h + u) * nrg) * Np);  // uniform over the wavefront
 #pragma unroll
             for (int u = 0; u < 4; u++) {
+              const int r = ib + (4 * h + u) * nrg;
               part[4 * h + u] = 0.0;
-              if (ib + (4 * h + u) * nrg < N) {
-                acc += x[u] * vs[ib + (4 * h + u) * nrg];
-                part[4 * h + u] = x[u].x * vc0 + x[u].y * vc1;
+              if (r < N) {
+                acc += x[u] * vs[r];
+                if (r >= dend) part[4 * h + u] = x[u].x * vc0 + x[u].y * vc1;
               }
             }
           }
           const double tot = td_sum8(part, lane);
           const int r = ib + (lane >> 3) * nrg;
-          if ((lane & 7) == 0 && r < N) yg[r] = tot;
+          if ((lane & 7) == 0 && r >= dend && r < N) yg[r] = tot;
         }
         red[(wave << 7) + 2 * lane] = acc.x;
         red[(wave << 7) + 2 * lane + 1] = acc.y;
