@@ -24,9 +24,11 @@ PEAK = {"hbm_gbps": 8000.0, "mfma_bf16": 2500.0, "mfma_f64": 78.6, "mfma_f32": 1
 # ---- algorithmic work per batch (what the method must move or compute; derivations in the design doc) -------------
 def panel_ends(n_vis):
     """Last column + 1 of every panel of the reduction to tridiagonal form: the panel width is what fits the 160 KB of
-    LDS of a compute unit next to two vectors and 16 KB of partial sums (the library's sizing rule, csrc/tridiag.hip)."""
+    LDS of a compute unit next to two vectors and the partial sums of the matrix-vector product (the library's sizing
+    rule, csrc/tridiag.hip)."""
     nr = (n_vis + 15) // 16 * 16
-    nb = min(32, ((160 * 1024 - 1024 - 2048 * 8 - 2 * nr * 8) // (16 * nr)) & ~3)
+    row_sums = sum(nr - k for k in range(128, nr, 128))   # row sums of the matrix-vector product, one double each
+    nb = min(32, ((160 * 1024 - 1024 - 2048 * 8 - 2 * nr * 8 - 8 * row_sums) // (16 * nr)) & ~3)
     return [min(j0 + nb, n_vis - 1) for j0 in range(0, n_vis - 1, max(nb, 1))]
 
 

@@ -5,9 +5,9 @@
 //
 // The columns of an image are reduced by one workgroup of 16 wavefronts.  The reduction is bound by
 // memory: column j needs the product of the trailing (N-j-1)^2 matrix with v_j.  Measured on MI355X a
-// single workgroup streams 150 GB/s out of its L2 and 64 of them together 6 TB/s, which is what the
-// fabric delivers to any number of compute units for a working set of this size, so one compute unit per
-// image is enough for the products at batch 64.
+// single workgroup streams 110 to 150 GB/s out of its L2 and 64 of them together 5 to 6 TB/s, which is what
+// the fabric delivers to any number of compute units for a working set of this size, so one compute unit
+// per image is enough for the products at batch 64.
 //
 // The trailing matrix is only rewritten once per panel of nb columns (the scheme of LAPACK's
 // dlatrd/dsytrd): inside a panel the reflectors v and the vectors w of the rank-2 updates
@@ -15,12 +15,18 @@
 // reduced and to the matrix-vector product (tridiag_panel_kernel, one launch per panel).  The panels then
 // go to global memory and the trailing matrix gets the rank-2nb update on the matrix cores from a launch
 // of its own that spreads over the whole chip (tridiag_update_kernel: computed for the lower triangle,
-// stored to both, since the matrix-vector product reads whole rows): inside the panel kernel the update
-// ran on one compute unit per image, 2 of its 10.7 ms per batch of 64 and of its 9.3 ms for one image.
-// G is symmetric and stored in full, so the product p = A v is formed as column sums over rows,
-// p_c = sum_i A[i][c] v_i: a lane owns two neighbouring columns, loads are 16 bytes wide and contiguous
-// across the wavefront, and no cross-lane reduction is needed; 4 row groups x 4 column groups of
-// wavefronts leave four partial sums per column, added in a fixed order (results are bit-reproducible).
+// stored to both): inside the panel kernel the update ran on one compute unit per image, 2 of its 10.7 ms
+// per batch of 64 and of its 9.3 ms for one image.
+//
+// G is symmetric and stored in full.  The product p = A v reads 128-column groups of rows (a lane owns two
+// neighbouring columns, loads are 16 bytes wide and contiguous across the wavefront).  Inside the diagonal
+// block of a column group both triangles are read and a row only adds to the column sums
+// p_c += A[r][c] v_r, which need no exchange between lanes; a row below the block is fetched once and used
+// twice, for the column sums and for its own row sum sum_c A[r][c] v_c over the group's columns (the mirror
+// image above the diagonal is never read), added up over the lanes eight rows at a time.  That is 0.58 of
+// the elements of the full trailing matrices at 576 tokens.  The 16 wavefronts are dealt to the column
+// groups in proportion to their rows (tridiag_table_kernel); every partial sum has one writer and the sums
+// are added in a fixed order (results are bit-reproducible).
 #include "tc_internal.h"
 
 namespace tc {
