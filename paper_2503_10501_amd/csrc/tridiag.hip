@@ -136,8 +136,9 @@ __global__ __launch_bounds__(256) void tridiag_table_kernel(int N, int* __restri
 // the matrix cores, for the strip of 16 rows x 64 columns (a, bch) counted from base = jend rounded down to 16;
 // product ks contracts over k = 4 ks + lane / 16 of the 2 kcols columns of [Vp | Wp] (rows) against [Wp | Vp]
 // (columns).  Only strips that reach the diagonal or lie below it are computed (64 bch <= 16 a + 15); a strip
-// strictly below the diagonal also writes its mirror image, which is a strip that is skipped.  Vp, Wp: [Nr][nb]
-// in LDS or in global memory.
+// strictly below the diagonal also writes its mirror image (in a strip that is skipped) where somebody reads it:
+// within 128 columns of the diagonal (the diagonal blocks of the matrix-vector product) and in the rows of the next
+// panel (a column is formed from its row).  Vp, Wp: [Nr][nb] in LDS or in global memory.
 __device__ inline void td_update_strip(double* __restrict__ A, int N, int Np, int Nr, int nb, int jend, int kcols,
                                        const double* Vp, const double* Wp, int a, int bch, int lane) {
   const int l15 = lane & 15, q4 = lane >> 4;
@@ -177,7 +178,7 @@ __device__ inline void td_update_strip(double* __restrict__ A, int N, int Np, in
       const int rr = rt + 4 * e + q4;
       if (rr >= jend && cc >= jend && rr < N && cc < N) {
         A[(size_t)rr * Np + cc] = acc[t][e];
-        if (below) A[(size_t)cc * Np + rr] = acc[t][e];
+        if (below && (rr - cc < 128 || cc < jend + nb)) A[(size_t)cc * Np + rr] = acc[t][e];
       }
     }
   }
