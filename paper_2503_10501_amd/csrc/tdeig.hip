@@ -68,12 +68,16 @@ __global__ __launch_bounds__(256) void td_prepare_kernel(const double* __restric
   if (tid == 0) { tnorm[b] = tn; bad[b] = 0; }
 }
 
-// One lane per eigenvalue; blockIdx.y = image.  The usual case, T not split anywhere (or every lane of the
+// G = 1 << gs lanes per eigenvalue; blockIdx.y = image.  A step evaluates the number of eigenvalues below G
+// points that cut the interval into G + 1 equal parts, one point per lane, and keeps the part that holds the
+// eigenvalue: log2(G + 1) bits per walk over the rows instead of one (the walk is a chain of dependent
+// operations that a wavefront alone on its SIMD cannot hide; with few images the chip has lanes to spare).
+// The usual case, T not split anywhere (or every lane of the
 // wavefront in the same block), reads the rows through the scalar unit: the coefficients are the same for all
 // lanes, and fetched per lane from LDS the sixteen bytes per row and lane made the LDS the limit of the kernel.
 __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict__ prep, size_t prep_stride,
                                                         const double* __restrict__ tnorm, double* __restrict__ lam,
-                                                        int2* __restrict__ blk, int N, int Np) {
+                                                        int2* __restrict__ blk, int N, int Np, int gs) {
   extern __shared__ __attribute__((aligned(16))) unsigned char tb_smem[];
   double* ds = reinterpret_cast<double*>(tb_smem);  // [N], scaled
   double* es = ds + N;                               // [N]: es[i] = |coupling of rows i-1 and i|, es[0] = 0, scaled
@@ -96,8 +100,11 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
   if (tn > 0.0 && tn < DBL_MAX) (void)frexp(tn, &ex);
   const double up = ldexp(1.0, ex);
   __syncthreads();
-  const int k = blockIdx.x * 256 + tid;
-  if (k >= N) return;
+  const int G = 1 << gs, sec = tid & (G - 1);  // this lane's point: the (sec + 1)-th of G
+  const int k = (blockIdx.x * 256 + tid) >> gs;
+  if (k >= N) return;                          // (whole groups of G lanes leave together)
+  const double inv = 1.0 / (double)(G + 1);
+  const int gshift = (tid & 63) & ~(G - 1);    // first lane of the group within the wavefront
   int s = k, t = k + 1;
   while (s > 0 && e2[s] != 0.0) s--;
   while (t < N && e2[t] != 0.0) t++;
@@ -120,7 +127,9 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
     const double mid = 0.5 * (lo + hi);
     if (!(mid > lo && mid < hi)) break;     // the interval cannot be halved any more
     if (hi - lo <= 0.25 * TD_EPS) break;    // the entries of T carry errors of eps ||T|| themselves; same count for every lane
-    double pp = 1.0, p = d_s - mid;         // p_{i-2}, p_{i-1}
+    const double width = hi - lo;
+    const double x = gs ? lo + width * ((double)(sec + 1) * inv) : mid;  // the lane's point
+    double pp = 1.0, p = d_s - x;           // p_{i-2}, p_{i-1}
     // Sign changes are counted on the sign bits.  The signs of the minors are shifted into one register, a bit
     // per row (bit 0 = the newest); after eight rows the changes among them and against the minor before them
     // are the set bits of (signs xor signs >> 1) in its low byte.  An exact zero needs no special case: its
@@ -144,7 +153,7 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
   {                                                                                            \
     _Pragma("unroll") for (int u = 0; u < 8; u++) NXT[u] = pr[i0 + 8 + u];                     \
     _Pragma("unroll") for (int u = 0; u < 8; u++) {                                            \
-      const double pn = fma(CUR[u].x - mid, p, -(CUR[u].y * pp));                              \
+      const double pn = fma(CUR[u].x - x, p, -(CUR[u].y * pp));                              \
       signs = __builtin_amdgcn_alignbit(signs, (unsigned)__double2hiint(pn), 31);              \
       pp = p;                                                                                  \
       p = pn;                                                                                  \
@@ -170,7 +179,7 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
 #pragma unroll
       for (int u = 0; u < 8; u++) {
         if (i0 + u < t0) {
-          const double pn = fma(ca[u].x - mid, p, -(ca[u].y * pp));
+          const double pn = fma(ca[u].x - x, p, -(ca[u].y * pp));
           cnt += (int)((unsigned)(__double2hiint(pn) ^ __double2hiint(p)) >> 31);
           pp = p;
           p = pn;
@@ -191,7 +200,7 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
                       "+v"(CUR[4].y), "+v"(CUR[5].y), "+v"(CUR[6].y), "+v"(CUR[7].y));                                    \
     if (i0 + 8 <= t) { /* a whole chunk: no selects */                                                                    \
       _Pragma("unroll") for (int u = 0; u < 8; u++) {                                                                     \
-        const double pn = fma(CUR[u].x - mid, p, -(CUR[u].y * pp));                                                       \
+        const double pn = fma(CUR[u].x - x, p, -(CUR[u].y * pp));                                                       \
         signs = __builtin_amdgcn_alignbit(signs, (unsigned)__double2hiint(pn), 31);                                       \
         pp = p;                                                                                                           \
         p = pn;                                                                                                           \
@@ -199,7 +208,7 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
     } else {                                                                                                              \
       _Pragma("unroll") for (int u = 0; u < 8; u++) {                                                                     \
         const bool in = i0 + u < t;                                                                                       \
-        const double pn = fma(in ? CUR[u].x - mid : 1.0, p, -((in ? CUR[u].y : 0.0) * pp));                               \
+        const double pn = fma(in ? CUR[u].x - x : 1.0, p, -((in ? CUR[u].y : 0.0) * pp));                               \
         signs = __builtin_amdgcn_alignbit(signs, (unsigned)__double2hiint(pn), 31);                                       \
         pp = p;                                                                                                           \
         p = pn;                                                                                                           \
@@ -219,10 +228,23 @@ __global__ __launch_bounds__(256) void td_bisect_kernel(const double* __restrict
     }
 #undef TB_CHUNK
     }
-    if (cnt > m) hi = mid; else lo = mid;
+    if (gs == 0) {
+      if (cnt > m) hi = mid; else lo = mid;
+    } else {
+      // points with at most m eigenvalues below them lie left of the eigenvalue: their number (the counts rise
+      // with the point) picks the part; the new ends are points that lanes of the group evaluated, bit for bit
+      const unsigned long long left = __ballot(cnt <= m);
+      const int ms = __popcll((left >> gshift) & ((1ull << G) - 1ull));
+      const double nlo = ms == 0 ? lo : lo + width * ((double)ms * inv);
+      const double nhi = ms == G ? hi : lo + width * ((double)(ms + 1) * inv);
+      lo = nlo;
+      hi = nhi;
+    }
   }
-  lam[(size_t)b * Np + k] = 0.5 * (lo + hi) * up;
-  blk[(size_t)b * Np + k] = int2{s, t};
+  if (sec == 0) {
+    lam[(size_t)b * Np + k] = 0.5 * (lo + hi) * up;
+    blk[(size_t)b * Np + k] = int2{s, t};
+  }
 }
 
 // ---- 2b -----------------------------------------------------------------------------------------------
@@ -725,7 +747,10 @@ int launch_td_eigen(const Plan& pl, const double* dvec, const double* evec, cons
   // (the scaled copy of T lives at the start of each image's region of DP until the factorisations overwrite it)
   const size_t prep_stride = (size_t)Np * Np;
   TC_TIMED(PK_BISECT, 0, st, (td_prepare_kernel<<<B, 256, 0, st>>>(dvec, evec, DP, prep_stride, tnorm, bad, N, Np)));
-  TC_TIMED(PK_BISECT, 0, st, (td_bisect_kernel<<<dim3((N + 255) / 256, B), 256, (size_t)5 * N * 8 + 256, st>>>(DP, prep_stride, tnorm, lam, blk, N, Np)));
+  // lanes per eigenvalue: as many as keep the launch near one wavefront per SIMD (by the size of the whole call, so
+  // that an image's result does not depend on how the call is cut into stream groups)
+  const int gs = pl.batch_call <= 16 ? 3 : pl.batch_call <= 32 ? 2 : pl.batch_call <= 128 ? 1 : 0;
+  TC_TIMED(PK_BISECT, 0, st, (td_bisect_kernel<<<dim3(((N << gs) + 255) / 256, B), 256, (size_t)5 * N * 8 + 256, st>>>(DP, prep_stride, tnorm, lam, blk, N, Np, gs)));
   int n2 = 1;
   while (n2 < N) n2 <<= 1;
   const size_t shm_sig = sigma_out ? (size_t)n2 * sizeof(float) : 0;
