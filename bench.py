@@ -21,7 +21,7 @@ sys.path.insert(0, ROOT)
 PEAK = {"hbm_gbps": 8000.0, "mfma_bf16": 2500.0, "mfma_f64": 78.6, "mfma_f32": 157.3, "vec_f64": 78.6, "vec_f32": 157.3}
 
 
-# ---- algorithmic work per batch (what the method must move or compute; derivations in the design doc) -------------
+# ---- algorithmic work per batch (what the method must move or compute) ---------------------------------------
 def panel_ends(n_vis):
     """Last column + 1 of every panel of the reduction to tridiagonal form: the panel width is what fits the 160 KB of
     LDS of a compute unit next to two vectors and the partial sums of the matrix-vector product (the library's sizing
