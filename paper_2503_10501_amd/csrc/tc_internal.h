@@ -206,8 +206,10 @@ __device__ inline T wave_sum(T v) {
 // returns the same bits.
 template <int CTRL>
 __device__ inline double dpp_f64(double x) {
-  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xF, 0xF, false);
-  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xF, 0xF, false);
+  // (every lane is written -- all rows and banks enabled, and the controls used read lanes inside the wavefront --,
+  // so the form without a previous value will do: no register has to be cleared first)
+  const int lo = __builtin_amdgcn_mov_dpp(__double2loint(x), CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_mov_dpp(__double2hiint(x), CTRL, 0xF, 0xF, false);
   return __hiloint2double(hi, lo);
 }
 __device__ inline double readlane_f64(double x, int l) {

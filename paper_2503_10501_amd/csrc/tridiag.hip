@@ -288,7 +288,13 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
           for (int u = 0; u < 8; u++) x[u] = *reinterpret_cast<const d2*>(col + (size_t)(ib + u * nrg) * Np);
 #pragma unroll
           for (int u = 0; u < 8; u++) acc += x[u] * vs[ib + u * nrg];
-          if (ib + 7 * nrg >= dend) {  // uniform over the wavefront
+          if (ib >= dend) {  // all eight rows below the block (uniform over the wavefront)
+            double part[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) part[u] = x[u].x * vc0 + x[u].y * vc1;
+            const double tot = td_sum8(part, lane);
+            if ((lane & 7) == 0) yg[ib + (lane >> 3) * nrg] = tot;
+          } else if (ib + 7 * nrg >= dend) {  // some of them
             double part[8];
 #pragma unroll
             for (int u = 0; u < 8; u++) part[u] = ib + u * nrg >= dend ? x[u].x * vc0 + x[u].y * vc1 : 0.0;
