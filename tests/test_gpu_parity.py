@@ -225,6 +225,18 @@ def test_tridiagonal_route_up_to_its_largest_token_count(n_vis, heads):
     assert max(rep["C_rel"]) < 1e-4
 
 
+@pytest.mark.parametrize("n_vis", [127, 128, 129, 130, 191, 255, 257, 385])
+def test_tridiagonal_route_around_the_column_group_boundaries(n_vis):
+    # the matrix-vector product of the reduction works on groups of 128 columns with a diagonal block each: token
+    # counts just below, at and just above multiples of 128 (and of 64), odd and even, batch 3 (eight lanes per
+    # eigenvalue in the bisection)
+    tc, gu, parity, _, Workload = _mods()
+    w = Workload("groups_%d" % n_vis, 23, 3, n_vis, 5, 3, 4, 64, "bf16", n_vis // 4, n_vis // 8, 8, "powerlaw", 0.05, "proj")
+    rep = parity.run_all_stages(w, eig_method=METHODS["tridiagonal"])
+    print("groups", n_vis, rep)
+    assert max(rep["C_rel"]) < 1e-4
+
+
 @pytest.mark.parametrize("first", [0, 64])
 def test_llava13b_batch128_every_image(first, capsys):
     # the batch of 128 runs on the GPU as a whole both times; the oracle takes one half per test
