@@ -237,6 +237,28 @@ def test_tridiagonal_route_around_the_column_group_boundaries(n_vis):
     assert max(rep["C_rel"]) < 1e-4
 
 
+def test_bisection_gives_the_same_singular_values_with_one_to_eight_lanes_per_eigenvalue():
+    # the number of lanes that share an eigenvalue in the bisection follows the size of the call (8 up to 16 images,
+    # 4 up to 32, 2 up to 128, 1 above): the same images in calls of 1, 20, 40 and 130 images must give the same
+    # singular values (to the resolution of the bisection) and contribution scores
+    tc, gu, parity, _, Workload = _mods()
+    from workloads import make_batch
+    w = Workload("lanes", 29, 130, 96, 5, 3, 2, 64, "bf16", 24, 12, 8, "powerlaw", 0.05, "proj")
+    b = make_batch(w)
+    O, S = gu.attn_output(tc.params_for(w), b["Q"], b["K"], b["V"])
+    ref = None
+    for nb in (130, 40, 20, 1):
+        p = tc.params_for(w, batch=nb, eig_method=METHODS["tridiagonal"])
+        E, C, sig, info = gu.ipgs_score(p, O[:nb].contiguous(), S[:nb].contiguous())
+        assert int(info.min()) > 0
+        if ref is None:
+            ref = (C.double(), sig.double())
+            continue
+        smax = ref[1][:nb].max(dim=1, keepdim=True).values
+        assert float(((sig.double() - ref[1][:nb]).abs() / smax).max()) < 1e-6   # float32 output
+        assert float(((C.double() - ref[0][:nb]).abs() / ref[0][:nb].abs().max(dim=1, keepdim=True).values).max()) < 1e-5
+
+
 @pytest.mark.parametrize("first", [0, 64])
 def test_llava13b_batch128_every_image(first, capsys):
     # the batch of 128 runs on the GPU as a whole both times; the oracle takes one half per test
