@@ -34,9 +34,6 @@ namespace tc {
 typedef __attribute__((ext_vector_type(2))) double d2;
 typedef __attribute__((ext_vector_type(4))) double d4;
 
-#ifndef TD_INFLIGHT
-#define TD_INFLIGHT 12
-#endif
 constexpr int TD_THREADS = 1024;
 constexpr int TD_WAVES = TD_THREADS / 64;
 constexpr int TD_LDS_BYTES = 160 * 1024;  // LDS of one compute unit, all of it for the one workgroup
