@@ -442,15 +442,24 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t* __res
   }
 }
 
-// S[b][x] = (1 / (H Nq)) sum_h sum_tiles partial column sums, in a fixed order.
+// S[b][x] = (1 / (H Nq)) sum_h sum_tiles partial column sums, in a fixed order: four threads per token take a
+// quarter of the partial rows each (the loads of one thread depend on nothing but are issued one after the other),
+// their float64 sums are added in order.
 __global__ __launch_bounds__(256) void attn_score_reduce(const float* __restrict__ Spart, float* __restrict__ S, int N,
                                                          int Nq, int H, int n_qtiles, size_t stride) {
-  const int b = blockIdx.y, x = blockIdx.x * 256 + threadIdx.x;
-  if (x >= N) return;
-  const float* sp = Spart + (size_t)b * stride + x;
+  __shared__ double part[4][64];
+  const int b = blockIdx.y, xl = threadIdx.x & 63, q = threadIdx.x >> 6, x = blockIdx.x * 64 + xl;
+  const int rows = H * n_qtiles, per = (rows + 3) / 4;
   double acc = 0.0;
-  for (int i = 0; i < H * n_qtiles; i++) acc += (double)sp[(size_t)i * N];
-  S[(size_t)b * N + x] = (float)(acc / ((double)H * (double)Nq));
+  if (x < N) {
+    const float* sp = Spart + (size_t)b * stride + x;
+    const int i1 = min(rows, (q + 1) * per);
+    for (int i = q * per; i < i1; i++) acc += (double)sp[(size_t)i * N];
+  }
+  part[q][xl] = acc;
+  __syncthreads();
+  if (q == 0 && x < N)
+    S[(size_t)b * N + x] = (float)(((part[0][xl] + part[1][xl]) + (part[2][xl] + part[3][xl])) / ((double)H * (double)Nq));
 }
 
 // ---------------- float32 storage: plain-ALU correctness path ----------------
@@ -556,7 +565,7 @@ int launch_attention(const Plan& pl, int dtype, int causal, const void* Q, const
       if (dtype == TC_F16) TC_ATTN16(64, true); else TC_ATTN16(64, false);
     }
 #undef TC_ATTN16
-    if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_score_reduce<<<dim3((pl.N + 255) / 256, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.Nq, pl.H, pl.n_qtiles, pl.spart_stride)));
+    if (S) TC_TIMED(PK_ATTN_REDUCE, 0, st, (attn_score_reduce<<<dim3((pl.N + 63) / 64, pl.B), 256, 0, st>>>(Spart, S, pl.N, pl.Nq, pl.H, pl.n_qtiles, pl.spart_stride)));
   } else {
     const dim3 grid(pl.Nq, pl.H, pl.B);
     if (pl.dh == 128) {
