@@ -358,11 +358,19 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
     // ---- end of the panel ----------------------------------------------------------------------------------
     const int cnt = jend - j0;          // columns reduced in this panel
     const int kcols = round_up(cnt, 4); // contraction length per factor, padded with zero columns
-    // the reflectors leave as float rows (stage 3 applies them in float32)
-    for (int jj = 0; jj < cnt; jj++) {
-      const int j = j0 + jj;
-      for (int i = tid; i < N; i += TD_THREADS)
-        Vout[((size_t)(j >> 4) * Np + i) * 16 + (j & 15)] = i > j ? (float)Vp[i * nb + jj] : 0.f;
+    // the reflectors leave as float rows (stage 3 applies them in float32), four columns per 16-byte store: j0 is a
+    // multiple of 4, so the four lie in one block of sixteen; slots of a last group past column jend - 1 get zeros
+    // (stage 3 does not use them)
+    for (int g4 = 0; g4 < kcols; g4 += 4) {
+      const int j = j0 + g4;
+      for (int i = tid; i < N; i += TD_THREADS) {
+        float4 v;
+        v.x = (g4 < cnt && i > j) ? (float)Vp[i * nb + g4] : 0.f;
+        v.y = (g4 + 1 < cnt && i > j + 1) ? (float)Vp[i * nb + g4 + 1] : 0.f;
+        v.z = (g4 + 2 < cnt && i > j + 2) ? (float)Vp[i * nb + g4 + 2] : 0.f;
+        v.w = (g4 + 3 < cnt && i > j + 3) ? (float)Vp[i * nb + g4 + 3] : 0.f;
+        *reinterpret_cast<float4*>(&Vout[((size_t)(j >> 4) * Np + i) * 16 + (j & 15)]) = v;
+      }
     }
     if (kcols > cnt) {  // a last, shorter panel: columns cnt .. kcols-1 still hold the previous panel
       for (int e = tid; e < Nr * (kcols - cnt); e += TD_THREADS) {
