@@ -394,11 +394,12 @@ __global__ __launch_bounds__(TD_THREADS) void tridiag_panel_kernel(double* __res
       // the panels for the update of the trailing matrix (rows that the update does not store are written as zero)
       double* Vg = panels + (size_t)b * panels_stride;
       double* Wg = Vg + (size_t)Nr * nb;
-      for (int e = tid; e < Nr * kcols; e += TD_THREADS) {
-        const int i = e / kcols, k = e % kcols;
-        Vg[i * nb + k] = (i >= jend && i < N) ? Vp[i * nb + k] : 0.0;
-        Wg[i * nb + k] = (i >= jend && i < N) ? Wp[i * nb + k] : 0.0;
-      }
+      // (the update reads rows from jend rounded down to 16 on; sixteen lanes per row, no index divisions)
+      for (int k = tid & 15; k < kcols; k += 16)
+        for (int i = (jend & ~15) + (tid >> 4); i < Nr; i += TD_THREADS / 16) {
+          Vg[i * nb + k] = (i >= jend && i < N) ? Vp[i * nb + k] : 0.0;
+          Wg[i * nb + k] = (i >= jend && i < N) ? Wp[i * nb + k] : 0.0;
+        }
     }
   }
   if (fused && tid == 0) {
